@@ -1,0 +1,167 @@
+"""fp64 CPU oracle for the factorized-linear hot path -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
+may import this package.  It never imports the HIP package and shares nothing with it.
+
+The arithmetic lives in ``lowrank_oracle.c`` (plain C loops in binary64, following the
+paper's Section 3.1); this module compiles it with gcc on first use and marshals numpy
+float64 arrays through ctypes.  Every function takes and returns float64; callers widen
+the bf16 / fp32 inputs the GPU sees exactly to float64 before calling.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lowrank_oracle.c")
+_LIB = os.path.join(_HERE, "liblr_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle (gcc, -O2, OpenMP, no FP contraction).  Returns the .so path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call([
+            "gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared", "-std=c11",
+            "-Wall", "-Wextra", _SRC, "-o", _LIB, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+_i64 = ctypes.c_int64
+
+
+def num_threads() -> int:
+    """Threads the OpenMP row loop uses (reported as ``cores`` by the benchmark)."""
+    return int(_load().lr_oracle_num_threads())
+
+
+def linear(x, U, V, bias=None) -> np.ndarray:
+    """y = (x U) V (+ bias): the factor-pair linear layer of Section 3.1."""
+    x, U, V = _f64(x), _f64(U), _f64(V)
+    M, d_in = x.shape
+    r, d_out = V.shape
+    assert U.shape == (d_in, r), (U.shape, d_in, r)
+    b = None if bias is None else _f64(bias)
+    assert b is None or b.shape == (d_out,)
+    y = np.empty((M, d_out), dtype=np.float64)
+    rc = _load().lr_oracle_linear(_p(x), _p(U), _p(V), _p(b), _p(y),
+                                  _i64(M), _i64(d_in), _i64(r), _i64(d_out))
+    assert rc == 0, rc
+    return y
+
+
+def stage1(x, U) -> np.ndarray:
+    """t = x U, the rank-space intermediate."""
+    x, U = _f64(x), _f64(U)
+    M, d_in = x.shape
+    assert U.shape[0] == d_in
+    r = U.shape[1]
+    t = np.empty((M, r), dtype=np.float64)
+    _load().lr_oracle_stage1(_p(x), _p(U), _p(t), _i64(M), _i64(d_in), _i64(r))
+    return t
+
+
+def stage2(t, V, bias=None) -> np.ndarray:
+    """y = t V (+ bias)."""
+    t, V = _f64(t), _f64(V)
+    M, r = t.shape
+    assert V.shape[0] == r
+    d_out = V.shape[1]
+    b = None if bias is None else _f64(bias)
+    y = np.empty((M, d_out), dtype=np.float64)
+    _load().lr_oracle_stage2(_p(t), _p(V), _p(b), _p(y), _i64(M), _i64(r), _i64(d_out))
+    return y
+
+
+def cache_write(proj, cache: np.ndarray, pos, T: int) -> None:
+    """Scatter rows of ``proj`` [B*T, H*E] into the dense cache [B, S_max, H, E] in place
+    at positions pos[b] .. pos[b]+T-1 (Section 3.1, dense KV cache)."""
+    proj = _f64(proj)
+    assert cache.dtype == np.float64 and cache.flags.c_contiguous and cache.ndim == 4
+    B, S_max, H, E = cache.shape
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    assert pos.shape == (B,) and proj.shape == (B * T, H * E)
+    rc = _load().lr_oracle_cache_write(_p(proj), _p(cache), _p(pos), _i64(B), _i64(T),
+                                       _i64(S_max), _i64(H), _i64(E))
+    if rc != 0:
+        raise ValueError("cache position out of range")
+
+
+def qkv(x, Us: Sequence, Vs: Sequence, biases: Optional[Sequence] = None, kv: Optional[dict] = None):
+    """Several projections of the same x (Q, K, V; or the layers that share one basis).
+
+    Projections whose U is the *same object* share one stage-1 product t = x U (the
+    shared basis is used once, Section 3.1).  ``kv`` (optional) is a dict with float64
+    arrays ``k_cache``/``v_cache`` [B, S_max, H, E], int ``pos`` [B], ``T`` tokens per
+    sequence and ``k_index``/``v_index`` naming which projections are K and V; those
+    outputs are also scattered into the caches in place.  Returns the list of outputs.
+    """
+    n = len(Us)
+    assert len(Vs) == n
+    outs = []
+    t_by_basis = {}
+    for i in range(n):
+        key = id(Us[i])
+        if key not in t_by_basis:
+            t_by_basis[key] = stage1(x, Us[i])
+        b = None if biases is None else biases[i]
+        outs.append(stage2(t_by_basis[key], Vs[i], b))
+    if kv is not None:
+        cache_write(outs[kv["k_index"]], kv["k_cache"], kv["pos"], kv["T"])
+        cache_write(outs[kv["v_index"]], kv["v_cache"], kv["pos"], kv["T"])
+    return outs
+
+
+def packed_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g=None, b_u=None, b_d=None) -> np.ndarray:
+    """out = down(SiLU(gate(x)) * up(x)) with the packed gate|up input factor (Section 3.1)."""
+    x, U_gu, V_g, V_u, U_d, V_d = map(_f64, (x, U_gu, V_g, V_u, U_d, V_d))
+    M, d = x.shape
+    r_g, ffn = V_g.shape
+    r_u = V_u.shape[0]
+    r_d = U_d.shape[1]
+    assert U_gu.shape == (d, r_g + r_u) and V_u.shape == (r_u, ffn)
+    assert U_d.shape == (ffn, r_d) and V_d.shape == (r_d, d)
+    bg = None if b_g is None else _f64(b_g)
+    bu = None if b_u is None else _f64(b_u)
+    bd = None if b_d is None else _f64(b_d)
+    out = np.empty((M, d), dtype=np.float64)
+    rc = _load().lr_oracle_packed_mlp(_p(x), _p(U_gu), _p(V_g), _p(V_u), _p(U_d), _p(V_d),
+                                      _p(bg), _p(bu), _p(bd), _p(out),
+                                      _i64(M), _i64(d), _i64(ffn), _i64(r_g), _i64(r_u), _i64(r_d))
+    assert rc == 0, rc
+    return out
+
+
+def pack_concat(U_list: Sequence[np.ndarray]) -> np.ndarray:
+    """Offline prepack: [U_0 | U_1 | ...] along the rank axis, bit-exact for any dtype."""
+    Us = [np.ascontiguousarray(u) for u in U_list]
+    d_in = Us[0].shape[0]
+    dt = Us[0].dtype
+    assert all(u.shape[0] == d_in and u.dtype == dt and u.ndim == 2 for u in Us)
+    n = len(Us)
+    ptrs = (ctypes.c_void_p * n)(*[u.ctypes.data for u in Us])
+    rs = (ctypes.c_int64 * n)(*[u.shape[1] for u in Us])
+    packed = np.empty((d_in, sum(u.shape[1] for u in Us)), dtype=dt)
+    _load().lr_oracle_pack_concat(ptrs, rs, ctypes.c_int(n), _i64(d_in), _i64(dt.itemsize), _p(packed))
+    return packed
