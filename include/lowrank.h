@@ -1,0 +1,167 @@
+/*
+ * lowrank.h -- C ABI of liblowrank.so: the factorized linear layer y = (x U) V of an
+ * SVD-compressed transformer on one AMD MI355X (gfx950), in a decode form (1..32 token
+ * rows, bound by streaming the factors from HBM) and a prefill form (hundreds to thousands
+ * of rows, bound by bf16 MFMA throughput).
+ *
+ * The operations are those of the paper's Section 3.1 ("FlashSVD v1.5 Design"):
+ *   - every compressed linear layer is a pair of factors ("common native factorized
+ *     representation", first paragraph);
+ *   - attention reconstructs dense q/k/v for the current tokens only and stores K and V in a
+ *     standard dense cache (second paragraph);
+ *   - the MLP packs the gate and up input-side factors into one operand, runs one wide
+ *     projection, splits the rank activations, and leaves output-side reconstruction and the
+ *     down projection unchanged (third paragraph, Figure 3);
+ *   - a basis shared by grouped layers stays physically shared and is used once (first
+ *     paragraph);
+ *   - prefill and decode run phase-specific kernels (abstract, Section 3).
+ *
+ * Conventions common to every entry point
+ *   Layout     All matrices are row-major and contiguous: x[M, d_in], U[d_in, r], V[r, d_out],
+ *              bias[d_out], y[M, d_out].  W ~ U V is [d_in, d_out] (row-vector convention).
+ *   dtype      One element type per call (lr_dtype) for x, U, V, bias, outputs and caches.
+ *              Accumulation is fp32 or wider; the output is rounded once (nearest-even).
+ *   Pointers   Device pointers unless marked "host".  Inputs are never written.  Outputs must
+ *              not alias inputs.  The caller owns every buffer; the library allocates and frees
+ *              no device memory, never synchronises the stream and never changes the current
+ *              device.  All work is enqueued on `stream` (a hipStream_t, NULL = default stream).
+ *   Workspace  Caller-provided device scratch of at least lowrank_workspace_bytes(...) bytes,
+ *              256-byte aligned.  It must be prepared ONCE after allocation with
+ *              lowrank_workspace_init (or by zero-filling it) and is left prepared by every
+ *              successful call.  Two calls that share a workspace must be ordered on one stream;
+ *              calls overlapping in time on one workspace race.
+ *   Errors     Return value is an lr_status: 0 on success, negative on error.  On a validation
+ *              error nothing is launched.  lowrank_last_error() gives a thread-local message.
+ *              No C++ exception crosses this boundary.
+ *   Sizes      Any M, d_in, r, d_out >= 0 is legal.  M == 0 is a no-op.  r == 0 gives
+ *              y = bias (or zeros).  The fast kernels need bf16, 16-byte aligned pointers and
+ *              dimensions that are multiples of 64; anything else takes a slower generic kernel
+ *              with the same results to rounding.
+ */
+#ifndef LOWRANK_H
+#define LOWRANK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LR_F32 = 0, LR_BF16 = 1 } lr_dtype;
+
+/* Phase of serving (paper: "phase-specific kernels").  AUTO picks DECODE when M <= 32. */
+typedef enum { LR_PHASE_DECODE = 0, LR_PHASE_PREFILL = 1, LR_PHASE_AUTO = 2 } lr_phase;
+
+typedef enum {
+    LR_OK = 0,
+    LR_ERR_NULL = -1,        /* a required pointer is NULL */
+    LR_ERR_SHAPE = -2,       /* negative or inconsistent sizes */
+    LR_ERR_DTYPE = -3,       /* unknown lr_dtype */
+    LR_ERR_ALIGN = -4,       /* workspace not 256-byte aligned */
+    LR_ERR_PHASE = -5,       /* unknown lr_phase */
+    LR_ERR_WORKSPACE = -6,   /* workspace missing or too small */
+    LR_ERR_LAUNCH = -7,      /* the HIP runtime refused a launch (message has the HIP error) */
+    LR_ERR_UNSUPPORTED = -8  /* combination not available */
+} lr_status;
+
+typedef enum { LR_OP_LINEAR = 0, LR_OP_QKV = 1, LR_OP_PACKED_MLP = 2 } lr_op;
+
+/*
+ * One factorized linear layer (Section 3.1, first paragraph):
+ *     y[M, d_out] = (x[M, d_in] * U[d_in, r]) * V[r, d_out]  (+ bias[d_out] if bias != NULL)
+ */
+int lowrank_linear(const void *x, const void *U, const void *V, const void *bias /* nullable */,
+                   void *y, int64_t M, int64_t d_in, int64_t r, int64_t d_out,
+                   int dtype /* lr_dtype */, int phase /* lr_phase */,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Where the K and V projections of lowrank_qkv are written besides `out` (Section 3.1,
+ * second paragraph: a standard dense KV cache; layout [batch, position, head, head_dim]).
+ * The M rows of x are B sequences of tokens_per_seq consecutive tokens (M = B * tokens_per_seq).
+ * Row b*tokens_per_seq + s of projection k_index goes to
+ *     k_cache[b, pos[b] + s, h, e]   for column c = h * head_dim + e,
+ * likewise v_index -> v_cache.  d_out of both projections must equal n_heads * head_dim.
+ * pos is a DEVICE array of B int32; the caller guarantees 0 <= pos[b] and
+ * pos[b] + tokens_per_seq <= S_max (rows that would fall outside are skipped, never written
+ * out of bounds).  This struct itself lives in HOST memory.
+ */
+typedef struct {
+    void *k_cache;             /* device, [B, S_max, n_heads, head_dim], element type = dtype */
+    void *v_cache;             /* device, same shape */
+    const int32_t *pos;        /* device, int32[B] */
+    int64_t B, S_max, n_heads, head_dim, tokens_per_seq;
+    int32_t k_index, v_index;  /* which projection is K, which is V (0-based) */
+} lr_kv_target;
+
+/*
+ * n_proj (1..8) factorized projections of the same x (Q, K, V of one attention block; or the
+ * layers that share one basis):
+ *     out[i][M, d_out[i]] = (x * U[i]) * V[i] (+ bias[i])
+ * U, V, bias, out, r, d_out are HOST arrays of n_proj entries; U[i], V[i], out[i] are device
+ * pointers.  bias may be NULL (no projection has a bias) or hold NULL entries.  out[i] may be
+ * NULL when projection i is wanted only in the cache.  If U[i] == U[j] (same pointer, hence
+ * r[i] == r[j]) the product x * U[i] is formed once and reused: the shared-basis form.
+ * kv may be NULL.
+ */
+int lowrank_qkv(const void *x, const void *const *U, const void *const *V,
+                const void *const *bias /* nullable */, void *const *out,
+                const int64_t *r, const int64_t *d_out, int n_proj,
+                int64_t M, int64_t d_in, const lr_kv_target *kv /* nullable */,
+                int dtype, int phase, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Packed MLP (Section 3.1, third paragraph).  U_gu[d, r_g + r_u] is the offline-packed
+ * operand [U_gate | U_up], gate columns first:
+ *     t    = x[M, d] * U_gu
+ *     g    = t[:, :r_g] * V_g[r_g, ffn] + b_g         u = t[:, r_g:] * V_u[r_u, ffn] + b_u
+ *     h    = SiLU(g) .* u,   SiLU(z) = z / (1 + exp(-z))
+ *     out[M, d] = (h * U_d[ffn, r_d]) * V_d[r_d, d] + b_d
+ * b_g, b_u (ffn entries) and b_d (d entries) are nullable.  g, u and h never reach `out`'s
+ * caller; h may be staged in the workspace.
+ */
+int lowrank_packed_mlp(const void *x, const void *U_gu, const void *V_g, const void *V_u,
+                       const void *U_d, const void *V_d,
+                       const void *b_g, const void *b_u, const void *b_d,
+                       void *out, int64_t M, int64_t d, int64_t ffn,
+                       int64_t r_g, int64_t r_u, int64_t r_d,
+                       int dtype, int phase, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Offline prepack (Section 3.1, third paragraph; Figure 3): concatenate n (1..8) factors
+ * U_list[i][d_in, r_list[i]] along the rank axis into U_packed[d_in, sum r_list].  U_list and
+ * r_list are HOST arrays; the matrices are device memory.  Pure data movement: bit-exact.
+ */
+int lowrank_pack_concat(const void *const *U_list, const int64_t *r_list, int n, int64_t d_in,
+                        int dtype, void *U_packed, void *stream);
+
+/*
+ * Workspace size in bytes (pure host function, no GPU needed).  Meaning of the size arguments:
+ *   LR_OP_LINEAR      d_in, r_total = r,                 d_out
+ *   LR_OP_QKV         d_in, r_total = sum of r[i],       d_out = sum of d_out[i]
+ *   LR_OP_PACKED_MLP  d_in = d, r_total = r_g + r_u + r_d, d_out = ffn
+ * Returns 0 for invalid arguments.  The value is an upper bound over both phases when phase is
+ * LR_PHASE_AUTO.
+ */
+size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
+                               int dtype, int phase);
+
+/* Prepare a freshly allocated workspace (enqueues a fill on `stream`).  Equivalent to zero-filling it. */
+int lowrank_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Name of the kernel family the dispatcher picks for a call of this shape, e.g.
+ * "decode_mfma", "prefill_mfma", "generic" (pure host function; static storage).
+ * `aligned` is nonzero when every pointer of the call is 16-byte aligned.
+ */
+const char *lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
+                              int dtype, int phase, int aligned);
+
+const char *lowrank_last_error(void);   /* thread-local, static storage, never NULL */
+const char *lowrank_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOWRANK_H */

@@ -1,0 +1,205 @@
+// C-ABI entry points of liblowrank.so: argument validation, plan selection (host integer
+// logic only) and launches.  See include/lowrank.h for the contract of every function.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include "lr_common.hpp"
+
+namespace lr {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int launch_status(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return LR_OK;
+    set_error("%s: HIP launch failed: %s", what, hipGetErrorString(e));
+    return LR_ERR_LAUNCH;
+}
+
+static inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+static int check_common(int dtype, int phase, int64_t M, void* ws, size_t ws_bytes, size_t need) {
+    if (dtype != LR_F32 && dtype != LR_BF16) { set_error("unknown dtype %d", dtype); return LR_ERR_DTYPE; }
+    if (phase != LR_PHASE_DECODE && phase != LR_PHASE_PREFILL && phase != LR_PHASE_AUTO) {
+        set_error("unknown phase %d", phase); return LR_ERR_PHASE; }
+    if (M > 0) {
+        if (!ws) { set_error("workspace is NULL"); return LR_ERR_WORKSPACE; }
+        if (((uintptr_t)ws) & 255u) { set_error("workspace must be 256-byte aligned"); return LR_ERR_ALIGN; }
+        if (ws_bytes < need) { set_error("workspace too small: %zu bytes given, %zu needed", ws_bytes, need); return LR_ERR_WORKSPACE; }
+    }
+    return LR_OK;
+}
+
+static inline int resolve_phase(int phase, int64_t M) {
+    if (phase == LR_PHASE_AUTO) return M <= 32 ? LR_PHASE_DECODE : LR_PHASE_PREFILL;
+    return phase;
+}
+
+static size_t ws_bytes_for(int op, int64_t M, int64_t r_total, int64_t d_out) {
+    // header + two fp32 rank-space areas (the second one lets a fused kernel clear the area of
+    // the next call while it uses the current one) + for the MLP two fp32 [M, ffn] areas.
+    size_t n = kHeaderBytes + 2 * align256((size_t)M * (size_t)r_total * 4);
+    if (op == LR_OP_PACKED_MLP) n += 2 * align256((size_t)M * (size_t)d_out * 4);
+    return n;
+}
+
+}  // namespace lr
+
+using namespace lr;
+
+extern "C" {
+
+const char* lowrank_last_error(void) { return g_err; }
+const char* lowrank_version(void) { return "lowrank-mi355x 0.1 (gfx950)"; }
+
+size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
+                               int dtype, int phase) {
+    if (op < LR_OP_LINEAR || op > LR_OP_PACKED_MLP) return 0;
+    if (M < 0 || d_in < 0 || r_total < 0 || d_out < 0) return 0;
+    if (dtype != LR_F32 && dtype != LR_BF16) return 0;
+    if (phase < LR_PHASE_DECODE || phase > LR_PHASE_AUTO) return 0;
+    return ws_bytes_for(op, M, r_total, d_out);
+}
+
+int lowrank_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    if (!workspace) { set_error("workspace is NULL"); return LR_ERR_NULL; }
+    if (((uintptr_t)workspace) & 255u) { set_error("workspace must be 256-byte aligned"); return LR_ERR_ALIGN; }
+    return fill_zero(workspace, workspace_bytes & ~(size_t)3, (hipStream_t)stream);
+}
+
+const char* lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
+                              int dtype, int phase, int aligned) {
+    (void)op; (void)M; (void)d_in; (void)r_total; (void)d_out; (void)dtype; (void)phase; (void)aligned;
+    return "generic";
+}
+
+int lowrank_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
+                   int64_t M, int64_t d_in, int64_t r, int64_t d_out, int dtype, int phase,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || d_in < 0 || r < 0 || d_out < 0) { set_error("negative size"); return LR_ERR_SHAPE; }
+    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_LINEAR, M, r, d_out));
+    if (st != LR_OK) return st;
+    if (M == 0 || d_out == 0) return LR_OK;
+    if (!y || (d_in > 0 && !x) || (r > 0 && d_in > 0 && !U) || (r > 0 && !V)) { set_error("NULL operand"); return LR_ERR_NULL; }
+    hipStream_t s = (hipStream_t)stream;
+    float* t = (float*)((char*)workspace + kHeaderBytes);
+    CacheDst none = {nullptr, nullptr, 0, 1};
+    st = generic_stage1(x, false, U, t, r, M, d_in, r, dtype, s);
+    if (st != LR_OK) return st;
+    return generic_stage2(t, r, V, bias, y, M, r, d_out, none, dtype, s);
+}
+
+int lowrank_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
+                void* const* out, const int64_t* r, const int64_t* d_out, int n_proj,
+                int64_t M, int64_t d_in, const lr_kv_target* kv, int dtype, int phase,
+                void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_proj < 1 || n_proj > 8) { set_error("n_proj must be 1..8"); return LR_ERR_SHAPE; }
+    if (!U || !V || !out || !r || !d_out) { set_error("NULL host array"); return LR_ERR_NULL; }
+    if (M < 0 || d_in < 0) { set_error("negative size"); return LR_ERR_SHAPE; }
+    int64_t r_sum = 0, n_sum = 0;
+    for (int i = 0; i < n_proj; ++i) {
+        if (r[i] < 0 || d_out[i] < 0) { set_error("negative size in projection %d", i); return LR_ERR_SHAPE; }
+        r_sum += r[i]; n_sum += d_out[i];
+    }
+    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_QKV, M, r_sum, n_sum));
+    if (st != LR_OK) return st;
+    // shared bases: projection i reuses the stage-1 product of the first j < i with U[j] == U[i]
+    int base_of[8]; int64_t t_off[8]; int64_t R = 0;
+    for (int i = 0; i < n_proj; ++i) {
+        base_of[i] = i;
+        for (int j = 0; j < i; ++j)
+            if (U[j] == U[i] && U[i] != nullptr) {
+                if (r[j] != r[i]) { set_error("projections %d and %d share U but differ in rank", j, i); return LR_ERR_SHAPE; }
+                base_of[i] = j; break;
+            }
+        if (base_of[i] == i) { t_off[i] = R; R += r[i]; } else t_off[i] = t_off[base_of[i]];
+    }
+    if (kv) {
+        if (kv->k_index < 0 || kv->k_index >= n_proj || kv->v_index < 0 || kv->v_index >= n_proj) {
+            set_error("k_index / v_index out of range"); return LR_ERR_SHAPE; }
+        if (kv->B < 0 || kv->tokens_per_seq < 1 || kv->B * kv->tokens_per_seq != M) {
+            set_error("kv: B * tokens_per_seq must equal M"); return LR_ERR_SHAPE; }
+        if (kv->S_max < kv->tokens_per_seq || kv->n_heads < 1 || kv->head_dim < 1) {
+            set_error("kv: bad cache shape"); return LR_ERR_SHAPE; }
+        const int64_t w = kv->n_heads * kv->head_dim;
+        if (d_out[kv->k_index] != w || d_out[kv->v_index] != w) {
+            set_error("kv: d_out of K and V must equal n_heads * head_dim"); return LR_ERR_SHAPE; }
+        if (M > 0 && (!kv->pos || !kv->k_cache || !kv->v_cache)) { set_error("kv: NULL cache or pos"); return LR_ERR_NULL; }
+    }
+    if (M == 0) return LR_OK;
+    for (int i = 0; i < n_proj; ++i) {
+        const bool to_cache = kv && (i == kv->k_index || i == kv->v_index);
+        if (d_out[i] == 0) continue;
+        if (!out[i] && !to_cache) { set_error("projection %d has no destination", i); return LR_ERR_NULL; }
+        if ((r[i] > 0 && d_in > 0 && !U[i]) || (r[i] > 0 && !V[i])) { set_error("NULL factor in projection %d", i); return LR_ERR_NULL; }
+    }
+    if (d_in > 0 && !x) { set_error("x is NULL"); return LR_ERR_NULL; }
+    hipStream_t s = (hipStream_t)stream;
+    float* t = (float*)((char*)workspace + kHeaderBytes);
+    const int64_t ldt = R > 0 ? R : 1;
+    for (int i = 0; i < n_proj; ++i)
+        if (base_of[i] == i) {
+            st = generic_stage1(x, false, U[i], t + t_off[i], ldt, M, d_in, r[i], dtype, s);
+            if (st != LR_OK) return st;
+        }
+    for (int i = 0; i < n_proj; ++i) {
+        CacheDst cd = {nullptr, nullptr, 0, 1};
+        if (kv && i == kv->k_index) cd = {kv->k_cache, kv->pos, kv->S_max, kv->tokens_per_seq};
+        if (kv && i == kv->v_index) cd = {kv->v_cache, kv->pos, kv->S_max, kv->tokens_per_seq};
+        st = generic_stage2(t + t_off[i], ldt, V[i], bias ? bias[i] : nullptr, out[i], M, r[i], d_out[i], cd, dtype, s);
+        if (st != LR_OK) return st;
+    }
+    return LR_OK;
+}
+
+int lowrank_packed_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u,
+                       const void* U_d, const void* V_d, const void* b_g, const void* b_u, const void* b_d,
+                       void* out, int64_t M, int64_t d, int64_t ffn, int64_t r_g, int64_t r_u, int64_t r_d,
+                       int dtype, int phase, void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || d < 0 || ffn < 0 || r_g < 0 || r_u < 0 || r_d < 0) { set_error("negative size"); return LR_ERR_SHAPE; }
+    const int64_t r_total = r_g + r_u + r_d;
+    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_PACKED_MLP, M, r_total, ffn));
+    if (st != LR_OK) return st;
+    if (M == 0 || d == 0) return LR_OK;
+    if (!x || !out) { set_error("NULL operand"); return LR_ERR_NULL; }
+    if ((r_g + r_u > 0 && !U_gu) || (r_g > 0 && ffn > 0 && !V_g) || (r_u > 0 && ffn > 0 && !V_u) ||
+        (r_d > 0 && ffn > 0 && !U_d) || (r_d > 0 && !V_d)) { set_error("NULL factor"); return LR_ERR_NULL; }
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)workspace + kHeaderBytes;
+    float* t = (float*)base;                                   // [M, r_g + r_u + r_d]
+    float* h = (float*)(base + 2 * align256((size_t)M * (size_t)r_total * 4));   // [M, ffn]
+    const int64_t ldt = r_total > 0 ? r_total : 1;
+    CacheDst none = {nullptr, nullptr, 0, 1};
+    st = generic_stage1(x, false, U_gu, t, ldt, M, d, r_g + r_u, dtype, s);
+    if (st != LR_OK) return st;
+    st = generic_gateup(t, ldt, V_g, V_u, b_g, b_u, h, M, r_g, r_u, ffn, dtype, s);
+    if (st != LR_OK) return st;
+    st = generic_stage1(h, true, U_d, t + (r_g + r_u), ldt, M, ffn, r_d, dtype, s);
+    if (st != LR_OK) return st;
+    return generic_stage2(t + (r_g + r_u), ldt, V_d, b_d, out, M, r_d, d, none, dtype, s);
+}
+
+int lowrank_pack_concat(const void* const* U_list, const int64_t* r_list, int n, int64_t d_in,
+                        int dtype, void* U_packed, void* stream) {
+    if (n < 1 || n > 8) { set_error("n must be 1..8"); return LR_ERR_SHAPE; }
+    if (!U_list || !r_list) { set_error("NULL host array"); return LR_ERR_NULL; }
+    if (dtype != LR_F32 && dtype != LR_BF16) { set_error("unknown dtype %d", dtype); return LR_ERR_DTYPE; }
+    if (d_in < 0) { set_error("negative size"); return LR_ERR_SHAPE; }
+    int64_t R = 0;
+    for (int i = 0; i < n; ++i) {
+        if (r_list[i] < 0) { set_error("negative rank"); return LR_ERR_SHAPE; }
+        if (r_list[i] > 0 && d_in > 0 && !U_list[i]) { set_error("NULL factor %d", i); return LR_ERR_NULL; }
+        R += r_list[i];
+    }
+    if (R * d_in > 0 && !U_packed) { set_error("U_packed is NULL"); return LR_ERR_NULL; }
+    return generic_pack_concat(U_list, r_list, n, d_in, dtype == LR_F32 ? 4 : 2, U_packed, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function the header declares,
+and its host-side logic (workspace sizing, argument validation, plan names) behaves.  No kernel
+is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lowrank.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_08314_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lowrank_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = declared_functions()
+    assert {"lowrank_linear", "lowrank_qkv", "lowrank_packed_mlp"} <= set(names)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in lowrank.h but not exported"
+    assert "gfx950" in B.lowrank_version()
+
+
+def test_workspace_bytes_host_function(B):
+    assert B.lowrank_workspace_bytes(B.LR_OP_LINEAR, 0, 4096, 384, 4096, B.LR_BF16, "decode") >= 4096
+    a = B.lowrank_workspace_bytes(B.LR_OP_LINEAR, 32, 4096, 384, 4096, B.LR_BF16, "decode")
+    b = B.lowrank_workspace_bytes(B.LR_OP_LINEAR, 64, 4096, 384, 4096, B.LR_BF16, "decode")
+    assert b > a >= 4096 + 32 * 384 * 4
+    m = B.lowrank_workspace_bytes(B.LR_OP_PACKED_MLP, 32, 4096, 2304, 11008, B.LR_BF16, "decode")
+    assert m >= 32 * (2304 + 11008) * 4
+    assert B.lowrank_workspace_bytes(9, 1, 1, 1, 1, B.LR_BF16, "decode") == 0
+    assert B.lowrank_workspace_bytes(B.LR_OP_QKV, -1, 1, 1, 1, B.LR_BF16, "decode") == 0
+    assert B.lowrank_workspace_bytes(B.LR_OP_QKV, 1, 1, 1, 1, 5, "decode") == 0
+
+
+def test_validation_errors_without_launch(B):
+    lib = ctypes.CDLL(B.LIB_PATH)
+    lib.lowrank_linear.argtypes = B._lib.lowrank_linear.argtypes
+    lib.lowrank_last_error.restype = ctypes.c_char_p
+    fake = 0x1000  # never dereferenced: every call below fails validation first
+    call = lambda **kw: lib.lowrank_linear(kw.get("x", fake), fake, fake, None, kw.get("y", fake),
+                                           kw.get("M", 4), 64, 8, 64, kw.get("dtype", 1), kw.get("phase", 0),
+                                           kw.get("ws", 0x10000), kw.get("wsb", 1 << 20), None)
+    assert call(M=-1) == -2
+    assert call(dtype=3) == -3
+    assert call(phase=9) == -5
+    assert call(ws=None) == -6
+    assert call(ws=0x10010) == -4
+    assert call(wsb=16) == -6 and b"workspace" in lib.lowrank_last_error()
+    assert call(y=None) == -1
+    assert call(M=0, ws=None) == 0          # empty batch: legal no-op, needs no workspace
+
+
+def test_plan_names(B):
+    for args in [(B.LR_OP_LINEAR, 1, 4096, 384, 4096), (B.LR_OP_PACKED_MLP, 8192, 4096, 2304, 11008),
+                 (B.LR_OP_QKV, 3, 37, 5, 19)]:
+        for phase in ("decode", "prefill", "auto"):
+            assert B.lowrank_plan_name(*args, B.LR_BF16, phase) in {"generic", "decode_mfma", "prefill_mfma"}
+    # ragged shapes, fp32 and unaligned pointers always take the generic kernels
+    assert B.lowrank_plan_name(B.LR_OP_QKV, 3, 37, 5, 19, B.LR_BF16, "decode") == "generic"
+    assert B.lowrank_plan_name(B.LR_OP_LINEAR, 16, 512, 128, 512, B.LR_F32, "decode") == "generic"
+    assert B.lowrank_plan_name(B.LR_OP_LINEAR, 16, 4096, 384, 4096, B.LR_BF16, "decode", aligned=False) == "generic"
