@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 #include "lr_common.hpp"
+#include "decode.hpp"
 
 namespace lr {
 
@@ -42,6 +43,21 @@ static inline int resolve_phase(int phase, int64_t M) {
     return phase;
 }
 
+enum Plan { PLAN_GENERIC = 0, PLAN_DECODE = 1, PLAN_PREFILL = 2 };
+static const char* const kPlanNames[] = {"generic", "decode_mfma", "prefill_mfma"};
+
+bool prefill_shape_ok(int64_t M, int64_t K, int64_t N) { (void)M; (void)K; (void)N; return false; }
+
+// The tuned kernels are bf16-only and need 16-byte aligned operands; decode additionally needs
+// M <= 32.  A DECODE request with more rows, or a PREFILL request, goes to the prefill kernels
+// when the shape allows, else to the generic ones.
+static Plan pick_plan(int dtype, int phase, int64_t M, bool decode_ok, bool prefill_ok, bool aligned) {
+    if (dtype != LR_BF16 || !aligned) return PLAN_GENERIC;
+    if (resolve_phase(phase, M) == LR_PHASE_DECODE && decode_ok) return PLAN_DECODE;
+    if (prefill_ok) return PLAN_PREFILL;
+    return PLAN_GENERIC;
+}
+
 static size_t ws_bytes_for(int op, int64_t M, int64_t r_total, int64_t d_out) {
     // header + two fp32 rank-space areas (the second one lets a fused kernel clear the area of
     // the next call while it uses the current one) + for the MLP two fp32 [M, ffn] areas.
@@ -76,8 +92,19 @@ int lowrank_workspace_init(void* workspace, size_t workspace_bytes, void* stream
 
 const char* lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
                               int dtype, int phase, int aligned) {
-    (void)op; (void)M; (void)d_in; (void)r_total; (void)d_out; (void)dtype; (void)phase; (void)aligned;
-    return "generic";
+    if (phase < LR_PHASE_DECODE || phase > LR_PHASE_AUTO || M < 1) return kPlanNames[PLAN_GENERIC];
+    bool dec, pre;
+    if (op == LR_OP_PACKED_MLP) {   // every rank taken as r_total / 3
+        const int64_t r = r_total / 3;
+        dec = (r_total % 3 == 0) && decode_shape_ok(M, d_in, 2 * r) && decode_shape_ok(M, r, d_out) &&
+              decode_shape_ok(M, d_out, r) && decode_shape_ok(M, r, d_in);
+        pre = (r_total % 3 == 0) && prefill_shape_ok(M, d_in, 2 * r) && prefill_shape_ok(M, r, d_out) &&
+              prefill_shape_ok(M, d_out, r) && prefill_shape_ok(M, r, d_in);
+    } else {                        // QKV: the sums stand for projections that each satisfy the rule
+        dec = decode_shape_ok(M, d_in, r_total) && decode_shape_ok(M, r_total, d_out);
+        pre = prefill_shape_ok(M, d_in, r_total) && prefill_shape_ok(M, r_total, d_out);
+    }
+    return kPlanNames[pick_plan(dtype, phase, M, dec, pre, aligned != 0)];
 }
 
 int lowrank_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
@@ -89,6 +116,10 @@ int lowrank_linear(const void* x, const void* U, const void* V, const void* bias
     if (M == 0 || d_out == 0) return LR_OK;
     if (!y || (d_in > 0 && !x) || (r > 0 && d_in > 0 && !U) || (r > 0 && !V)) { set_error("NULL operand"); return LR_ERR_NULL; }
     hipStream_t s = (hipStream_t)stream;
+    const bool al = aligned16(x) && aligned16(U) && aligned16(V) && aligned16(y) && aligned16(bias);
+    const Plan plan = pick_plan(dtype, phase, M, decode_shape_ok(M, d_in, r) && decode_shape_ok(M, r, d_out),
+                                prefill_shape_ok(M, d_in, r) && prefill_shape_ok(M, r, d_out), al);
+    if (plan == PLAN_DECODE) return decode_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, s);
     float* t = (float*)((char*)workspace + kHeaderBytes);
     CacheDst none = {nullptr, nullptr, 0, 1};
     st = generic_stage1(x, false, U, t, r, M, d_in, r, dtype, s);
@@ -142,6 +173,16 @@ int lowrank_qkv(const void* x, const void* const* U, const void* const* V, const
     }
     if (d_in > 0 && !x) { set_error("x is NULL"); return LR_ERR_NULL; }
     hipStream_t s = (hipStream_t)stream;
+    bool al = aligned16(x), dec = true, pre = true;
+    for (int i = 0; i < n_proj; ++i) {
+        al = al && aligned16(U[i]) && aligned16(V[i]) && aligned16(out[i]) && aligned16(bias ? bias[i] : nullptr);
+        dec = dec && decode_shape_ok(M, d_in, r[i]) && decode_shape_ok(M, r[i], d_out[i]);
+        pre = pre && prefill_shape_ok(M, d_in, r[i]) && prefill_shape_ok(M, r[i], d_out[i]);
+    }
+    if (kv) al = al && aligned16(kv->k_cache) && aligned16(kv->v_cache);
+    const Plan plan = pick_plan(dtype, phase, M, dec, pre, al);
+    if (plan == PLAN_DECODE)
+        return decode_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, s);
     float* t = (float*)((char*)workspace + kHeaderBytes);
     const int64_t ldt = R > 0 ? R : 1;
     for (int i = 0; i < n_proj; ++i)
@@ -172,6 +213,15 @@ int lowrank_packed_mlp(const void* x, const void* U_gu, const void* V_g, const v
     if ((r_g + r_u > 0 && !U_gu) || (r_g > 0 && ffn > 0 && !V_g) || (r_u > 0 && ffn > 0 && !V_u) ||
         (r_d > 0 && ffn > 0 && !U_d) || (r_d > 0 && !V_d)) { set_error("NULL factor"); return LR_ERR_NULL; }
     hipStream_t s = (hipStream_t)stream;
+    const bool al = aligned16(x) && aligned16(U_gu) && aligned16(V_g) && aligned16(V_u) && aligned16(U_d) &&
+                    aligned16(V_d) && aligned16(b_g) && aligned16(b_u) && aligned16(b_d) && aligned16(out);
+    const bool dec = decode_shape_ok(M, d, r_g) && decode_shape_ok(M, d, r_u) && decode_shape_ok(M, r_g, ffn) &&
+                     decode_shape_ok(M, r_u, ffn) && decode_shape_ok(M, ffn, r_d) && decode_shape_ok(M, r_d, d);
+    const bool pre = prefill_shape_ok(M, d, r_g + r_u) && prefill_shape_ok(M, r_g, ffn) && prefill_shape_ok(M, r_u, ffn) &&
+                     prefill_shape_ok(M, ffn, r_d) && prefill_shape_ok(M, r_d, d);
+    const Plan plan = pick_plan(dtype, phase, M, dec, pre, al);
+    if (plan == PLAN_DECODE)
+        return decode_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, s);
     char* base = (char*)workspace + kHeaderBytes;
     float* t = (float*)base;                                   // [M, r_g + r_u + r_d]
     float* h = (float*)(base + 2 * align256((size_t)M * (size_t)r_total * 4));   // [M, ffn]

@@ -37,7 +37,7 @@ def run_attention(G, oracle, w, phase):
     Us = [G.dev(t["U_" + n]) for n in "qkv"]
     Vs = [G.dev(t["V_" + n]) for n in "qkv"]
     outs = [torch.full((M, d), float("nan"), dtype=G.tdtype(w.dtype), device="cuda") for _ in range(3)]
-    SENT = -7.0
+    SENT = -65536.0
     kc = torch.full((m["B"], S_max, H, E), SENT, dtype=G.tdtype(w.dtype), device="cuda")
     vc = torch.full((m["B"], S_max, H, E), SENT, dtype=G.tdtype(w.dtype), device="cuda")
     pos = G.dev(m["pos"])
@@ -93,8 +93,8 @@ def test_config4_prefill_layer(G, oracle, S, r_attn, r_mlp):
     Us = [G.dev(t["U_" + n]) for n in "qkv"]
     Vs = [G.dev(t["V_" + n]) for n in "qkv"]
     outs = [torch.full((S, d), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
-    kc = torch.full((1, S, H, E), -7.0, dtype=torch.bfloat16, device="cuda")
-    vc = torch.full((1, S, H, E), -7.0, dtype=torch.bfloat16, device="cuda")
+    kc = torch.full((1, S, H, E), -65536.0, dtype=torch.bfloat16, device="cuda")
+    vc = torch.full((1, S, H, E), -65536.0, dtype=torch.bfloat16, device="cuda")
     ws = B.new_workspace(B.LR_OP_QKV, S, d, 3 * r_attn, 3 * d, B.LR_BF16, "prefill")
     B.lowrank_qkv(x, Us, Vs, None, outs, dict(k_cache=kc, v_cache=vc, pos=G.dev(m["pos"]), tokens_per_seq=S,
                                               k_index=1, v_index=2), "prefill", ws)
