@@ -28,8 +28,9 @@
  *   Workspace  Caller-provided device scratch of at least lowrank_workspace_bytes(...) bytes,
  *              256-byte aligned.  It must be prepared ONCE after allocation with
  *              lowrank_workspace_init (or by zero-filling it) and is left prepared by every
- *              successful call.  Two calls that share a workspace must be ordered on one stream;
- *              calls overlapping in time on one workspace race.
+ *              successful call.  A workspace is always passed with the same workspace_bytes.
+ *              Two calls that share a workspace must be ordered on one stream; calls overlapping
+ *              in time on one workspace race.
  *   Errors     Return value is an lr_status: 0 on success, negative on error.  On a validation
  *              error nothing is launched.  lowrank_last_error() gives a thread-local message.
  *              No C++ exception crosses this boundary.
@@ -149,6 +150,14 @@ size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total,
 
 /* Prepare a freshly allocated workspace (enqueues a fill on `stream`).  Equivalent to zero-filling it. */
 int lowrank_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Diagnostic, the only function here that SYNCHRONISES `stream`: reads the workspace's control
+ * block back and returns LR_OK, or LR_ERR_LAUNCH if a bounded device-side wait between the stages
+ * of a fused decode call gave up (then that call's results are invalid and the workspace must be
+ * prepared again).
+ */
+int lowrank_workspace_status(const void *workspace, void *stream);
 
 /*
  * Name of the kernel family the dispatcher picks for a call of this shape, e.g.

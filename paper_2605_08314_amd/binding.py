@@ -50,6 +50,8 @@ _lib.lowrank_workspace_bytes.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _in
 _lib.lowrank_workspace_bytes.restype = _sz
 _lib.lowrank_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.lowrank_workspace_init.restype = _int
+_lib.lowrank_workspace_status.argtypes = [_vp, _vp]
+_lib.lowrank_workspace_status.restype = _int
 _lib.lowrank_plan_name.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int, _int]
 _lib.lowrank_plan_name.restype = ctypes.c_char_p
 _lib.lowrank_last_error.restype = ctypes.c_char_p
@@ -110,6 +112,11 @@ def lowrank_plan_name(op: int, M: int, d_in: int, r_total: int, d_out: int, dtyp
 
 def lowrank_workspace_init(workspace: torch.Tensor, stream=None) -> None:
     _check(_lib.lowrank_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def lowrank_workspace_status(workspace: torch.Tensor, stream=None) -> None:
+    """Synchronises the stream; raises if a fused decode call on this workspace gave up waiting."""
+    _check(_lib.lowrank_workspace_status(_ptr(workspace), _stream(stream)))
 
 
 def new_workspace(op: int, M: int, d_in: int, r_total: int, d_out: int, dtype: int, phase="auto",

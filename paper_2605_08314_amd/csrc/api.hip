@@ -59,16 +59,22 @@ static Plan pick_plan(int dtype, int phase, int64_t M, bool decode_ok, bool pref
 }
 
 static size_t ws_bytes_for(int op, int64_t M, int64_t r_total, int64_t d_out) {
-    // header + two fp32 rank-space areas (the second one lets a fused kernel clear the area of
-    // the next call while it uses the current one) + for the MLP two fp32 [M, ffn] areas.
-    size_t n = kHeaderBytes + 2 * align256((size_t)M * (size_t)r_total * 4);
-    if (op == LR_OP_PACKED_MLP) n += 2 * align256((size_t)M * (size_t)d_out * 4);
-    return n;
+    // header | accumulator area 0 | accumulator area 1 | staging (two quarters), see ws_layout().
+    // A quarter holds the fp32 rank-space rows [M, r_total]; for the MLP also fp32 [M, ffn], so
+    // that the staging half fits rank-space rows plus hidden rows in any kernel family.
+    size_t q = align256((size_t)M * (size_t)r_total * 4);
+    if (op == LR_OP_PACKED_MLP) { const size_t hq = align256((size_t)M * (size_t)d_out * 4); if (hq > q) q = hq; }
+    if (q < 256) q = 256;
+    return kHeaderBytes + 4 * q;
 }
 
 }  // namespace lr
 
 using namespace lr;
+
+#ifdef LR_TRACE
+extern "C" int lowrank_debug_trace(void* buf) { lr::g_trace_buffer = (unsigned long long*)buf; return 0; }
+#endif
 
 extern "C" {
 
@@ -88,6 +94,19 @@ int lowrank_workspace_init(void* workspace, size_t workspace_bytes, void* stream
     if (!workspace) { set_error("workspace is NULL"); return LR_ERR_NULL; }
     if (((uintptr_t)workspace) & 255u) { set_error("workspace must be 256-byte aligned"); return LR_ERR_ALIGN; }
     return fill_zero(workspace, workspace_bytes & ~(size_t)3, (hipStream_t)stream);
+}
+
+int lowrank_workspace_status(const void* workspace, void* stream) {
+    if (!workspace) { set_error("workspace is NULL"); return LR_ERR_NULL; }
+    Ctrl c;
+    hipStream_t s = (hipStream_t)stream;
+    if (hipMemcpyAsync(&c, workspace, sizeof(Ctrl), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) {
+        set_error("workspace status: copy failed: %s", hipGetErrorString(hipGetLastError()));
+        return LR_ERR_LAUNCH;
+    }
+    if (c.error != 0) { set_error("a device-side wait between stages gave up; results of that call are invalid, re-initialise the workspace"); return LR_ERR_LAUNCH; }
+    return LR_OK;
 }
 
 const char* lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
@@ -119,8 +138,8 @@ int lowrank_linear(const void* x, const void* U, const void* V, const void* bias
     const bool al = aligned16(x) && aligned16(U) && aligned16(V) && aligned16(y) && aligned16(bias);
     const Plan plan = pick_plan(dtype, phase, M, decode_shape_ok(M, d_in, r) && decode_shape_ok(M, r, d_out),
                                 prefill_shape_ok(M, d_in, r) && prefill_shape_ok(M, r, d_out), al);
-    if (plan == PLAN_DECODE) return decode_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, s);
-    float* t = (float*)((char*)workspace + kHeaderBytes);
+    if (plan == PLAN_DECODE) return decode_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
+    float* t = (float*)ws_layout(workspace, workspace_bytes).staging;
     CacheDst none = {nullptr, nullptr, 0, 1};
     st = generic_stage1(x, false, U, t, r, M, d_in, r, dtype, s);
     if (st != LR_OK) return st;
@@ -182,8 +201,8 @@ int lowrank_qkv(const void* x, const void* const* U, const void* const* V, const
     if (kv) al = al && aligned16(kv->k_cache) && aligned16(kv->v_cache);
     const Plan plan = pick_plan(dtype, phase, M, dec, pre, al);
     if (plan == PLAN_DECODE)
-        return decode_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, s);
-    float* t = (float*)((char*)workspace + kHeaderBytes);
+        return decode_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, workspace_bytes, s);
+    float* t = (float*)ws_layout(workspace, workspace_bytes).staging;
     const int64_t ldt = R > 0 ? R : 1;
     for (int i = 0; i < n_proj; ++i)
         if (base_of[i] == i) {
@@ -221,10 +240,10 @@ int lowrank_packed_mlp(const void* x, const void* U_gu, const void* V_g, const v
                      prefill_shape_ok(M, ffn, r_d) && prefill_shape_ok(M, r_d, d);
     const Plan plan = pick_plan(dtype, phase, M, dec, pre, al);
     if (plan == PLAN_DECODE)
-        return decode_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, s);
-    char* base = (char*)workspace + kHeaderBytes;
+        return decode_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, workspace_bytes, s);
+    char* base = ws_layout(workspace, workspace_bytes).staging;
     float* t = (float*)base;                                   // [M, r_g + r_u + r_d]
-    float* h = (float*)(base + 2 * align256((size_t)M * (size_t)r_total * 4));   // [M, ffn]
+    float* h = (float*)(base + align256((size_t)M * (size_t)r_total * 4));       // [M, ffn]
     const int64_t ldt = r_total > 0 ? r_total : 1;
     CacheDst none = {nullptr, nullptr, 0, 1};
     st = generic_stage1(x, false, U_gu, t, ldt, M, d, r_g + r_u, dtype, s);

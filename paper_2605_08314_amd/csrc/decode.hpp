@@ -21,12 +21,57 @@ struct DProb {
     int tile_begin;   // first tile index of this product inside the stage
 };
 
-struct DStage {
-    DProb p[kMaxProb];
-    int nprob;
-    int M;
-    int total_tiles;
+template <int NP> struct DStageT { DProb p[NP]; int nprob, M, total_tiles; };
+typedef DStageT<kMaxProb> DStage;
+
+// Control block at the start of every workspace (zero when prepared).  A stage barrier is kSlots
+// counters on separate 128-byte lines: workgroup w adds 1 to slot w % kSlots, a waiting wave reads
+// all slots with one load instruction.  One hot counter for 256 workgroups costs several
+// microseconds per barrier on this chip; sixteen cool ones cost about one.
+constexpr int kBarriers = 3;
+constexpr int kSlots = 16;
+constexpr int kSlotStride = 32;   // uint32 words between slots (128 bytes)
+struct Ctrl {
+    uint32_t epoch;                     // number of fused calls completed on this workspace
+    uint32_t error;                     // nonzero: a bounded device-side wait gave up
+    uint32_t dirty[2];                  // floats of accumulator area p that are not zero
+    uint32_t pad[28];
+    uint32_t cnt[2][kBarriers][kSlots * kSlotStride];   // [epoch parity][barrier][slot]
 };
+static_assert(sizeof(Ctrl) <= kHeaderBytes, "control block must fit the workspace header");
+
+// Where the parts of a workspace of `ws_bytes` bytes sit: header | acc area 0 | acc area 1 | staging.
+struct WsLayout {
+    Ctrl* ctrl; char* acc0; size_t acc_bytes; char* staging; size_t staging_bytes;
+};
+inline WsLayout ws_layout(void* ws, size_t ws_bytes) {
+    WsLayout L;
+    L.ctrl = (Ctrl*)ws;
+    L.acc_bytes = ((ws_bytes - kHeaderBytes) / 4) & ~(size_t)255;
+    L.acc0 = (char*)ws + kHeaderBytes;
+    L.staging = L.acc0 + 2 * L.acc_bytes;
+    L.staging_bytes = ws_bytes - kHeaderBytes - 2 * L.acc_bytes;
+    return L;
+}
+
+struct FusedCommon {
+    Ctrl* ctrl;
+    char* acc0;              // accumulator area 0; area 1 = acc0 + acc_bytes
+    size_t acc_bytes;
+    uint32_t dirty_floats;   // floats of the accumulator area this call adds into
+    uint32_t reserved;
+    unsigned long long* trace;   // timeline buffer of trace builds, else NULL
+};
+template <int NP> struct Fused2Args { FusedCommon fc; DStageT<NP> s1, s2; };
+struct FusedMlpArgs { FusedCommon fc; DStageT<1> a, b, c, d; };
+
+// Fused launches (all stages in one kernel, `grid` resident workgroups of nw = 4 or 8 waves).  cpl* = columns per lane
+// of each stage.  Return LR_ERR_UNSUPPORTED if the grid would not be fully resident.
+int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int cpl1, int cpl2,
+                         int grid, int nw, hipStream_t s);
+int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, int nw, hipStream_t s);
+extern unsigned long long* g_trace_buffer;   // host copy of the trace pointer (NULL unless a trace build set it)
+int decode_resident_grid();   // workgroups that are certainly co-resident (number of CUs), cached
 
 // Launch one stage: cpl = bf16 columns per lane (4 or 8), a_f32 = activations are fp32 (rank-space
 // accumulators) rather than bf16, epi = EPI_*.
@@ -35,14 +80,14 @@ int decode_launch_stage(const DStage& st, int cpl, bool a_f32, int epi, hipStrea
 // Host planners (decode_plan.hip).  They assume decode_shape_ok(...) held for every product.
 bool decode_shape_ok(int64_t M, int64_t K, int64_t N);
 int decode_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
-                  int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, hipStream_t s);
+                  int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s);
 int decode_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
                void* const* out, const int64_t* r, const int64_t* d_out, int n_proj, const int* base_of,
                const int64_t* t_off, int64_t R, int64_t M, int64_t d_in, const lr_kv_target* kv,
-               void* ws, hipStream_t s);
+               void* ws, size_t ws_bytes, hipStream_t s);
 int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u, const void* U_d,
                const void* V_d, const void* b_g, const void* b_u, const void* b_d, void* out,
                int64_t M, int64_t d, int64_t ffn, int64_t r_g, int64_t r_u, int64_t r_d,
-               void* ws, hipStream_t s);
+               void* ws, size_t ws_bytes, hipStream_t s);
 
 }  // namespace lr

@@ -1,0 +1,533 @@
+// Decode-phase kernels (1..32 token rows, bf16): each stage of the factorized layer is a skinny
+// product C[M, N] (+)= A[M, K] * W[K, N] whose cost is streaming W from HBM exactly once.
+//
+// Work decomposition.  A workgroup (4 wavefronts of 64 lanes) owns one tile of W:
+// KS rows x NC columns (NC = 16 * CPL, CPL = bf16 columns per lane: 4 -> 8-byte loads,
+// 8 -> 16-byte loads).  Its waves take the tile's 32-row blocks round-robin.  For one block a lane
+// (j = lane % 16, g = lane / 16) loads rows 8g..8g+7, columns CPL*j..CPL*j+CPL-1: every load
+// instruction of the wave covers four full row segments of NC*2 bytes, i.e. coalesced and
+// contiguous, straight from the row-major factor -- no repacking of U or V is needed.
+//
+// The token rows ride on the matrix cores: v_mfma_f32_16x16x32_bf16 with the activations as the
+// 16-row operand (rows >= M are zero) and the weights as the 16-column operand.  That operand
+// wants, per lane, 8 consecutive k for ONE column; the lane holds 8 k-rows x CPL columns, so a
+// 16-bit transpose inside the lane (v_perm_b32) yields CPL operands, one per column offset b,
+// and MFMA number b produces output columns {CPL*j + b}.  Lane (j, g) of result b holds rows
+// 4g..4g+3 of column CPL*j + b, so a lane ends up with CPL contiguous output columns per row.
+//
+// The four waves' partial sums are combined through LDS in a fixed order; then either
+//   EPI_ATOMIC : added into an fp32 accumulator in global memory (split-K stages: t = x U, t_d = h U_d),
+//   EPI_STORE  : + bias, rounded to bf16, stored to y and/or scattered into the dense KV cache,
+//   EPI_GATEUP : two products (gate, up) of the same columns -> SiLU(g + b_g) * (u + b_u) -> bf16 h.
+#pragma once
+#include "decode.hpp"
+
+namespace lr {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x8_t __attribute__((ext_vector_type(8)));
+
+template <int CPL> struct WFrag { uint32_t w[8][CPL / 2]; };   // 8 k-rows x CPL bf16 columns
+// 8 consecutive k of one token row, as loaded: packed bf16 (4 dwords) or raw fp32 (8 dwords, converted
+// only when the MFMA consumes it, so that issuing the load never waits on earlier loads).
+template <bool AF32> struct AFrag { uint32_t a[AF32 ? 8 : 4]; };
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// two fp32 -> packed bf16 pair, round-to-nearest-even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    union { bf16x2_t v; uint32_t u; } x;
+    x.v = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+    return x.u;
+}
+
+template <int CPL>
+__device__ __forceinline__ void load_w(WFrag<CPL>& f, const bf16_t* __restrict__ W, int N, int row0, int col) {
+    const bf16_t* p = W + (size_t)row0 * (size_t)N + col;
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+        if constexpr (CPL == 8) {
+            const uint4 v = *reinterpret_cast<const uint4*>(p + (size_t)a * N);
+            f.w[a][0] = v.x; f.w[a][1] = v.y; f.w[a][2] = v.z; f.w[a][3] = v.w;
+        } else {
+            const uint2 v = *reinterpret_cast<const uint2*>(p + (size_t)a * N);
+            f.w[a][0] = v.x; f.w[a][1] = v.y;
+        }
+    }
+}
+
+// 8-byte load that is coherent across the whole device (agent scope): used for data that other
+// workgroups of the SAME launch produced (rank-space accumulators, hidden rows).
+__device__ __forceinline__ uint2 ld_coherent_b64(const void* p) {
+    const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+}
+__device__ __forceinline__ void st_coherent_b64(void* p, uint2 v) {
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), (uint64_t)v.x | ((uint64_t)v.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// COH: the rows were written earlier in this launch by other workgroups -> coherent loads.
+template <bool AF32, bool COH>
+__device__ __forceinline__ void load_a(AFrag<AF32>& f, const void* A, int lda, int m, int M, int k) {
+    constexpr int ND = AF32 ? 8 : 4;
+    if (m < M) {
+        const uint32_t* p = AF32 ? reinterpret_cast<const uint32_t*>(reinterpret_cast<const float*>(A) + (size_t)m * lda + k)
+                                 : reinterpret_cast<const uint32_t*>(reinterpret_cast<const bf16_t*>(A) + (size_t)m * lda + k);
+        if constexpr (COH) {
+#pragma unroll
+            for (int i = 0; i < ND; i += 2) { const uint2 v = ld_coherent_b64(p + i); f.a[i] = v.x; f.a[i + 1] = v.y; }
+        } else {
+#pragma unroll
+            for (int i = 0; i < ND; i += 4) {
+                const uint4 v = *reinterpret_cast<const uint4*>(p + i);
+                f.a[i] = v.x; f.a[i + 1] = v.y; f.a[i + 2] = v.z; f.a[i + 3] = v.w;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < ND; ++i) f.a[i] = 0u;
+    }
+}
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    union { uint32_t u[4]; bf16x8_t v; } x;
+    x.u[0] = a; x.u[1] = b; x.u[2] = c; x.u[3] = d;
+    return x.v;
+}
+
+// acc[mb][b] += A_mb (16 x 32) * W(:, column offset b) (32 x 16 lanes)
+template <int MB, int CPL, bool AF32>
+__device__ __forceinline__ void mma_block(f32x4_t (&acc)[MB][CPL], const WFrag<CPL>& wf, const AFrag<AF32> (&af)[MB]) {
+    bf16x8_t av[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        if constexpr (AF32) {
+            const uint32_t* a = af[mb].a;
+            av[mb] = as_bf16x8(pack2(__uint_as_float(a[0]), __uint_as_float(a[1])), pack2(__uint_as_float(a[2]), __uint_as_float(a[3])),
+                               pack2(__uint_as_float(a[4]), __uint_as_float(a[5])), pack2(__uint_as_float(a[6]), __uint_as_float(a[7])));
+        } else {
+            av[mb] = as_bf16x8(af[mb].a[0], af[mb].a[1], af[mb].a[2], af[mb].a[3]);
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < CPL; ++b) {
+        const int q = b >> 1;
+        const uint32_t sel = (b & 1) ? 0x07060302u : 0x05040100u;   // pick the high / low bf16 of each dword
+        // dword s of the operand = { row 2s (low half), row 2s+1 (high half) } of column b
+        const bf16x8_t bv = as_bf16x8(__builtin_amdgcn_perm(wf.w[1][q], wf.w[0][q], sel),
+                                      __builtin_amdgcn_perm(wf.w[3][q], wf.w[2][q], sel),
+                                      __builtin_amdgcn_perm(wf.w[5][q], wf.w[4][q], sel),
+                                      __builtin_amdgcn_perm(wf.w[7][q], wf.w[6][q], sel));
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            acc[mb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mb], bv, acc[mb][b], 0, 0, 0);
+    }
+}
+
+// Hook run between the first weight loads of a tile and its first activation loads.
+struct NoSync { static constexpr bool kCoherent = false; static constexpr bool kPolls = false; __device__ __forceinline__ void operator()() const {} };
+// Same, for later tiles of a stage whose input other workgroups of this launch produced.
+struct NoSyncCoherent { static constexpr bool kCoherent = true; static constexpr bool kPolls = false; __device__ __forceinline__ void operator()() const {} };
+
+// This wave's share of rows [32*kb0, 32*kb1) of W: blocks kb0 + wave, kb0 + wave + NW, ...
+// The first PF weight blocks are requested before `sync()` runs and the activations after it, so
+// that a wait for the producer of A overlaps with weight traffic already in flight.
+template <int MB, int CPL, bool AF32, int PF, int NW, class Sync>
+__device__ __forceinline__ void mma_range(f32x4_t (&acc)[MB][CPL], const bf16_t* __restrict__ W, int N,
+                                          const void* A, int lda, int M, int col, int kb0, int kb1,
+                                          int wave, int j, int g, const Sync& sync) {
+    WFrag<CPL> wf[PF];
+    AFrag<AF32> af[PF][MB];
+    int blk = kb0 + wave;
+    // The polling wave (wave 0) asks for its weights only after the wait: loads return in order, so
+    // a poll issued behind a long weight prefetch would see the counters late.
+    const bool early = !(Sync::kPolls && wave == 0);
+    if (early) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int bb = blk + NW * p;
+            if (bb < kb1) load_w<CPL>(wf[p], W, N, 32 * bb + 8 * g, col);
+        }
+    }
+    sync();
+    if (!early) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int bb = blk + NW * p;
+            if (bb < kb1) load_w<CPL>(wf[p], W, N, 32 * bb + 8 * g, col);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+        const int bb = blk + NW * p;
+        if (bb < kb1) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) load_a<AF32, Sync::kCoherent>(af[p][mb], A, lda, 16 * mb + j, M, 32 * bb + 8 * g);
+        }
+    }
+    for (; blk < kb1; blk += NW * PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int bb = blk + NW * p;
+            if (bb < kb1) {
+                mma_block<MB, CPL, AF32>(acc, wf[p], af[p]);
+                const int nb = bb + NW * PF;
+                if (nb < kb1) {
+                    load_w<CPL>(wf[p], W, N, 32 * nb + 8 * g, col);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) load_a<AF32, Sync::kCoherent>(af[p][mb], A, lda, 16 * mb + j, M, 32 * nb + 8 * g);
+                }
+            }
+        }
+    }
+}
+
+template <int CPL>
+__device__ __forceinline__ void store_bf16_row(bf16_t* dst, const float (&v)[CPL]) {
+    if constexpr (CPL == 8) {
+        uint4 o; o.x = pack2(v[0], v[1]); o.y = pack2(v[2], v[3]); o.z = pack2(v[4], v[5]); o.w = pack2(v[6], v[7]);
+        *reinterpret_cast<uint4*>(dst) = o;
+    } else {
+        uint2 o; o.x = pack2(v[0], v[1]); o.y = pack2(v[2], v[3]);
+        *reinterpret_cast<uint2*>(dst) = o;
+    }
+}
+
+template <int CPL>
+__device__ __forceinline__ void load_bf16_row(float (&v)[CPL], const bf16_t* src) {
+#pragma unroll
+    for (int b = 0; b < CPL; ++b) v[b] = bf16_to_f32(src[b]);
+}
+
+// One workgroup tile, from loads to epilogue.  `red` is LDS scratch of red_floats<...>() floats.
+template <int MB, int CPL, bool AF32, int EPI, int PF, int NW, class Sync>
+__device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float4* __restrict__ red,
+                                            const Sync& sync, size_t acc_shift) {
+    constexpr int NMAT = (EPI == EPI_GATEUP) ? 2 : 1;
+    constexpr int NC = 16 * CPL;
+    constexpr int Q = CPL / 4;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 15, g = lane >> 4;
+    const int tn = lt % P.tiles_n, tk = lt / P.tiles_n;
+    const int n0 = tn * NC;
+    const int col = n0 + CPL * j;
+
+    f32x4_t acc[NMAT][MB][CPL];
+#pragma unroll
+    for (int mt = 0; mt < NMAT; ++mt)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int b = 0; b < CPL; ++b) acc[mt][mb][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    {
+        const int kb0 = tk * (P.KS >> 5);
+        int kb1 = kb0 + (P.KS >> 5);
+        if (kb1 > (P.K >> 5)) kb1 = P.K >> 5;
+        const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
+        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, kb0, kb1, wave, j, g, sync);
+    }
+    if constexpr (NMAT == 2) {
+        const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
+        if constexpr (Sync::kCoherent) mma_range<MB, CPL, AF32, PF, NW>(acc[1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncCoherent());
+        else mma_range<MB, CPL, AF32, PF, NW>(acc[1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSync());
+    }
+
+    // cross-wave reduction through LDS: red[wave][slot = (mat*MB + mb)*4 + v][q][lane]
+    constexpr int NSL = NMAT * MB * 4;
+#pragma unroll
+    for (int mt = 0; mt < NMAT; ++mt)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+                    red[((wave * NSL + (mt * MB + mb) * 4 + v) * Q + q) * 64 + lane] =
+                        make_float4(acc[mt][mb][4 * q + 0][v], acc[mt][mb][4 * q + 1][v],
+                                    acc[mt][mb][4 * q + 2][v], acc[mt][mb][4 * q + 3][v]);
+    __syncthreads();
+#pragma unroll
+    for (int pidx = tid; pidx < 256 * MB; pidx += 64 * NW) {   // (mb, v, lane') triples
+        const int sl = pidx >> 6, ln = pidx & 63;
+        const int mb = sl >> 2, v = sl & 3;
+        const int m = 16 * mb + 4 * (ln >> 4) + v;
+        const int n = n0 + CPL * (ln & 15);
+        float val[NMAT][CPL];
+#pragma unroll
+        for (int mt = 0; mt < NMAT; ++mt)
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                float4 s = red[((0 * NSL + mt * MB * 4 + sl) * Q + q) * 64 + ln];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) {
+                    const float4 o = red[((w * NSL + mt * MB * 4 + sl) * Q + q) * 64 + ln];
+                    s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w;
+                }
+                val[mt][4 * q + 0] = s.x; val[mt][4 * q + 1] = s.y; val[mt][4 * q + 2] = s.z; val[mt][4 * q + 3] = s.w;
+            }
+        if (m < M) {
+            if constexpr (EPI == EPI_ATOMIC) {
+                float* c = (float*)((char*)P.C + acc_shift) + (size_t)m * P.ldc + n;
+#pragma unroll
+                for (int b = 0; b < CPL; ++b) unsafeAtomicAdd(c + b, val[0][b]);
+            } else if constexpr (EPI == EPI_STORE) {
+                if (P.bias) {
+                    float bv[CPL];
+                    load_bf16_row<CPL>(bv, P.bias + n);
+#pragma unroll
+                    for (int b = 0; b < CPL; ++b) val[0][b] += bv[b];
+                }
+                if (P.Y) store_bf16_row<CPL>(P.Y + (size_t)m * P.N + n, val[0]);
+                if (P.cache) {
+                    const int bi = m / P.T, s = m - bi * P.T;
+                    const int64_t pp = (int64_t)P.pos[bi] + s;
+                    if (pp >= 0 && pp < P.S_max)
+                        store_bf16_row<CPL>(reinterpret_cast<bf16_t*>(P.cache) + ((size_t)bi * P.S_max + (size_t)pp) * P.N + n, val[0]);
+                }
+            } else {
+                float hv[CPL];
+                float bg[CPL], bu[CPL];
+#pragma unroll
+                for (int b = 0; b < CPL; ++b) { bg[b] = 0.f; bu[b] = 0.f; }
+                if (P.bias) load_bf16_row<CPL>(bg, P.bias + n);
+                if (P.bias2) load_bf16_row<CPL>(bu, P.bias2 + n);
+#pragma unroll
+                for (int b = 0; b < CPL; ++b) hv[b] = silu_f32(val[0][b] + bg[b]) * (val[NMAT - 1][b] + bu[b]);
+                if constexpr (CPL == 4 && Sync::kCoherent) {   // fused launch: another workgroup reads h next
+                    st_coherent_b64(P.Y + (size_t)m * P.N + n, make_uint2(pack2(hv[0], hv[1]), pack2(hv[2], hv[3])));
+                } else {
+                    store_bf16_row<CPL>(P.Y + (size_t)m * P.N + n, hv);
+                }
+            }
+        }
+    }
+}
+
+template <int MB, int CPL, int EPI, int NW>
+constexpr int red_float4s() { return NW * ((EPI == EPI_GATEUP) ? 2 : 1) * MB * 4 * (CPL / 4) * 64; }
+
+template <int MB, int CPL, bool AF32, int EPI, int PF>
+__global__ void __launch_bounds__(256) k_decode_stage(DStage st) {
+    __shared__ float4 red[red_float4s<MB, CPL, EPI, 4>()];
+    const int tile = blockIdx.x;
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxProb; ++i)
+        if (i < st.nprob && tile >= st.p[i].tile_begin) pi = i;
+    const DProb& P = st.p[pi];
+    decode_tile<MB, CPL, AF32, EPI, PF, 4>(P, st.M, tile - P.tile_begin, red, NoSync(), 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fused decode calls: all stages of one entry point in ONE launch.  The grid is small enough for
+// every workgroup to be resident at once (host checks this against the occupancy of the kernel),
+// stages are separated by a device-wide arrive/wait counter in the workspace control block, and
+// a workgroup asks for the first weight blocks of its next tile BEFORE it waits, so HBM keeps
+// streaming across the dependency.  Waiting is bounded: after kSpinLimit polls the workgroup sets
+// the control block's error word and carries on (wrong results, reported by
+// lowrank_workspace_status), so every wave always reaches the end of the kernel.
+//
+// Split-K accumulators live in one of two areas picked by the parity of the control block's epoch;
+// while a call accumulates into area p it clears what the previous call dirtied in area 1-p, and
+// the last workgroup to arrive at the first barrier publishes epoch+1 and the new dirty extents.
+constexpr uint32_t kSpinLimit = 1u << 20;
+
+// Optional timeline of the fused kernels (builds with -DLR_TRACE only; never in the shipped library):
+// thread 0 of every workgroup stores the 100 MHz wall clock at numbered points.
+#ifdef LR_TRACE
+#define LR_STAMP_TO(tr, i) do { if (threadIdx.x == 0 && (tr)) (tr)[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define LR_STAMP_TO(tr, i) do { } while (0)
+#endif
+#define LR_STAMP(i) LR_STAMP_TO(fa.fc.trace, i)
+
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Stage barrier.  Data shared inside a launch is only touched by atomics and by agent-coherent
+// loads / stores, so no cache maintenance is needed: it is enough that every wave has drained its
+// memory operations (workgroup-scope release = s_waitcnt) before the workgroup's arrival is counted.
+// (Agent-scope release / acquire fences here cost tens of microseconds per barrier: they write back
+// and invalidate the L2.)
+// All threads of the workgroup call this after their last store / atomic of the stage.
+__device__ __forceinline__ void grid_arrive(uint32_t* slots) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x == 0)
+        __hip_atomic_fetch_add(slots + (blockIdx.x % kSlots) * kSlotStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct GridWait {
+    static constexpr bool kCoherent = true;
+    static constexpr bool kPolls = true;
+    const uint32_t* slots;
+    uint32_t grid;
+    uint32_t* err;
+    int stamp;
+    unsigned long long* trace;
+    __device__ __forceinline__ void operator()() const {
+        if (threadIdx.x < 64) {     // wave 0: lane s < kSlots watches slot s
+            const uint32_t lane = threadIdx.x;
+            const uint32_t want = lane < kSlots ? (grid + kSlots - 1 - lane) / kSlots : 0u;   // workgroups with w % kSlots == lane
+            const uint32_t* p = slots + (lane < kSlots ? lane : 0u) * kSlotStride;
+            uint32_t spins = 0;
+            while (true) {
+                const bool ok = ld_agent(p) >= want;
+                if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) break;
+                if (++spins > kSpinLimit) {
+                    if (lane == 0) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+        __syncthreads();
+        LR_STAMP_TO(trace, stamp);
+    }
+};
+
+// Start of every fused kernel: ONE 16-byte read of {epoch, error, dirty[0], dirty[1]}; nothing waits
+// on it until the first epilogue needs the parity.
+struct CtrlSnap { uint32_t epoch, p, dirty_other; };
+__device__ __forceinline__ CtrlSnap fused_begin(const FusedCommon& fc) {
+    const uint2 a = ld_coherent_b64(&fc.ctrl->epoch);      // epoch, error
+    const uint2 d = ld_coherent_b64(&fc.ctrl->dirty[0]);
+    CtrlSnap c;
+    c.epoch = a.x; c.p = a.x & 1u;
+    c.dirty_other = c.p ? d.x : d.y;
+    return c;
+}
+
+// Clear what the previous call left in the other accumulator area and the other parity's barrier
+// counters (nobody uses them during this call).  Called by every workgroup before its first arrive.
+__device__ __forceinline__ void fused_clear_other(const FusedCommon& fc, const CtrlSnap& c) {
+    const uint32_t n4 = (c.dirty_other + 3u) >> 2;
+    float4* other = reinterpret_cast<float4*>(fc.acc0 + (size_t)(1u - c.p) * fc.acc_bytes);
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += gridDim.x * blockDim.x)
+        other[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (blockIdx.x == 0)
+        for (uint32_t i = threadIdx.x; i < (uint32_t)(kBarriers * kSlots); i += blockDim.x)
+            fc.ctrl->cnt[1u - c.p][i / kSlots][(i % kSlots) * kSlotStride] = 0u;
+}
+
+// First barrier of a fused kernel: every workgroup clears its share of the other accumulator area,
+// then arrives.
+__device__ __forceinline__ void fused_first_arrive(const FusedCommon& fc, const CtrlSnap& c) {
+    fused_clear_other(fc, c);
+    grid_arrive(fc.ctrl->cnt[c.p][0]);
+}
+
+// Workgroup 0, once it has seen the first barrier complete (every workgroup has read the control
+// block by then), publishes the next epoch and the new dirty extents.
+__device__ __forceinline__ void fused_publish(const FusedCommon& fc, const CtrlSnap& c) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        fc.ctrl->dirty[c.p] = fc.dirty_floats;
+        fc.ctrl->dirty[1u - c.p] = 0u;
+        __hip_atomic_store(&fc.ctrl->epoch, c.epoch + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int NP>
+__device__ __forceinline__ const DProb& find_prob(const DStageT<NP>& st, int tile) {
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < NP; ++i)
+        if (i < st.nprob && tile >= st.p[i].tile_begin) pi = i;
+    return st.p[pi];
+}
+
+// lowrank_linear / lowrank_qkv: t += x U (split-K, atomics)  ->  barrier  ->  y = t V (+bias, cache).
+template <int MB, int CPL1, int CPL2, int PF, int NP, int NW>
+__global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
+    constexpr int R1 = red_float4s<MB, CPL1, EPI_ATOMIC, NW>(), R2 = red_float4s<MB, CPL2, EPI_STORE, NW>();
+    __shared__ float4 red[R1 > R2 ? R1 : R2];
+    const CtrlSnap cs = fused_begin(fa.fc);
+    const uint32_t p = cs.p;
+    const size_t shift = (size_t)p * fa.fc.acc_bytes;
+    for (int tile = blockIdx.x; tile < fa.s1.total_tiles; tile += gridDim.x) {
+        const DProb& P = find_prob<NP>(fa.s1, tile);
+        decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift);
+        __syncthreads();
+    }
+    fused_first_arrive(fa.fc, cs);
+    const GridWait gw = {fa.fc.ctrl->cnt[p][0], gridDim.x, &fa.fc.ctrl->error, 3, fa.fc.trace};
+    bool waited = false;
+    for (int tile = blockIdx.x; tile < fa.s2.total_tiles; tile += gridDim.x) {
+        const DProb& P = find_prob<NP>(fa.s2, tile);
+        if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, gw, shift);
+        else         decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncCoherent(), shift);
+        if (!waited) fused_publish(fa.fc, cs);
+        waited = true;
+        __syncthreads();
+    }
+    if (blockIdx.x == 0 && !waited) { gw(); fused_publish(fa.fc, cs); }
+}
+
+// lowrank_packed_mlp: four stages, three barriers.
+template <int MB, int CPLA, int CPLC, int CPLD, int PF, int NW>
+__global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
+    constexpr int RA = red_float4s<MB, CPLA, EPI_ATOMIC, NW>(), RB = red_float4s<MB, 4, EPI_GATEUP, NW>();
+    constexpr int RC = red_float4s<MB, CPLC, EPI_ATOMIC, NW>(), RD = red_float4s<MB, CPLD, EPI_STORE, NW>();
+    constexpr int R01 = RA > RB ? RA : RB, R23 = RC > RD ? RC : RD;
+    __shared__ float4 red[R01 > R23 ? R01 : R23];
+    const CtrlSnap cs = fused_begin(fa.fc);
+    const uint32_t p = cs.p;
+    const size_t shift = (size_t)p * fa.fc.acc_bytes;
+    const uint32_t G = gridDim.x;
+    uint32_t (*cnt)[kSlots * kSlotStride] = fa.fc.ctrl->cnt[p];
+    LR_STAMP(0);
+    // A: t_gu += x U_gu
+    for (int tile = blockIdx.x; tile < fa.a.total_tiles; tile += G) {
+        decode_tile<MB, CPLA, false, EPI_ATOMIC, PF, NW>(fa.a.p[0], fa.a.M, tile, red, NoSync(), shift);
+        __syncthreads();
+    }
+    LR_STAMP(1);
+    fused_first_arrive(fa.fc, cs);
+    LR_STAMP(2);
+    // B: h = SiLU(t_g V_g + b_g) * (t_u V_u + b_u)
+    {
+        const GridWait gw = {cnt[0], G, &fa.fc.ctrl->error, 3, fa.fc.trace};
+        bool waited = false;
+        for (int tile = blockIdx.x; tile < fa.b.total_tiles; tile += G) {
+            if (!waited) decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, gw, shift);
+            else         decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncCoherent(), shift);
+            if (!waited) fused_publish(fa.fc, cs);
+            waited = true;
+            __syncthreads();
+        }
+        if (blockIdx.x == 0 && !waited) { gw(); fused_publish(fa.fc, cs); }
+    }
+    LR_STAMP(4);
+    grid_arrive(cnt[1]);
+    LR_STAMP(5);
+    // C: t_d += h U_d
+    {
+        const GridWait gw = {cnt[1], G, &fa.fc.ctrl->error, 6, fa.fc.trace};
+        bool waited = false;
+        for (int tile = blockIdx.x; tile < fa.c.total_tiles; tile += G) {
+            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, gw, shift);
+            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncCoherent(), shift);
+            waited = true;
+            __syncthreads();
+        }
+    }
+    LR_STAMP(7);
+    grid_arrive(cnt[2]);
+    LR_STAMP(8);
+    // D: out = t_d V_d + b_d
+    {
+        const GridWait gw = {cnt[2], G, &fa.fc.ctrl->error, 9, fa.fc.trace};
+        bool waited = false;
+        for (int tile = blockIdx.x; tile < fa.d.total_tiles; tile += G) {
+            if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, gw, shift);
+            else         decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncCoherent(), shift);
+            waited = true;
+            __syncthreads();
+        }
+    }
+    LR_STAMP(10);
+}
+
+}  // namespace lr

@@ -1,10 +1,13 @@
-// Host-side planning of the decode phase: how each stage is cut into workgroup tiles.
-// Integer logic only; every function enqueues kernels on the caller's stream and returns.
+// Host-side planning of the decode phase: how each stage is cut into workgroup tiles and whether
+// the call runs as one fused launch.  Integer logic only; every function enqueues kernels on the
+// caller's stream and returns.
 #include <stdlib.h>
 #include <string.h>
 #include "decode.hpp"
 
 namespace lr {
+
+unsigned long long* g_trace_buffer = nullptr;
 
 static int env_int(const char* name, int dflt) {
     const char* v = getenv(name);
@@ -18,42 +21,44 @@ bool decode_shape_ok(int64_t M, int64_t K, int64_t N) {
            K < (1 << 24) && N < (1 << 24);
 }
 
-static int pick_cpl(int64_t N) {
-    const int forced = env_int("LOWRANK_DECODE_CPL", 0);
-    if ((forced == 4) || (forced == 8 && N % 128 == 0)) return forced;
-    return 4;
+// Columns per lane of a stage whose matrices all have N % 128 == 0 (else 4): 4 = 64-column tiles
+// with 8-byte loads (more, smaller tiles), 8 = 128-column tiles with 16-byte loads.
+static int pick_cpl(bool all128) {
+    return (env_int("LOWRANK_DECODE_CPL", 4) == 8 && all128) ? 8 : 4;
 }
 
-// Split-K stage: rows per tile so that the stage has about `want` tiles; multiples of 128 rows
-// (one 32-row block per wave), larger slices for more token rows to keep the number of fp32
-// atomics (tiles_k * M * N) small against the weight bytes.
-static int pick_ks(int64_t K, int64_t tiles_n_total, int64_t M) {
+// Split-K stage: rows of W per tile so that the stage has about `want_tiles` tiles.  Multiples of
+// 32 rows, at least 128 (one block per wave); at least 256 for more than 8 token rows, which keeps
+// the fp32 atomics (tiles_k * M * N) small against the weight bytes.
+static int pick_ks(int64_t K, int64_t tiles_n_total, int64_t M, int64_t want_tiles) {
     const int forced = env_int("LOWRANK_DECODE_KS", 0);
-    if (forced >= 32 && forced % 32 == 0) return forced;
-    const int64_t want = env_int("LOWRANK_DECODE_TILES", 512);
-    int64_t tk = (want + tiles_n_total - 1) / tiles_n_total;
-    if (tk < 1) tk = 1;
-    int64_t ks = (K + tk - 1) / tk;
-    ks = ((ks + 127) / 128) * 128;
-    const int64_t floor_ks = M > 8 ? 256 : 128;
-    if (ks < floor_ks) ks = floor_ks;
-    if (ks > K) ks = ((K + 31) / 32) * 32;
+    int64_t ks;
+    if (forced >= 32 && forced % 32 == 0) ks = forced;
+    else {
+        int64_t tk = want_tiles / (tiles_n_total > 0 ? tiles_n_total : 1);
+        if (tk < 1) tk = 1;
+        ks = (K + tk - 1) / tk;
+        ks = ((ks + 31) / 32) * 32;
+        const int64_t floor_ks = M > 8 ? 256 : 128;
+        if (ks < floor_ks) ks = floor_ks;
+    }
+    if (ks > K) ks = K;
     return (int)ks;
 }
 
 static void zero_prob(DProb& p) { memset(&p, 0, sizeof(p)); p.T = 1; }
 
-// t[M, ldc] += A[M, K] * W[K, N] for several (A shared) weight matrices, split along K.
 struct SplitK { const void* W; int64_t N; float* C; };
+struct Final { const float* T; int64_t r; const void* V; int64_t N; const void* bias; void* Y; CacheDst cd; };
 
-static int stage_splitk(const void* A, bool a_f32, int64_t lda, int64_t M, int64_t K, const SplitK* items, int n,
-                        int64_t ldc, hipStream_t s) {
-    DStage st; st.nprob = n; st.M = (int)M;
-    int64_t n_all = 0; bool all128 = true;
-    for (int i = 0; i < n; ++i) { n_all += items[i].N; all128 = all128 && (items[i].N % 128 == 0); }
-    const int cpl = all128 ? pick_cpl(128) : 4;
+// t[M, ldc] += A[M, K] * W_i[K, N_i] for several weight matrices sharing A, split along K.
+static void build_splitk(DStage& st, const void* A, int64_t lda, int64_t M, int64_t K, const SplitK* items, int n,
+                         int64_t ldc, int64_t want_tiles, int cpl) {
+    st.nprob = n; st.M = (int)M;
+    int64_t n_all = 0;
+    for (int i = 0; i < n; ++i) n_all += items[i].N;
     const int nc = 16 * cpl;
-    const int ks = pick_ks(K, n_all / nc, M);
+    const int ks = pick_ks(K, n_all / nc, M, want_tiles);
     const int tk = (int)((K + ks - 1) / ks);
     int tile = 0;
     for (int i = 0; i < n; ++i) {
@@ -63,17 +68,12 @@ static int stage_splitk(const void* A, bool a_f32, int64_t lda, int64_t M, int64
         tile += p.tiles_n * tk;
     }
     st.total_tiles = tile;
-    return decode_launch_stage(st, cpl, a_f32, EPI_ATOMIC, s);
 }
 
-struct Final { const float* T; int64_t r; const void* V; int64_t N; const void* bias; void* Y; CacheDst cd; };
-
-// y_i[M, N_i] = t_i[M, r_i] * V_i[r_i, N_i] + bias_i, full K per tile, epilogue writes bf16.
-static int stage_final(const Final* items, int n, int64_t ldt, int64_t M, hipStream_t s) {
-    DStage st; st.nprob = n; st.M = (int)M;
-    bool all128 = true;
-    for (int i = 0; i < n; ++i) all128 = all128 && (items[i].N % 128 == 0);
-    const int cpl = all128 ? pick_cpl(128) : 4;
+// y_i[M, N_i] = t_i[M, r_i] * V_i[r_i, N_i] + bias_i: full K per tile, the epilogue writes bf16.
+static int build_final(DStage& st, const Final* items, int n, int64_t ldt, int64_t M) {
+    st.nprob = n; st.M = (int)M;
+    const int cpl = 4;   // 64-column tiles: full K per tile, so narrow tiles are the only source of parallelism
     const int nc = 16 * cpl;
     int tile = 0;
     for (int i = 0; i < n; ++i) {
@@ -85,76 +85,114 @@ static int stage_final(const Final* items, int n, int64_t ldt, int64_t M, hipStr
         tile += p.tiles_n;
     }
     st.total_tiles = tile;
-    return decode_launch_stage(st, cpl, true, EPI_STORE, s);
+    return cpl;
+}
+
+// One launch per call unless LOWRANK_DECODE_FUSED=0 or the device query fails.
+static int fused_grid() {
+    if (env_int("LOWRANK_DECODE_FUSED", 1) == 0) return 0;
+    const int cus = decode_resident_grid();
+    if (cus <= 0) return 0;
+    const int forced = env_int("LOWRANK_DECODE_GRID", 0);
+    return (forced > 0 && forced <= cus) ? forced : cus;
+}
+
+static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* sk_in, int nb, const Final* fin_in,
+                         int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s) {
+    const WsLayout L = ws_layout(ws, ws_bytes);
+    const int G = fused_grid();
+    const bool fused = G > 0 && (size_t)M * R * 4 <= L.acc_bytes;
+    float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
+    SplitK sk[kMaxProb]; Final fin[kMaxProb];
+    for (int i = 0; i < nb; ++i) { sk[i] = sk_in[i]; sk[i].C = tbase + (size_t)(uintptr_t)sk_in[i].C; }      // C, T hold float offsets
+    for (int i = 0; i < nf; ++i) { fin[i] = fin_in[i]; fin[i].T = tbase + (size_t)(uintptr_t)fin_in[i].T; }
+    DStage s1, s2;
+    bool all128 = true;
+    for (int i = 0; i < nb; ++i) all128 = all128 && (sk[i].N % 128 == 0);
+    const int c1 = pick_cpl(all128);
+    build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : env_int("LOWRANK_DECODE_TILES", 512), c1);
+    const int c2 = build_final(s2, fin, nf, R, M);
+    if (fused) {
+        FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, (uint32_t)(M * R), 0u, g_trace_buffer};
+        return decode_launch_fused2(fc, s1, s2, c1, c2, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, s);
+    }
+    int st = fill_zero(tbase, (size_t)M * R * 4, s);
+    if (st != LR_OK) return st;
+    st = decode_launch_stage(s1, c1, false, EPI_ATOMIC, s);
+    if (st != LR_OK) return st;
+    return decode_launch_stage(s2, c2, true, EPI_STORE, s);
 }
 
 int decode_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
-                  int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, hipStream_t s) {
-    float* t = (float*)((char*)ws + kHeaderBytes);
-    int st = fill_zero(t, (size_t)M * r * 4, s);
-    if (st != LR_OK) return st;
-    SplitK sk = {U, r, t};
-    st = stage_splitk(x, false, d_in, M, d_in, &sk, 1, r, s);
-    if (st != LR_OK) return st;
-    Final f = {t, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
-    return stage_final(&f, 1, r, M, s);
+                  int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s) {
+    SplitK sk = {U, r, (float*)0};
+    Final f = {(const float*)0, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
+    return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, ws, ws_bytes, s);
 }
 
 int decode_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
                void* const* out, const int64_t* r, const int64_t* d_out, int n_proj, const int* base_of,
                const int64_t* t_off, int64_t R, int64_t M, int64_t d_in, const lr_kv_target* kv,
-               void* ws, hipStream_t s) {
-    float* t = (float*)((char*)ws + kHeaderBytes);
-    int st = fill_zero(t, (size_t)M * R * 4, s);
-    if (st != LR_OK) return st;
+               void* ws, size_t ws_bytes, hipStream_t s) {
     SplitK sk[kMaxProb]; int nb = 0;
     for (int i = 0; i < n_proj; ++i)
-        if (base_of[i] == i) sk[nb++] = SplitK{U[i], r[i], t + t_off[i]};
-    st = stage_splitk(x, false, d_in, M, d_in, sk, nb, R, s);
-    if (st != LR_OK) return st;
+        if (base_of[i] == i) sk[nb++] = SplitK{U[i], r[i], (float*)(uintptr_t)t_off[i]};
     Final f[kMaxProb];
     for (int i = 0; i < n_proj; ++i) {
         CacheDst cd = {nullptr, nullptr, 0, 1};
         if (kv && i == kv->k_index) cd = CacheDst{kv->k_cache, kv->pos, kv->S_max, kv->tokens_per_seq};
         if (kv && i == kv->v_index) cd = CacheDst{kv->v_cache, kv->pos, kv->S_max, kv->tokens_per_seq};
-        f[i] = Final{t + t_off[i], r[i], V[i], d_out[i], bias ? bias[i] : nullptr, out[i], cd};
+        f[i] = Final{(const float*)(uintptr_t)t_off[i], r[i], V[i], d_out[i], bias ? bias[i] : nullptr, out[i], cd};
     }
-    return stage_final(f, n_proj, R, M, s);
+    return run_two_stage(x, d_in, M, sk, nb, f, n_proj, R, ws, ws_bytes, s);
 }
 
 int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u, const void* U_d,
                const void* V_d, const void* b_g, const void* b_u, const void* b_d, void* out,
                int64_t M, int64_t d, int64_t ffn, int64_t r_g, int64_t r_u, int64_t r_d,
-               void* ws, hipStream_t s) {
+               void* ws, size_t ws_bytes, hipStream_t s) {
     const int64_t r_gu = r_g + r_u, r_all = r_gu + r_d;
-    char* base = (char*)ws + kHeaderBytes;
-    float* t = (float*)base;                                              // [M, r_g + r_u + r_d] fp32
-    bf16_t* h = (bf16_t*)(base + 2 * align256((size_t)M * (size_t)r_all * 4));   // [M, ffn] bf16
-    int st = fill_zero(t, (size_t)M * r_all * 4, s);
-    if (st != LR_OK) return st;
-    // stage A: t_gu = x U_gu
+    const WsLayout L = ws_layout(ws, ws_bytes);
+    const int G = fused_grid();
+    const bool fused = G > 0 && (size_t)M * r_all * 4 <= L.acc_bytes;
+    // rank-space accumulators t[M, r_g + r_u + r_d] (fp32) and the bf16 hidden rows h[M, ffn]
+    float* t = fused ? (float*)L.acc0 : (float*)L.staging;
+    bf16_t* h = fused ? (bf16_t*)L.staging : (bf16_t*)(L.staging + align256((size_t)M * r_all * 4));
+    const int64_t want = fused ? G : env_int("LOWRANK_DECODE_TILES", 512);
+    DStage sa, sb, sc, sd;
     SplitK a = {U_gu, r_gu, t};
-    st = stage_splitk(x, false, d, M, d, &a, 1, r_all, s);
-    if (st != LR_OK) return st;
-    // stage B: h = SiLU(t_g V_g + b_g) * (t_u V_u + b_u)
-    {
-        DStage sg; sg.nprob = 1; sg.M = (int)M;
-        DProb& p = sg.p[0]; zero_prob(p);
+    const int ca = pick_cpl(r_gu % 128 == 0 && r_d % 128 == 0), cc = ca;   // both split-K stages share one tile width
+    build_splitk(sa, x, d, M, d, &a, 1, r_all, want, ca);
+    {   // gate/up: both products of a 64-column tile in one workgroup, full K
+        sb.nprob = 1; sb.M = (int)M;
+        DProb& p = sb.p[0]; zero_prob(p);
         p.W = (const bf16_t*)V_g; p.A = t; p.K = (int)r_g; p.lda = (int)r_all;
         p.W2 = (const bf16_t*)V_u; p.A2 = t + r_g; p.K2 = (int)r_u; p.lda2 = (int)r_all;
         p.N = (int)ffn; p.Y = h; p.bias = (const bf16_t*)b_g; p.bias2 = (const bf16_t*)b_u;
         p.tiles_n = (int)(ffn / 64); p.KS = (int)r_g; p.tile_begin = 0;
-        sg.total_tiles = p.tiles_n;
-        st = decode_launch_stage(sg, 4, true, EPI_GATEUP, s);
-        if (st != LR_OK) return st;
+        sb.total_tiles = p.tiles_n;
     }
-    // stage C: t_d = h U_d
     SplitK c = {U_d, r_d, t + r_gu};
-    st = stage_splitk(h, false, ffn, M, ffn, &c, 1, r_all, s);
-    if (st != LR_OK) return st;
-    // stage D: out = t_d V_d + b_d
+    build_splitk(sc, h, ffn, M, ffn, &c, 1, r_all, want, cc);
     Final f = {t + r_gu, r_d, V_d, d, b_d, out, {nullptr, nullptr, 0, 1}};
-    return stage_final(&f, 1, r_all, M, s);
+    const int cd = build_final(sd, &f, 1, r_all, M);
+    if (fused) {
+        FusedMlpArgs fa;
+        fa.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, (uint32_t)(M * r_all), 0u, g_trace_buffer};
+        const DStage* src[4] = {&sa, &sb, &sc, &sd};
+        DStageT<1>* dst[4] = {&fa.a, &fa.b, &fa.c, &fa.d};
+        for (int i = 0; i < 4; ++i) { dst[i]->p[0] = src[i]->p[0]; dst[i]->nprob = 1; dst[i]->M = (int)M; dst[i]->total_tiles = src[i]->total_tiles; }
+        return decode_launch_fused_mlp(fa, ca, cc, cd, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, s);
+    }
+    int st = fill_zero(t, (size_t)M * r_all * 4, s);
+    if (st != LR_OK) return st;
+    st = decode_launch_stage(sa, ca, false, EPI_ATOMIC, s);
+    if (st != LR_OK) return st;
+    st = decode_launch_stage(sb, 4, true, EPI_GATEUP, s);
+    if (st != LR_OK) return st;
+    st = decode_launch_stage(sc, cc, false, EPI_ATOMIC, s);
+    if (st != LR_OK) return st;
+    return decode_launch_stage(sd, cd, true, EPI_STORE, s);
 }
 
 }  // namespace lr

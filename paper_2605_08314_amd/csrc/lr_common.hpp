@@ -57,7 +57,7 @@ struct CacheDst {
 // ---- workspace layout --------------------------------------------------------------------------
 // [0, kHeaderBytes)   control block (epoch, error flag, barrier counters), zero when prepared
 // then fp32 areas, each 256-byte aligned, carved by the entry points.
-constexpr size_t kHeaderBytes = 4096;
+constexpr size_t kHeaderBytes = 16384;
 __host__ __device__ inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct Dims { int64_t M, d_in, r, d_out; };

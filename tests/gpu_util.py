@@ -45,7 +45,7 @@ def run_linear(x, U, V, bias, phase, dtype):
     y = torch.full((M, d_out), float("nan"), dtype=tdtype(dtype), device="cuda")
     ws = B.new_workspace(B.LR_OP_LINEAR, M, d_in, r, d_out, code(dtype), phase)
     B.lowrank_linear(xd, Ud, Vd, bd, y, phase, ws)
-    torch.cuda.synchronize()
+    B.lowrank_workspace_status(ws)
     return y
 
 
@@ -61,5 +61,5 @@ def run_mlp(w, phase, x=None, biases=True):
     bd = dev(t["b_d"]) if biases and "b_d" in t else None
     B.lowrank_packed_mlp(xd, dev(t["U_gu"]), dev(t["V_g"]), dev(t["V_u"]), dev(t["U_d"]), dev(t["V_d"]),
                          bg, bu, bd, out, phase, ws)
-    torch.cuda.synchronize()
+    B.lowrank_workspace_status(ws)
     return out

@@ -44,7 +44,7 @@ def run_attention(G, oracle, w, phase):
     ws = B.new_workspace(B.LR_OP_QKV, M, d, 3 * r, 3 * d, G.code(w.dtype), phase)
     B.lowrank_qkv(x, Us, Vs, None, outs, dict(k_cache=kc, v_cache=vc, pos=pos, tokens_per_seq=T, k_index=1, v_index=2),
                   phase, ws)
-    torch.cuda.synchronize()
+    B.lowrank_workspace_status(ws)
     want = oracle.qkv(t["x"].f64, [t["U_" + n].f64 for n in "qkv"], [t["V_" + n].f64 for n in "qkv"])
     for i in range(3):
         assert max_rel_err(G.host64(outs[i]), want[i]) <= TOL[w.dtype], f"projection {i}"
@@ -128,13 +128,14 @@ def test_config5_shared_basis(G, oracle, M, phase):
     outs = [torch.full((M, d), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
     ws = B.new_workspace(B.LR_OP_QKV, M, d, 2 * r, 2 * d, B.LR_BF16, phase)
     B.lowrank_qkv(x, [U, U], Vs, None, outs, None, phase, ws)          # same pointer twice: basis used once
-    torch.cuda.synchronize()
+    B.lowrank_workspace_status(ws)
     rows = np.arange(M) if M <= 32 else synth.prefill_row_sample(M, tile=256, per_tile=1)
     Uf = t["U_sh"].f64
     want = oracle.qkv(t["x"].f64[rows], [Uf, Uf], [t["V_0"].f64, t["V_1"].f64])
     for i in range(2):
         assert max_rel_err(G.host64(outs[i][rows]), want[i]) <= TOL["bf16"]
-    # the aliased call equals two independent single-layer calls bit for bit
+    # the aliased call equals two independent single-layer calls up to the order of the fp32
+    # split-K additions (a few bf16 ulps at most)
     for i in range(2):
         y = G.run_linear(t["x"], t["U_sh"], t[f"V_{i}"], None, phase, "bf16")
-        assert np.array_equal(G.bits(y), G.bits(outs[i]))
+        assert max_rel_err(G.host64(y), G.host64(outs[i])) <= 2.0 ** -6
