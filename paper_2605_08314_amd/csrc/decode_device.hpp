@@ -126,9 +126,9 @@ __device__ __forceinline__ void mma_block(f32x4_t (&acc)[MB][CPL], const WFrag<C
 }
 
 // Hook run between the first weight loads of a tile and its first activation loads.
-struct NoSync { static constexpr bool kCoherent = false; static constexpr bool kPolls = false; __device__ __forceinline__ void operator()() const {} };
+struct NoSync { static constexpr bool kCoherent = false; __device__ __forceinline__ void operator()() const {} };
 // Same, for later tiles of a stage whose input other workgroups of this launch produced.
-struct NoSyncCoherent { static constexpr bool kCoherent = true; static constexpr bool kPolls = false; __device__ __forceinline__ void operator()() const {} };
+struct NoSyncCoherent { static constexpr bool kCoherent = true; __device__ __forceinline__ void operator()() const {} };
 
 // This wave's share of rows [32*kb0, 32*kb1) of W: blocks kb0 + wave, kb0 + wave + NW, ...
 // The first PF weight blocks are requested before `sync()` runs and the activations after it, so
@@ -140,24 +140,12 @@ __device__ __forceinline__ void mma_range(f32x4_t (&acc)[MB][CPL], const bf16_t*
     WFrag<CPL> wf[PF];
     AFrag<AF32> af[PF][MB];
     int blk = kb0 + wave;
-    // The polling wave (wave 0) asks for its weights only after the wait: loads return in order, so
-    // a poll issued behind a long weight prefetch would see the counters late.
-    const bool early = !(Sync::kPolls && wave == 0);
-    if (early) {
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int bb = blk + NW * p;
-            if (bb < kb1) load_w<CPL>(wf[p], W, N, 32 * bb + 8 * g, col);
-        }
+    for (int p = 0; p < PF; ++p) {
+        const int bb = blk + NW * p;
+        if (bb < kb1) load_w<CPL>(wf[p], W, N, 32 * bb + 8 * g, col);
     }
     sync();
-    if (!early) {
-#pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int bb = blk + NW * p;
-            if (bb < kb1) load_w<CPL>(wf[p], W, N, 32 * bb + 8 * g, col);
-        }
-    }
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
         const int bb = blk + NW * p;
@@ -361,7 +349,6 @@ __device__ __forceinline__ void grid_arrive(uint32_t* slots) {
 
 struct GridWait {
     static constexpr bool kCoherent = true;
-    static constexpr bool kPolls = true;
     const uint32_t* slots;
     uint32_t grid;
     uint32_t* err;
