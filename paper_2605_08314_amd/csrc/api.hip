@@ -5,6 +5,7 @@
 #include <string.h>
 #include "lr_common.hpp"
 #include "decode.hpp"
+#include "prefill.hpp"
 
 namespace lr {
 
@@ -46,7 +47,6 @@ static inline int resolve_phase(int phase, int64_t M) {
 enum Plan { PLAN_GENERIC = 0, PLAN_DECODE = 1, PLAN_PREFILL = 2 };
 static const char* const kPlanNames[] = {"generic", "decode_mfma", "prefill_mfma"};
 
-bool prefill_shape_ok(int64_t M, int64_t K, int64_t N) { (void)M; (void)K; (void)N; return false; }
 
 // The tuned kernels are bf16-only and need 16-byte aligned operands; decode additionally needs
 // M <= 32.  A DECODE request with more rows, or a PREFILL request, goes to the prefill kernels
@@ -139,6 +139,7 @@ int lowrank_linear(const void* x, const void* U, const void* V, const void* bias
     const Plan plan = pick_plan(dtype, phase, M, decode_shape_ok(M, d_in, r) && decode_shape_ok(M, r, d_out),
                                 prefill_shape_ok(M, d_in, r) && prefill_shape_ok(M, r, d_out), al);
     if (plan == PLAN_DECODE) return decode_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
+    if (plan == PLAN_PREFILL) return prefill_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
     float* t = (float*)ws_layout(workspace, workspace_bytes).staging;
     CacheDst none = {nullptr, nullptr, 0, 1};
     st = generic_stage1(x, false, U, t, r, M, d_in, r, dtype, s);
@@ -202,6 +203,8 @@ int lowrank_qkv(const void* x, const void* const* U, const void* const* V, const
     const Plan plan = pick_plan(dtype, phase, M, dec, pre, al);
     if (plan == PLAN_DECODE)
         return decode_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, workspace_bytes, s);
+    if (plan == PLAN_PREFILL)
+        return prefill_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, workspace_bytes, s);
     float* t = (float*)ws_layout(workspace, workspace_bytes).staging;
     const int64_t ldt = R > 0 ? R : 1;
     for (int i = 0; i < n_proj; ++i)
@@ -241,6 +244,8 @@ int lowrank_packed_mlp(const void* x, const void* U_gu, const void* V_g, const v
     const Plan plan = pick_plan(dtype, phase, M, dec, pre, al);
     if (plan == PLAN_DECODE)
         return decode_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, workspace_bytes, s);
+    if (plan == PLAN_PREFILL)
+        return prefill_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, workspace_bytes, s);
     char* base = ws_layout(workspace, workspace_bytes).staging;
     float* t = (float*)base;                                   // [M, r_g + r_u + r_d]
     float* h = (float*)(base + align256((size_t)M * (size_t)r_total * 4));       // [M, ffn]
