@@ -28,6 +28,9 @@ sys.path.insert(0, ROOT)
 
 D, FFN, R_ATTN, R_MLP, HEADS, HEAD_DIM = 4096, 11008, 384, 768, 32, 128
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per decode-MLP launch at B=1 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
+# same counters read for the 256 MiB copy of --pmc-mode (profiles/decode_mlp_pmc_traffic.txt).
+MLP_TRAFFIC_BYTES = 74560292
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -101,6 +104,8 @@ def main():
     ap.add_argument("--prefill-rows", type=int, default=8192)
     ap.add_argument("--eager", action="store_true", help="plain launches instead of HIP-graph replay")
     ap.add_argument("--quick", action="store_true", help="skip the per-batch table, prefill and the CPU baseline")
+    ap.add_argument("--pmc-mode", action="store_true",
+                    help="for rocprofv3 --pmc runs: a 256 MiB plain copy (known traffic) and 32 eager decode-MLP launches, nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -114,6 +119,8 @@ def main():
     gen = torch.Generator(device="cuda")
     gen.manual_seed(260508314)
     L, Bt = args.layers, args.batch
+    if args.pmc_mode:
+        L = min(L, 8)
     layers = [Layer(torch, gen=gen) for _ in range(L)]
     S_max = 64
     bf = torch.bfloat16
@@ -149,6 +156,19 @@ def main():
             for op in ops:
                 op(buf, li)
 
+    if args.pmc_mode:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        buf = decode_buffers(Bt)
+        for _ in range(4):
+            B.lowrank_probe_copy(dst, src)
+        for _ in range(4):
+            sweep(buf, (op_mlp,))
+        torch.cuda.synchronize()
+        B.lowrank_workspace_status(buf["ws_mlp"])
+        print(json.dumps({"pmc_mode": True, "copy_bytes": 256 << 20, "mlp_launches": 4 * L, "mlp_bytes_per_launch": mlp_bytes(Bt)}))
+        return
+
     # ---- the timed step: exactly --steps passes over the L-layer stack at B = --batch.
     # The step's 3L launches are recorded once into a HIP graph and replayed (the paper's
     # per-layer graph replay, Section 3.1, is the same idea); --eager times plain launches.
@@ -176,10 +196,21 @@ def main():
     mlp_sweep = (lambda: sweep(buf, (op_mlp,))) if args.eager else capture(torch, lambda: sweep(buf, (op_mlp,)))
     mlp_ms = time_region(torch, mlp_sweep, max(3, args.steps // 2), 2) / L
     mlp_gbs = mlp_bytes(Bt) / (mlp_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "lowrank_packed_mlp decode (all stages of one call)",
+    # what a kernel that only streams a buffer of the same size reaches on this machine (context for `frac`)
+    big = torch.empty(L * mlp_bytes(Bt) // 16 * 16, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    per = mlp_bytes(Bt) // 16 * 16
+    slices = [big[i * per:(i + 1) * per] for i in range(L)]
+    def read_sweep():
+        for sl in slices:
+            B.lowrank_probe_read(sl, sink)
+    read_ms = time_region(torch, read_sweep if args.eager else capture(torch, read_sweep), max(3, args.steps // 2), 2) / L
+    del big, slices
+    roofline = {"bound": "hbm", "kernel": "lowrank_packed_mlp decode (k_decode_fused_mlp, all four stages of one call)",
                 "achieved": round(mlp_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(mlp_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                "bytes_per_launch": mlp_bytes(Bt), "us_per_launch": round(mlp_ms * 1e3, 2)}
+                "frac": round(mlp_gbs / HBM_PEAK_GBS, 4), "traffic": MLP_TRAFFIC_BYTES if Bt == 1 else None,
+                "bytes_per_launch": mlp_bytes(Bt), "us_per_launch": round(mlp_ms * 1e3, 2),
+                "stream_read_same_size_GBps": round(per / (read_ms * 1e-3) / 1e9, 1)}
 
     out = {
         "metric": "decode GB/s (% HBM peak) + prefill TFLOP/s, Llama-7B-shaped rank-r layers",

@@ -167,6 +167,16 @@ int lowrank_workspace_status(const void *workspace, void *stream);
 const char *lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
                               int dtype, int phase, int aligned);
 
+/*
+ * Measurement helpers (no part of the method): a kernel that only streams `bytes` (multiple of 16,
+ * 16-byte aligned) from src, and a plain copy.  bench.py times the first to report the streaming
+ * ceiling of the box at the size of a decode call; the second is the kernel of known traffic used
+ * to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters.  `sink` is a device word that is
+ * (practically) never written.
+ */
+int lowrank_probe_read(const void *src, size_t bytes, void *sink, void *stream);
+int lowrank_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 const char *lowrank_last_error(void);   /* thread-local, static storage, never NULL */
 const char *lowrank_version(void);
 

@@ -52,6 +52,10 @@ _lib.lowrank_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.lowrank_workspace_init.restype = _int
 _lib.lowrank_workspace_status.argtypes = [_vp, _vp]
 _lib.lowrank_workspace_status.restype = _int
+_lib.lowrank_probe_read.argtypes = [_vp, _sz, _vp, _vp]
+_lib.lowrank_probe_read.restype = _int
+_lib.lowrank_probe_copy.argtypes = [_vp, _vp, _sz, _vp]
+_lib.lowrank_probe_copy.restype = _int
 _lib.lowrank_plan_name.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int, _int]
 _lib.lowrank_plan_name.restype = ctypes.c_char_p
 _lib.lowrank_last_error.restype = ctypes.c_char_p
@@ -117,6 +121,14 @@ def lowrank_workspace_init(workspace: torch.Tensor, stream=None) -> None:
 def lowrank_workspace_status(workspace: torch.Tensor, stream=None) -> None:
     """Synchronises the stream; raises if a fused decode call on this workspace gave up waiting."""
     _check(_lib.lowrank_workspace_status(_ptr(workspace), _stream(stream)))
+
+
+def lowrank_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    _check(_lib.lowrank_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
+
+
+def lowrank_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    _check(_lib.lowrank_probe_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)))
 
 
 def new_workspace(op: int, M: int, d_in: int, r_total: int, d_out: int, dtype: int, phase="auto",

@@ -88,19 +88,29 @@ static int build_final(DStage& st, const Final* items, int n, int64_t ldt, int64
     return cpl;
 }
 
-// One launch per call unless LOWRANK_DECODE_FUSED=0 or the device query fails.
-static int fused_grid() {
+// One launch per call unless LOWRANK_DECODE_FUSED=0 or the device query fails.  The grid is one
+// workgroup per ~96 KB of factor bytes, between 64 and the number of CUs: a stage barrier costs more
+// the more workgroups take part, and a 6 MB call (one O projection) gains nothing from 256 of them
+// (measured: 8.1 us at 64 workgroups, 9.8 us at 256), while 18 MB and more want the whole chip.
+static int fused_grid(size_t factor_bytes) {
     if (env_int("LOWRANK_DECODE_FUSED", 1) == 0) return 0;
     const int cus = decode_resident_grid();
     if (cus <= 0) return 0;
     const int forced = env_int("LOWRANK_DECODE_GRID", 0);
-    return (forced > 0 && forced <= cus) ? forced : cus;
+    if (forced > 0 && forced <= cus) return forced;
+    size_t g = factor_bytes / (96u << 10);
+    if (g < 64) g = 64;
+    if (g > (size_t)cus) g = (size_t)cus;
+    return (int)g;
 }
 
 static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* sk_in, int nb, const Final* fin_in,
                          int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s) {
     const WsLayout L = ws_layout(ws, ws_bytes);
-    const int G = fused_grid();
+    size_t factor_bytes = 0;
+    for (int i = 0; i < nb; ++i) factor_bytes += (size_t)d_in * sk_in[i].N * 2;
+    for (int i = 0; i < nf; ++i) factor_bytes += (size_t)fin_in[i].r * fin_in[i].N * 2;
+    const int G = fused_grid(factor_bytes);
     const bool fused = G > 0 && (size_t)M * R * 4 <= L.acc_bytes;
     float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
     SplitK sk[kMaxProb]; Final fin[kMaxProb];
@@ -153,7 +163,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
                void* ws, size_t ws_bytes, hipStream_t s) {
     const int64_t r_gu = r_g + r_u, r_all = r_gu + r_d;
     const WsLayout L = ws_layout(ws, ws_bytes);
-    const int G = fused_grid();
+    const int G = fused_grid(((size_t)d * r_gu + (size_t)(r_g + r_u) * ffn + (size_t)ffn * r_d + (size_t)r_d * d) * 2);
     const bool fused = G > 0 && (size_t)M * r_all * 4 <= L.acc_bytes;
     // rank-space accumulators t[M, r_g + r_u + r_d] (fp32) and the bf16 hidden rows h[M, ffn]
     float* t = fused ? (float*)L.acc0 : (float*)L.staging;
