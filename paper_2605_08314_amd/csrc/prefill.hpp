@@ -22,7 +22,8 @@ struct PArgs {
     int nprob;
     int M;
     int tiles_m;        // ceil(M / BM)
-    int tiles_n_max;    // max over problems of N / 128
+    int tiles_n_max;    // max over problems of ceil(N / BN)
+    int group_m;        // tile rows per L2 group of the tile order
 };
 
 bool prefill_shape_ok(int64_t M, int64_t K, int64_t N);

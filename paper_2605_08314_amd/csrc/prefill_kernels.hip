@@ -1,6 +1,6 @@
 // Prefill-phase GEMM (bf16 MFMA, LDS-staged): C[M, N] = A[M, K] * B[K, N] with A, B, C row-major.
 //
-// Tile: BM x 128 x 64 per workgroup of 4 waves (2 x 2), each wave (BM/2) x 64 built from
+// Tile: BM x BN x 64 per workgroup of 4 waves (2 x 2), each wave (BM/2) x (BN/2) built from
 // v_mfma_f32_32x32x16_bf16.  Both operands sit in LDS "chunk-major": the 8 consecutive k of one
 // row are one 16-byte unit, units of one k-chunk are contiguous over rows (one pad unit every
 // 8 rows), so a fragment read (lane = row, 16 bytes) is linear and conflict-free.  A comes from
@@ -21,14 +21,16 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int PBN = 128, PBK = 64;
+constexpr int PBK = 64;
 
 __host__ __device__ constexpr int plane_units(int rows) { return rows + rows / 8 + 1; }
 __device__ __forceinline__ int unit_of(int plane, int chunk, int row) { return chunk * plane + row + (row >> 3); }
 
-template <int BM> constexpr int main_units() { return 8 * plane_units(BM) + 8 * plane_units(PBN); }
-template <int BM> constexpr int epi_units() { return BM * (PBN + 8) * 2 / 16; }
-template <int BM> constexpr int lds_units() { return main_units<BM>() > epi_units<BM>() ? main_units<BM>() : epi_units<BM>(); }
+template <int BM, int BN> constexpr int stage_units() { return 8 * plane_units(BM) + 8 * plane_units(BN); }
+template <int BM, int BN> constexpr int epi_bytes() { return BM * (BN + 4) * 2; }
+template <int BM, int BN> constexpr int lds_bytes() {
+    return stage_units<BM, BN>() * 16 > epi_bytes<BM, BN>() ? stage_units<BM, BN>() * 16 : epi_bytes<BM, BN>();
+}
 
 __device__ __forceinline__ uint32_t ppack2(float lo, float hi) {
     union { bf16x2_t v; uint32_t u; } x;
@@ -42,155 +44,224 @@ __device__ __forceinline__ bf16x8_t frag_of(const uint4& v) {
     return x.b;
 }
 
-// One K loop: acc[mi][ni] += (B tile)^T x (A tile)^T over k in [0, K).
-template <int BM>
-__device__ __forceinline__ void gemm_loop(f32x16_t (&acc)[BM / 64][2], const bf16_t* __restrict__ A, int lda,
-                                          const bf16_t* __restrict__ B, int N, int K, int M, int m0, int n0, uint4* lds) {
-    constexpr int MI = BM / 64;
-    constexpr int NA = BM / 32;                 // 16-byte chunks of A per thread and k-step
-    constexpr int PA = plane_units(BM), PB = plane_units(PBN);
-    uint4* As = lds;
-    uint4* Bs = lds + 8 * PA;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int li = lane & 31, lg = lane >> 5;
-    const int cg = tid & 15, rg = tid >> 4;     // B loader: column group (8 columns), row group (4 k-rows)
+__device__ __forceinline__ uint32_t dword_of(const uint4& v, int q) { return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w; }
 
-    uint4 ra[NA], rb[4];
-    auto load_tiles = [&](int k0) {
+// Global -> register loads of one k-step (64 k): NA 16-byte chunks of A per thread; of B, NR k-rows x 8
+// columns per thread (NR = BN / 32: the 256 threads cover 64 k-rows x BN columns).
+template <int NA, int NR, int BN>
+__device__ __forceinline__ void load_tiles(uint4 (&ra)[NA], uint4 (&rb)[NR], const bf16_t* __restrict__ A, int lda,
+                                           const bf16_t* __restrict__ B, int N, int M, int m0, int n0, int k0, int tid) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-            const int m = m0 + row;
-            if (m < M) ra[i] = *reinterpret_cast<const uint4*>(A + (size_t)m * lda + k0 + kc * 8);
-            else ra[i] = make_uint4(0u, 0u, 0u, 0u);
-        }
-        const bf16_t* bp = B + (size_t)(k0 + rg * 4) * N + n0 + cg * 8;
+    for (int i = 0; i < NA; ++i) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        const int m = m0 + row;
+        if (m < M) ra[i] = *reinterpret_cast<const uint4*>(A + (size_t)m * lda + k0 + kc * 8);
+        else ra[i] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    constexpr int CGS = BN / 8;                          // column groups of 8
+    const int cg = tid % CGS, rg = tid / CGS;            // rg: group of NR consecutive k-rows
+    const bf16_t* bp = B + (size_t)(k0 + rg * NR) * N + n0 + cg * 8;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) rb[a] = *reinterpret_cast<const uint4*>(bp + (size_t)a * N);
-    };
-    auto store_tiles = [&]() {
+    for (int a = 0; a < NR; ++a) rb[a] = *reinterpret_cast<const uint4*>(bp + (size_t)a * N);
+}
+
+// Registers -> LDS: A chunks as they are; B transposed inside the lane: the NR k-values of one column
+// become NR*2 contiguous bytes of that column's 16-byte unit.
+template <int NA, int NR, int BM, int BN>
+__device__ __forceinline__ void store_tiles(const uint4 (&ra)[NA], const uint4 (&rb)[NR], uint4* As, uint4* Bs, int tid) {
+    constexpr int PA = plane_units(BM), PB = plane_units(BN);
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-            As[unit_of(PA, kc, row)] = ra[i];
-        }
-        const uint32_t* r0 = reinterpret_cast<const uint32_t*>(&rb[0]);
-        const uint32_t* r1 = reinterpret_cast<const uint32_t*>(&rb[1]);
-        const uint32_t* r2 = reinterpret_cast<const uint32_t*>(&rb[2]);
-        const uint32_t* r3 = reinterpret_cast<const uint32_t*>(&rb[3]);
-        uint2* Bs2 = reinterpret_cast<uint2*>(Bs);
+    for (int i = 0; i < NA; ++i) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        As[unit_of(PA, kc, row)] = ra[i];
+    }
+    constexpr int CGS = BN / 8;
+    const int cg = tid % CGS, rg = tid / CGS;
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const uint32_t sel = (b & 1) ? 0x07060302u : 0x05040100u;
+    for (int b = 0; b < 8; ++b) {
+        const uint32_t sel = (b & 1) ? 0x07060302u : 0x05040100u;
+        if constexpr (NR == 8) {
+            uint4 v;
+            v.x = __builtin_amdgcn_perm(dword_of(rb[1], b >> 1), dword_of(rb[0], b >> 1), sel);
+            v.y = __builtin_amdgcn_perm(dword_of(rb[3], b >> 1), dword_of(rb[2], b >> 1), sel);
+            v.z = __builtin_amdgcn_perm(dword_of(rb[5], b >> 1), dword_of(rb[4], b >> 1), sel);
+            v.w = __builtin_amdgcn_perm(dword_of(rb[7], b >> 1), dword_of(rb[6], b >> 1), sel);
+            Bs[unit_of(PB, rg, cg * 8 + b)] = v;
+        } else {
             uint2 v;
-            v.x = __builtin_amdgcn_perm(r1[b >> 1], r0[b >> 1], sel);    // k rows 4rg+0, 4rg+1 of column b
-            v.y = __builtin_amdgcn_perm(r3[b >> 1], r2[b >> 1], sel);    // k rows 4rg+2, 4rg+3
-            Bs2[unit_of(PB, rg >> 1, cg * 8 + b) * 2 + (rg & 1)] = v;
-        }
-    };
-
-    const int nk = K / PBK;
-    load_tiles(0);
-    for (int kt = 0; kt < nk; ++kt) {
-        __syncthreads();                 // everyone finished reading the previous tile
-        store_tiles();
-        __syncthreads();
-        if (kt + 1 < nk) load_tiles((kt + 1) * PBK);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8_t af[MI], bf[2];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) af[mi] = frag_of(As[unit_of(PA, 2 * kk + lg, wm * (BM / 2) + mi * 32 + li)]);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) bf[ni] = frag_of(Bs[unit_of(PB, 2 * kk + lg, wn * 64 + ni * 32 + li)]);
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ni], af[mi], acc[mi][ni], 0, 0, 0);
+            v.x = __builtin_amdgcn_perm(dword_of(rb[1], b >> 1), dword_of(rb[0], b >> 1), sel);   // k rows 4rg+0, 4rg+1 of column b
+            v.y = __builtin_amdgcn_perm(dword_of(rb[3], b >> 1), dword_of(rb[2], b >> 1), sel);   // k rows 4rg+2, 4rg+3
+            reinterpret_cast<uint2*>(Bs)[unit_of(PB, rg >> 1, cg * 8 + b) * 2 + (rg & 1)] = v;
         }
     }
 }
 
-template <int BM, int EPI, int MINB>
-__global__ void __launch_bounds__(256, MINB) k_prefill_gemm(PArgs pa) {
-    constexpr int MI = BM / 64;
-    __shared__ uint4 lds[lds_units<BM>()];
-    // tile order: each XCD (workgroups are dealt round-robin to the 8 XCDs) walks a contiguous range
-    // of tiles, n fastest, so the A rows of a tile row stay in that XCD's L2 while B streams past.
-    const int per_prob = pa.tiles_m * pa.tiles_n_max;
-    const int total = per_prob * pa.nprob;
-    int id = blockIdx.x;
-    {
-        const int chunk = (total + 7) / 8;
-        const int swz = (id & 7) * chunk + (id >> 3);
-        if ((total & 7) == 0) id = swz;
-    }
-    const int prob = id / per_prob;
-    const int rem = id - prob * per_prob;
-    const int tm = rem / pa.tiles_n_max, tn = rem - tm * pa.tiles_n_max;
-    const PProb& P = pa.p[prob];
-    if (tn * PBN >= P.N) return;
-    const int m0 = tm * BM, n0 = tn * PBN, M = pa.M;
+template <int MI, int NI>
+__device__ __forceinline__ void load_frags(bf16x8_t (&af)[MI], bf16x8_t (&bf)[NI], const uint4* a_base, const uint4* b_base,
+                                           int a_step, int b_step) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) af[mi] = frag_of(a_base[a_step + mi * 36]);   // 32 rows = 36 units (pad every 8)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) bf[ni] = frag_of(b_base[b_step + ni * 36]);
+}
 
-    f32x16_t acc[MI][2];
+template <int MI, int NI>
+__device__ __forceinline__ void mma_step(f32x16_t (&acc)[MI][NI], const bf16x8_t (&af)[MI], const bf16x8_t (&bf)[NI]) {
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ni], af[mi], acc[mi][ni], 0, 0, 0);
+}
+
+// The matrix work of one k-step from the LDS stage at `st`.  Each sched_barrier pins the order
+// "reads of substep kk+1, then MFMAs of substep kk", so the fragments of the next substep are in
+// flight for a whole substep of matrix work.
+template <int BM, int BN>
+__device__ __forceinline__ void compute_stage(f32x16_t (&acc)[BM / 64][BN / 64], const uint4* st, int a_off, int b_off) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    constexpr int PA = plane_units(BM), PB = plane_units(BN);
+    const uint4* a_base = st + a_off;
+    const uint4* b_base = st + b_off;
+    bf16x8_t af0[MI], bf0[NI], af1[MI], bf1[NI];
+    load_frags<MI, NI>(af0, bf0, a_base, b_base, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags<MI, NI>(af1, bf1, a_base, b_base, 2 * PA, 2 * PB);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step<MI, NI>(acc, af0, bf0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags<MI, NI>(af0, bf0, a_base, b_base, 4 * PA, 4 * PB);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step<MI, NI>(acc, af1, bf1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags<MI, NI>(af1, bf1, a_base, b_base, 6 * PA, 6 * PB);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step<MI, NI>(acc, af0, bf0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step<MI, NI>(acc, af1, bf1);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// One K loop: acc[mi][ni] += (B tile)^T x (A tile)^T over k in [0, K).  One LDS buffer, two barriers
+// per k-step, global data of the next step prefetched into registers; two or three workgroups per
+// CU overlap each other's store phases.  (A two-buffer variant with one barrier per step and a
+// 256 x 256 tile were measured slower on this chip: 786 / 909 vs 941 TFLOP/s on an 8192^3 product.)
+template <int BM, int BN>
+__device__ __forceinline__ void gemm_loop(f32x16_t (&acc)[BM / 64][BN / 64], const bf16_t* __restrict__ A, int lda,
+                                          const bf16_t* __restrict__ B, int N, int K, int M, int m0, int n0, uint4* lds) {
+    constexpr int NA = BM / 32, NR = BN / 32;
+    constexpr int PA = plane_units(BM), PB = plane_units(BN);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lg = lane >> 5;
+    // fragment offsets of this lane for k-substep 0 (chunk lg); substep kk adds 2*kk planes
+    const int a_off = unit_of(PA, lg, wm * (BM / 2) + li);
+    const int b_off = 8 * PA + unit_of(PB, lg, wn * (BN / 2) + li);
+
+    uint4 ra[NA], rb[NR];
+    const int nk = K / PBK;
+    load_tiles<NA, NR, BN>(ra, rb, A, lda, B, N, M, m0, n0, 0, tid);
+    for (int kt = 0; kt < nk; ++kt) {
+        __syncthreads();                 // everyone finished reading the previous tile
+        store_tiles<NA, NR, BM, BN>(ra, rb, lds, lds + 8 * PA, tid);
+        __syncthreads();
+        if (kt + 1 < nk) load_tiles<NA, NR, BN>(ra, rb, A, lda, B, N, M, m0, n0, (kt + 1) * PBK, tid);
+        compute_stage<BM, BN>(acc, lds, a_off, b_off);
+    }
+}
+
+template <int BM, int BN, int EPI, int MINB>
+__global__ void __launch_bounds__(256, MINB) k_prefill_gemm(PArgs pa) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    __shared__ uint4 lds[lds_bytes<BM, BN>() / 16];
+    // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own 4 MB L2: workgroup
+    // id -> (id % 8) * total/8 + id / 8 gives every XCD a contiguous range of the logical order, and the
+    // logical order walks groups of pa.group_m tile rows column by column, so the workgroups that run
+    // together on one XCD share both a few A row-tiles and a few B column-tiles.
+    const int per_prob = pa.tiles_m * pa.tiles_n_max;
+    const int total = per_prob * pa.nprob;
+    int id = blockIdx.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int prob = id / per_prob;
+    const int rem = id - prob * per_prob;
+    const int gsz = pa.group_m * pa.tiles_n_max;
+    const int mg = rem / gsz, r = rem - mg * gsz;
+    const int rows_here = (pa.tiles_m - mg * pa.group_m) < pa.group_m ? (pa.tiles_m - mg * pa.group_m) : pa.group_m;
+    const int tn = r / rows_here, tm = mg * pa.group_m + (r - tn * rows_here);
+    const PProb& P = pa.p[prob];
+    if (tn * BN >= P.N) return;
+    const int m0 = tm * BM, n0 = tn * BN, M = pa.M;
+
+    f32x16_t acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-    gemm_loop<BM>(acc, P.A, P.lda, P.B, P.N, P.K, M, m0, n0, lds);
+    gemm_loop<BM, BN>(acc, P.A, P.lda, P.B, P.N, P.K, M, m0, n0, lds);
 
-    f32x16_t acc2[(EPI == PEPI_GATEUP) ? MI : 1][2];
+    f32x16_t acc2[(EPI == PEPI_GATEUP) ? MI : 1][(EPI == PEPI_GATEUP) ? NI : 1];
     if constexpr (EPI == PEPI_GATEUP) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc2[mi][ni][v] = 0.f;
-        gemm_loop<BM>(acc2, P.A2, P.lda2, P.B2, P.N, P.K2, M, m0, n0, lds);
+        gemm_loop<BM, BN>(acc2, P.A2, P.lda2, P.B2, P.N, P.K2, M, m0, n0, lds);
     }
 
     // ---- epilogue: registers -> bf16 staging tile in LDS -> coalesced 16-byte row stores
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1, li = lane & 31, lg = lane >> 5;
-    constexpr int CS = PBN + 8;                       // staging row stride in bf16
+    constexpr int CS = BN + 4;                        // staging row stride in bf16: 8-byte lanes of a wave sweep the banks
     __syncthreads();                                  // main-loop LDS no longer needed
     bf16_t* Cs = reinterpret_cast<bf16_t*>(lds);
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int vg = 0; vg < 4; ++vg) {
+            const int col = wn * (BN / 2) + ni * 32 + 8 * vg + 4 * lg;    // first of this lane's 4 consecutive columns
+            float bg[4] = {0.f, 0.f, 0.f, 0.f}, bu[4] = {0.f, 0.f, 0.f, 0.f};
+            if (P.bias) {
+                const uint2 raw = *reinterpret_cast<const uint2*>(P.bias + n0 + col);
+                bg[0] = __uint_as_float(raw.x << 16); bg[1] = __uint_as_float(raw.x & 0xffff0000u);
+                bg[2] = __uint_as_float(raw.y << 16); bg[3] = __uint_as_float(raw.y & 0xffff0000u);
+            }
+            if constexpr (EPI == PEPI_GATEUP) {
+                if (P.bias2) {
+                    const uint2 raw = *reinterpret_cast<const uint2*>(P.bias2 + n0 + col);
+                    bu[0] = __uint_as_float(raw.x << 16); bu[1] = __uint_as_float(raw.x & 0xffff0000u);
+                    bu[2] = __uint_as_float(raw.y << 16); bu[3] = __uint_as_float(raw.y & 0xffff0000u);
+                }
+            }
 #pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-                const int row = wm * (BM / 2) + mi * 32 + li;                 // token row inside the tile
-                const int col = wn * 64 + ni * 32 + 8 * vg + 4 * lg;          // first of 4 consecutive columns
+            for (int mi = 0; mi < MI; ++mi) {
+                const int row = wm * (BM / 2) + mi * 32 + li;             // token row inside the tile
                 float v[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][4 * vg + e];
-                if constexpr (EPI == PEPI_GATEUP) {
-                    float bg[4] = {0.f, 0.f, 0.f, 0.f}, bu[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (P.bias) { for (int e = 0; e < 4; ++e) bg[e] = bf16_to_f32(P.bias[n0 + col + e]); }
-                    if (P.bias2) { for (int e = 0; e < 4; ++e) bu[e] = bf16_to_f32(P.bias2[n0 + col + e]); }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = silu_f32(v[e] + bg[e]) * (acc2[mi][ni][4 * vg + e] + bu[e]);
-                } else {
-                    if (P.bias) { for (int e = 0; e < 4; ++e) v[e] += bf16_to_f32(P.bias[n0 + col + e]); }
+                for (int e = 0; e < 4; ++e) {
+                    if constexpr (EPI == PEPI_GATEUP)
+                        v[e] = silu_f32(acc[mi][ni][4 * vg + e] + bg[e]) * (acc2[mi][ni][4 * vg + e] + bu[e]);
+                    else
+                        v[e] = acc[mi][ni][4 * vg + e] + bg[e];
                 }
                 uint2 o; o.x = ppack2(v[0], v[1]); o.y = ppack2(v[2], v[3]);
                 *reinterpret_cast<uint2*>(Cs + row * CS + col) = o;
             }
+        }
     __syncthreads();
-    constexpr int CHUNKS = BM * (PBN / 8);            // 16-byte chunks in the tile
+    constexpr int CPR = BN / 8;                       // 16-byte chunks per tile row
+    constexpr int CHUNKS = BM * CPR;
 #pragma unroll 4
     for (int c = tid; c < CHUNKS; c += 256) {
-        const int row = c >> 4, ch = c & 15;
+        const int row = c / CPR, ch = c % CPR;
         const int m = m0 + row;
         if (m >= M) continue;
-        const uint4 val = *reinterpret_cast<const uint4*>(Cs + row * CS + ch * 8);
+        const uint2 lo = *reinterpret_cast<const uint2*>(Cs + row * CS + ch * 8);
+        const uint2 hi = *reinterpret_cast<const uint2*>(Cs + row * CS + ch * 8 + 4);
+        const uint4 val = make_uint4(lo.x, lo.y, hi.x, hi.y);
         if (P.C) *reinterpret_cast<uint4*>(P.C + (size_t)m * P.ldc + n0 + ch * 8) = val;
         if constexpr (EPI == PEPI_STORE) {
             if (P.cache) {
@@ -209,37 +280,38 @@ bool prefill_shape_ok(int64_t M, int64_t K, int64_t N) {
            K < (1 << 24) && N < (1 << 24);
 }
 
-template <int BM, int EPI, int MINB>
+template <int BM, int BN, int EPI, int MINB>
 static int launch_cfg(PArgs a, hipStream_t s) {
     a.tiles_m = (a.M + BM - 1) / BM;
+    a.tiles_n_max = 0;
+    for (int i = 0; i < a.nprob; ++i) { const int t = (a.p[i].N + BN - 1) / BN; if (t > a.tiles_n_max) a.tiles_n_max = t; }
     const int total = a.tiles_m * a.tiles_n_max * a.nprob;
-    hipLaunchKernelGGL((k_prefill_gemm<BM, EPI, MINB>), dim3((unsigned)total), dim3(256), 0, s, a);
+    a.group_m = 8;
+    hipLaunchKernelGGL((k_prefill_gemm<BM, BN, EPI, MINB>), dim3((unsigned)total), dim3(256), 0, s, a);
     return launch_status("prefill gemm");
 }
 
-// BM = 256 unless that leaves the 256 CUs visibly under-filled (few tiles) and 128 fills them better.
-static int pick_bm(const PArgs& a, int force) {
-    if (force == 128 || force == 256) return force;
-    auto waste = [&](int bm) {
-        const long tiles = (long)((a.M + bm - 1) / bm) * a.tiles_n_max * a.nprob;
-        const long slots = 256L * (bm == 128 ? 2 : 2);    // resident tiles per round
-        const long rounds = (tiles + slots - 1) / slots;
-        return (double)(rounds * slots) / (double)tiles * (bm == 128 ? 1.15 : 1.0);   // 128-row tiles reuse B less
-    };
-    return waste(128) < waste(256) ? 128 : 256;
+static int env_shape() {
+    static int force = -2;
+    if (force == -2) { const char* v = getenv("LOWRANK_PREFILL_SHAPE"); force = v ? atoi(v) : -1; }
+    return force;
+}
+
+// Tile shape of a plain launch: 256 x 128 tiles (more reuse per LDS byte; measured 941 vs 856 TFLOP/s
+// on an 8192^3 product) when they still give every CU several rounds of work, else 128 x 128
+// (three workgroups per CU, less idle tail on the small-N rank-space products).
+static bool want_bm256(const PArgs& a) {
+    long tiles = 0;
+    for (int i = 0; i < a.nprob; ++i) tiles += (long)((a.M + 255) / 256) * (a.p[i].N / 128);
+    return tiles >= 4 * 512;
 }
 
 int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
     if (a.M <= 0 || a.nprob <= 0) return LR_OK;
-    static int force_bm = -1;
-    if (force_bm < 0) { const char* v = getenv("LOWRANK_PREFILL_BM"); force_bm = v ? atoi(v) : 0; }
-    if (epi == PEPI_GATEUP) {
-        const int bm = (force_bm == 256) ? 256 : 128;
-        if (bm == 256) return launch_cfg<256, PEPI_GATEUP, 1>(a, s);
-        return launch_cfg<128, PEPI_GATEUP, 2>(a, s);
-    }
-    if (pick_bm(a, force_bm) == 128) return launch_cfg<128, PEPI_STORE, 2>(a, s);
-    return launch_cfg<256, PEPI_STORE, 2>(a, s);
+    const int force = env_shape();
+    if (epi == PEPI_GATEUP) return launch_cfg<128, 128, PEPI_GATEUP, 2>(a, s);
+    if (force == 1 || (force != 2 && want_bm256(a))) return launch_cfg<256, 128, PEPI_STORE, 2>(a, s);
+    return launch_cfg<128, 128, PEPI_STORE, 2>(a, s);
 }
 
 }  // namespace lr
