@@ -16,6 +16,8 @@ struct DProb {
     bf16_t* Y;                                              // EPI_STORE / EPI_GATEUP: bf16 output [M, N] (nullable for STORE)
     const bf16_t* bias; const bf16_t* bias2;
     void* cache; const int32_t* pos; int S_max; int T;      // EPI_STORE: optional dense-cache scatter
+    int ldy;          // EPI_ATOMIC with bf16 finalisation: row stride of Y (the bf16 copy of the accumulator)
+    int ctile_begin;  // EPI_ATOMIC with bf16 finalisation: index of this product's first column-tile counter
     int tiles_n;      // column tiles (N / NC)
     int KS;           // rows of W per tile (multiple of 32); tiles along K = ceil(K / KS)
     int tile_begin;   // first tile index of this product inside the stage
@@ -31,12 +33,14 @@ typedef DStageT<kMaxProb> DStage;
 constexpr int kBarriers = 3;
 constexpr int kSlots = 16;
 constexpr int kSlotStride = 32;   // uint32 words between slots (128 bytes)
+constexpr int kTileCounters = 256;
 struct Ctrl {
     uint32_t epoch;                     // number of fused calls completed on this workspace
     uint32_t error;                     // nonzero: a bounded device-side wait gave up
     uint32_t dirty[2];                  // floats of accumulator area p that are not zero
     uint32_t pad[28];
     uint32_t cnt[2][kBarriers][kSlots * kSlotStride];   // [epoch parity][barrier][slot]
+    uint32_t tcnt[2][kTileCounters];                    // arrivals per accumulator column tile (bf16 finalisation)
 };
 static_assert(sizeof(Ctrl) <= kHeaderBytes, "control block must fit the workspace header");
 
@@ -68,8 +72,8 @@ struct FusedMlpArgs { FusedCommon fc; DStageT<1> a, b, c, d; };
 // Fused launches (all stages in one kernel, `grid` resident workgroups of nw = 4 or 8 waves).  cpl* = columns per lane
 // of each stage.  Return LR_ERR_UNSUPPORTED if the grid would not be fully resident.
 int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int cpl1, int cpl2,
-                         int grid, int nw, hipStream_t s);
-int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, int nw, hipStream_t s);
+                         int grid, int nw, bool t16, hipStream_t s);
+int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, int nw, bool t16, hipStream_t s);
 extern unsigned long long* g_trace_buffer;   // host copy of the trace pointer (NULL unless a trace build set it)
 int decode_resident_grid();   // workgroups that are certainly co-resident (number of CUs), cached
 

@@ -126,9 +126,14 @@ __device__ __forceinline__ void mma_block(f32x4_t (&acc)[MB][CPL], const WFrag<C
 }
 
 // Hook run between the first weight loads of a tile and its first activation loads.
-struct NoSync { static constexpr bool kCoherent = false; __device__ __forceinline__ void operator()() const {} };
+// kCoherent: the activation rows were produced earlier in this launch by other workgroups and are read with
+// agent-coherent loads; kFused: hidden rows written by this tile are read by other workgroups of this launch.
+struct NoSync { static constexpr bool kCoherent = false, kFused = false; __device__ __forceinline__ void operator()() const {} };
 // Same, for later tiles of a stage whose input other workgroups of this launch produced.
-struct NoSyncCoherent { static constexpr bool kCoherent = true; __device__ __forceinline__ void operator()() const {} };
+struct NoSyncCoherent { static constexpr bool kCoherent = true, kFused = true; __device__ __forceinline__ void operator()() const {} };
+// Later tiles of a stage whose input is a finalised bf16 copy that no workgroup on this XCD has read yet in
+// this launch: plain cached loads are safe (first touch misses L2) and let the other workgroups hit in L2.
+struct NoSyncPlain { static constexpr bool kCoherent = false, kFused = true; __device__ __forceinline__ void operator()() const {} };
 
 // This wave's share of rows [32*kb0, 32*kb1) of W: blocks kb0 + wave, kb0 + wave + NW, ...
 // The first PF weight blocks are requested before `sync()` runs and the activations after it, so
@@ -191,7 +196,7 @@ __device__ __forceinline__ void load_bf16_row(float (&v)[CPL], const bf16_t* src
 // One workgroup tile, from loads to epilogue.  `red` is LDS scratch of red_floats<...>() floats.
 template <int MB, int CPL, bool AF32, int EPI, int PF, int NW, class Sync>
 __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float4* __restrict__ red,
-                                            const Sync& sync, size_t acc_shift) {
+                                            const Sync& sync, size_t acc_shift, uint32_t* tcnt = nullptr) {
     constexpr int NMAT = (EPI == EPI_GATEUP) ? 2 : 1;
     constexpr int NC = 16 * CPL;
     constexpr int Q = CPL / 4;
@@ -218,6 +223,7 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
     if constexpr (NMAT == 2) {
         const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
         if constexpr (Sync::kCoherent) mma_range<MB, CPL, AF32, PF, NW>(acc[1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncCoherent());
+        else if constexpr (Sync::kFused) mma_range<MB, CPL, AF32, PF, NW>(acc[1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncPlain());
         else mma_range<MB, CPL, AF32, PF, NW>(acc[1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSync());
     }
 
@@ -235,6 +241,7 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
                         make_float4(acc[mt][mb][4 * q + 0][v], acc[mt][mb][4 * q + 1][v],
                                     acc[mt][mb][4 * q + 2][v], acc[mt][mb][4 * q + 3][v]);
     __syncthreads();
+    float atomic_returns = 0.f;
 #pragma unroll
     for (int pidx = tid; pidx < 256 * MB; pidx += 64 * NW) {   // (mb, v, lane') triples
         const int sl = pidx >> 6, ln = pidx & 63;
@@ -256,9 +263,12 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
             }
         if (m < M) {
             if constexpr (EPI == EPI_ATOMIC) {
+                // RETURNING atomics: a non-returning one is acknowledged as soon as the L2 has accepted it,
+                // before it is performed where other XCDs can see it; its return value only exists once it
+                // has been performed, and consuming the values below orders them before the arrival signal.
                 float* c = (float*)((char*)P.C + acc_shift) + (size_t)m * P.ldc + n;
 #pragma unroll
-                for (int b = 0; b < CPL; ++b) unsafeAtomicAdd(c + b, val[0][b]);
+                for (int b = 0; b < CPL; ++b) atomic_returns += unsafeAtomicAdd(c + b, val[0][b]);
             } else if constexpr (EPI == EPI_STORE) {
                 if (P.bias) {
                     float bv[CPL];
@@ -282,10 +292,38 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
                 if (P.bias2) load_bf16_row<CPL>(bu, P.bias2 + n);
 #pragma unroll
                 for (int b = 0; b < CPL; ++b) hv[b] = silu_f32(val[0][b] + bg[b]) * (val[NMAT - 1][b] + bu[b]);
-                if constexpr (CPL == 4 && Sync::kCoherent) {   // fused launch: another workgroup reads h next
+                if constexpr (CPL == 4 && Sync::kFused) {   // fused launch: another workgroup reads h next
                     st_coherent_b64(P.Y + (size_t)m * P.N + n, make_uint2(pack2(hv[0], hv[1]), pack2(hv[2], hv[3])));
                 } else {
                     store_bf16_row<CPL>(P.Y + (size_t)m * P.N + n, hv);
+                }
+            }
+        }
+    }
+    if constexpr (EPI == EPI_ATOMIC) asm volatile("" ::"v"(atomic_returns));   // every atomic above has returned
+
+    // bf16 finalisation of a split-K accumulator tile (more than 8 token rows): the workgroup that adds the
+    // last K-slice of this column tile converts the finished fp32 tile to bf16 once, so that the next stage's
+    // workgroups read half the bytes with plain cached loads instead of each converting the whole of t.
+    if constexpr (EPI == EPI_ATOMIC) {
+        if (tcnt) {
+            __shared__ uint32_t s_last;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // this wave's atomics have been performed
+            __syncthreads();
+            if (tid == 0) {
+                const uint32_t slices = (uint32_t)((P.K + P.KS - 1) / P.KS);
+                const uint32_t old = __hip_atomic_fetch_add(tcnt + P.ctile_begin + tn, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_last = (old == slices - 1u) ? 1u : 0u;
+            }
+            __syncthreads();
+            if (s_last) {
+                const float* src0 = (const float*)((const char*)P.C + acc_shift);
+                for (int it = tid; it < M * (NC / 4); it += 64 * NW) {
+                    const int m = it / (NC / 4), n = n0 + 4 * (it % (NC / 4));
+                    const float* src = src0 + (size_t)m * P.ldc + n;
+                    const uint2 a = ld_coherent_b64(src), b = ld_coherent_b64(src + 2);
+                    st_coherent_b64(P.Y + (size_t)m * P.ldy + n,
+                                    make_uint2(pack2(__uint_as_float(a.x), __uint_as_float(a.y)), pack2(__uint_as_float(b.x), __uint_as_float(b.y))));
                 }
             }
         }
@@ -348,7 +386,7 @@ __device__ __forceinline__ void grid_arrive(uint32_t* slots) {
 }
 
 struct GridWait {
-    static constexpr bool kCoherent = true;
+    static constexpr bool kCoherent = true, kFused = true;
     const uint32_t* slots;
     uint32_t grid;
     uint32_t* err;
@@ -375,6 +413,12 @@ struct GridWait {
     }
 };
 
+// The same wait in front of a stage that reads a finalised bf16 copy with plain loads.
+struct GridWaitPlain : GridWait {
+    static constexpr bool kCoherent = false, kFused = true;
+    __device__ __forceinline__ GridWaitPlain(const GridWait& g) : GridWait(g) {}
+};
+
 // Start of every fused kernel: ONE 16-byte read of {epoch, error, dirty[0], dirty[1]}; nothing waits
 // on it until the first epilogue needs the parity.
 struct CtrlSnap { uint32_t epoch, p, dirty_other; };
@@ -394,9 +438,11 @@ __device__ __forceinline__ void fused_clear_other(const FusedCommon& fc, const C
     float4* other = reinterpret_cast<float4*>(fc.acc0 + (size_t)(1u - c.p) * fc.acc_bytes);
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += gridDim.x * blockDim.x)
         other[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (blockIdx.x == 0)
+    if (blockIdx.x == 0) {
         for (uint32_t i = threadIdx.x; i < (uint32_t)(kBarriers * kSlots); i += blockDim.x)
             fc.ctrl->cnt[1u - c.p][i / kSlots][(i % kSlots) * kSlotStride] = 0u;
+        for (uint32_t i = threadIdx.x; i < (uint32_t)kTileCounters; i += blockDim.x) fc.ctrl->tcnt[1u - c.p][i] = 0u;
+    }
 }
 
 // First barrier of a fused kernel: every workgroup clears its share of the other accumulator area,
@@ -426,7 +472,7 @@ __device__ __forceinline__ const DProb& find_prob(const DStageT<NP>& st, int til
 }
 
 // lowrank_linear / lowrank_qkv: t += x U (split-K, atomics)  ->  barrier  ->  y = t V (+bias, cache).
-template <int MB, int CPL1, int CPL2, int PF, int NP, int NW>
+template <int MB, int CPL1, int CPL2, int PF, int NP, int NW, bool T16>
 __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     constexpr int R1 = red_float4s<MB, CPL1, EPI_ATOMIC, NW>(), R2 = red_float4s<MB, CPL2, EPI_STORE, NW>();
     __shared__ float4 red[R1 > R2 ? R1 : R2];
@@ -435,7 +481,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     const size_t shift = (size_t)p * fa.fc.acc_bytes;
     for (int tile = blockIdx.x; tile < fa.s1.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s1, tile);
-        decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift);
+        decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift,
+                                                         T16 ? fa.fc.ctrl->tcnt[p] : nullptr);
         __syncthreads();
     }
     fused_first_arrive(fa.fc, cs);
@@ -443,8 +490,13 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     bool waited = false;
     for (int tile = blockIdx.x; tile < fa.s2.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s2, tile);
-        if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, gw, shift);
-        else         decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncCoherent(), shift);
+        if constexpr (T16) {
+            if (!waited) decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift);
+            else         decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift);
+        } else {
+            if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, gw, shift);
+            else         decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncCoherent(), shift);
+        }
         if (!waited) fused_publish(fa.fc, cs);
         waited = true;
         __syncthreads();
@@ -453,7 +505,7 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
 }
 
 // lowrank_packed_mlp: four stages, three barriers.
-template <int MB, int CPLA, int CPLC, int CPLD, int PF, int NW>
+template <int MB, int CPLA, int CPLC, int CPLD, int PF, int NW, bool T16>
 __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
     constexpr int RA = red_float4s<MB, CPLA, EPI_ATOMIC, NW>(), RB = red_float4s<MB, 4, EPI_GATEUP, NW>();
     constexpr int RC = red_float4s<MB, CPLC, EPI_ATOMIC, NW>(), RD = red_float4s<MB, CPLD, EPI_STORE, NW>();
@@ -467,7 +519,7 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
     LR_STAMP(0);
     // A: t_gu += x U_gu
     for (int tile = blockIdx.x; tile < fa.a.total_tiles; tile += G) {
-        decode_tile<MB, CPLA, false, EPI_ATOMIC, PF, NW>(fa.a.p[0], fa.a.M, tile, red, NoSync(), shift);
+        decode_tile<MB, CPLA, false, EPI_ATOMIC, PF, NW>(fa.a.p[0], fa.a.M, tile, red, NoSync(), shift, T16 ? fa.fc.ctrl->tcnt[p] : nullptr);
         __syncthreads();
     }
     LR_STAMP(1);
@@ -478,8 +530,13 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
         const GridWait gw = {cnt[0], G, &fa.fc.ctrl->error, 3, fa.fc.trace};
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.b.total_tiles; tile += G) {
-            if (!waited) decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, gw, shift);
-            else         decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncCoherent(), shift);
+            if constexpr (T16) {
+                if (!waited) decode_tile<MB, 4, false, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, GridWaitPlain(gw), shift);
+                else         decode_tile<MB, 4, false, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncPlain(), shift);
+            } else {
+                if (!waited) decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, gw, shift);
+                else         decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncCoherent(), shift);
+            }
             if (!waited) fused_publish(fa.fc, cs);
             waited = true;
             __syncthreads();
@@ -494,8 +551,9 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
         const GridWait gw = {cnt[1], G, &fa.fc.ctrl->error, 6, fa.fc.trace};
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.c.total_tiles; tile += G) {
-            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, gw, shift);
-            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncCoherent(), shift);
+            uint32_t* tc = T16 ? fa.fc.ctrl->tcnt[p] : nullptr;
+            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, gw, shift, tc);
+            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncCoherent(), shift, tc);
             waited = true;
             __syncthreads();
         }
@@ -508,8 +566,13 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
         const GridWait gw = {cnt[2], G, &fa.fc.ctrl->error, 9, fa.fc.trace};
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.d.total_tiles; tile += G) {
-            if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, gw, shift);
-            else         decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncCoherent(), shift);
+            if constexpr (T16) {
+                if (!waited) decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift);
+                else         decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift);
+            } else {
+                if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, gw, shift);
+                else         decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncCoherent(), shift);
+            }
             waited = true;
             __syncthreads();
         }

@@ -4,23 +4,28 @@
 namespace lr {
 
 template <int MB, int CA, int CC, int CD>
-static int launch_mlp(const FusedMlpArgs& fa, int grid, int nw, hipStream_t s) {
-    if (nw == 8) hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 8>), dim3((unsigned)grid), dim3(512), 0, s, fa);
-    else hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 4>), dim3((unsigned)grid), dim3(256), 0, s, fa);
+static int launch_mlp(const FusedMlpArgs& fa, int grid, int nw, bool t16, hipStream_t s) {
+    if (t16) {
+        if (nw == 8) hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 8, true>), dim3((unsigned)grid), dim3(512), 0, s, fa);
+        else hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 4, true>), dim3((unsigned)grid), dim3(256), 0, s, fa);
+    } else {
+        if (nw == 8) hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 8, false>), dim3((unsigned)grid), dim3(512), 0, s, fa);
+        else hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 4, false>), dim3((unsigned)grid), dim3(256), 0, s, fa);
+    }
     return launch_status("fused decode (packed MLP)");
 }
 
 template <int MB>
-static int launch_mlp_cpl(const FusedMlpArgs& fa, int ca, int cc, int cd, int grid, int nw, hipStream_t s) {
+static int launch_mlp_cpl(const FusedMlpArgs& fa, int ca, int cc, int cd, int grid, int nw, bool t16, hipStream_t s) {
     if (cd != 4 || ca != cc) { set_error("bad decode tile configuration"); return LR_ERR_UNSUPPORTED; }
-    if (ca == 8) return launch_mlp<MB, 8, 8, 4>(fa, grid, nw, s);
-    return launch_mlp<MB, 4, 4, 4>(fa, grid, nw, s);
+    if (ca == 8) return launch_mlp<MB, 8, 8, 4>(fa, grid, nw, t16, s);
+    return launch_mlp<MB, 4, 4, 4>(fa, grid, nw, t16, s);
 }
 
-int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, int nw, hipStream_t s) {
+int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, int nw, bool t16, hipStream_t s) {
     if (fa.a.M <= 0) return LR_OK;
-    if (fa.a.M <= 16) return launch_mlp_cpl<1>(fa, cpl_a, cpl_c, cpl_d, grid, nw, s);
-    return launch_mlp_cpl<2>(fa, cpl_a, cpl_c, cpl_d, grid, nw, s);
+    if (fa.a.M <= 16) return launch_mlp_cpl<1>(fa, cpl_a, cpl_c, cpl_d, grid, nw, t16, s);
+    return launch_mlp_cpl<2>(fa, cpl_a, cpl_c, cpl_d, grid, nw, t16, s);
 }
 
 }  // namespace lr

@@ -48,12 +48,12 @@ static int pick_ks(int64_t K, int64_t tiles_n_total, int64_t M, int64_t want_til
 
 static void zero_prob(DProb& p) { memset(&p, 0, sizeof(p)); p.T = 1; }
 
-struct SplitK { const void* W; int64_t N; float* C; };
-struct Final { const float* T; int64_t r; const void* V; int64_t N; const void* bias; void* Y; CacheDst cd; };
+struct SplitK { const void* W; int64_t N; float* C; bf16_t* T16; };   // T16: bf16 copy of C made by the last K-slice (or NULL)
+struct Final { const void* T; int64_t r; const void* V; int64_t N; const void* bias; void* Y; CacheDst cd; };   // T: fp32 or bf16 rank-space rows
 
 // t[M, ldc] += A[M, K] * W_i[K, N_i] for several weight matrices sharing A, split along K.
 static void build_splitk(DStage& st, const void* A, int64_t lda, int64_t M, int64_t K, const SplitK* items, int n,
-                         int64_t ldc, int64_t want_tiles, int cpl) {
+                         int64_t ldc, int64_t want_tiles, int cpl, int* ctile_next) {
     st.nprob = n; st.M = (int)M;
     int64_t n_all = 0;
     for (int i = 0; i < n; ++i) n_all += items[i].N;
@@ -65,6 +65,7 @@ static void build_splitk(DStage& st, const void* A, int64_t lda, int64_t M, int6
         DProb& p = st.p[i]; zero_prob(p);
         p.W = (const bf16_t*)items[i].W; p.A = A; p.K = (int)K; p.lda = (int)lda; p.N = (int)items[i].N;
         p.C = items[i].C; p.ldc = (int)ldc; p.tiles_n = (int)(items[i].N / nc); p.KS = ks; p.tile_begin = tile;
+        p.Y = items[i].T16; p.ldy = (int)ldc; p.ctile_begin = *ctile_next; *ctile_next += p.tiles_n;
         tile += p.tiles_n * tk;
     }
     st.total_tiles = tile;
@@ -104,6 +105,12 @@ static int fused_grid(size_t factor_bytes) {
     return (int)g;
 }
 
+// More than 8 token rows: split-K accumulators are finalised to bf16 once (see decode_tile) instead of
+// every consumer workgroup converting all of t.
+static bool use_t16(int64_t M, int64_t col_tiles) {
+    return M > 8 && col_tiles <= kTileCounters && env_int("LOWRANK_DECODE_T16", 1) != 0;
+}
+
 static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* sk_in, int nb, const Final* fin_in,
                          int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s) {
     const WsLayout L = ws_layout(ws, ws_bytes);
@@ -112,19 +119,29 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
     for (int i = 0; i < nf; ++i) factor_bytes += (size_t)fin_in[i].r * fin_in[i].N * 2;
     const int G = fused_grid(factor_bytes);
     const bool fused = G > 0 && (size_t)M * R * 4 <= L.acc_bytes;
-    float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
-    SplitK sk[kMaxProb]; Final fin[kMaxProb];
-    for (int i = 0; i < nb; ++i) { sk[i] = sk_in[i]; sk[i].C = tbase + (size_t)(uintptr_t)sk_in[i].C; }      // C, T hold float offsets
-    for (int i = 0; i < nf; ++i) { fin[i] = fin_in[i]; fin[i].T = tbase + (size_t)(uintptr_t)fin_in[i].T; }
-    DStage s1, s2;
     bool all128 = true;
-    for (int i = 0; i < nb; ++i) all128 = all128 && (sk[i].N % 128 == 0);
+    for (int i = 0; i < nb; ++i) all128 = all128 && (sk_in[i].N % 128 == 0);
     const int c1 = pick_cpl(all128);
-    build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : env_int("LOWRANK_DECODE_TILES", 512), c1);
+    const bool t16 = fused && use_t16(M, R / (16 * c1));
+    float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
+    bf16_t* t16base = (bf16_t*)L.staging;                       // [M, R] bf16 (fused launches only)
+    SplitK sk[kMaxProb]; Final fin[kMaxProb];
+    // the callers pass the column offset of each product inside t as the pointer value of C / T
+    for (int i = 0; i < nb; ++i) {
+        const size_t off = (size_t)(uintptr_t)sk_in[i].C;
+        sk[i] = sk_in[i]; sk[i].C = tbase + off; sk[i].T16 = t16 ? t16base + off : nullptr;
+    }
+    for (int i = 0; i < nf; ++i) {
+        const size_t off = (size_t)(uintptr_t)fin_in[i].T;
+        fin[i] = fin_in[i]; fin[i].T = t16 ? (const void*)(t16base + off) : (const void*)(tbase + off);
+    }
+    DStage s1, s2;
+    int ctile = 0;
+    build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : env_int("LOWRANK_DECODE_TILES", 512), c1, &ctile);
     const int c2 = build_final(s2, fin, nf, R, M);
     if (fused) {
         FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, (uint32_t)(M * R), 0u, g_trace_buffer};
-        return decode_launch_fused2(fc, s1, s2, c1, c2, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, s);
+        return decode_launch_fused2(fc, s1, s2, c1, c2, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, t16, s);
     }
     int st = fill_zero(tbase, (size_t)M * R * 4, s);
     if (st != LR_OK) return st;
@@ -135,8 +152,8 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
 
 int decode_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
                   int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s) {
-    SplitK sk = {U, r, (float*)0};
-    Final f = {(const float*)0, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
+    SplitK sk = {U, r, (float*)0, nullptr};
+    Final f = {(const void*)0, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
     return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, ws, ws_bytes, s);
 }
 
@@ -146,13 +163,13 @@ int decode_qkv(const void* x, const void* const* U, const void* const* V, const 
                void* ws, size_t ws_bytes, hipStream_t s) {
     SplitK sk[kMaxProb]; int nb = 0;
     for (int i = 0; i < n_proj; ++i)
-        if (base_of[i] == i) sk[nb++] = SplitK{U[i], r[i], (float*)(uintptr_t)t_off[i]};
+        if (base_of[i] == i) sk[nb++] = SplitK{U[i], r[i], (float*)(uintptr_t)t_off[i], nullptr};
     Final f[kMaxProb];
     for (int i = 0; i < n_proj; ++i) {
         CacheDst cd = {nullptr, nullptr, 0, 1};
         if (kv && i == kv->k_index) cd = CacheDst{kv->k_cache, kv->pos, kv->S_max, kv->tokens_per_seq};
         if (kv && i == kv->v_index) cd = CacheDst{kv->v_cache, kv->pos, kv->S_max, kv->tokens_per_seq};
-        f[i] = Final{(const float*)(uintptr_t)t_off[i], r[i], V[i], d_out[i], bias ? bias[i] : nullptr, out[i], cd};
+        f[i] = Final{(const void*)(uintptr_t)t_off[i], r[i], V[i], d_out[i], bias ? bias[i] : nullptr, out[i], cd};
     }
     return run_two_stage(x, d_in, M, sk, nb, f, n_proj, R, ws, ws_bytes, s);
 }
@@ -165,26 +182,31 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     const WsLayout L = ws_layout(ws, ws_bytes);
     const int G = fused_grid(((size_t)d * r_gu + (size_t)(r_g + r_u) * ffn + (size_t)ffn * r_d + (size_t)r_d * d) * 2);
     const bool fused = G > 0 && (size_t)M * r_all * 4 <= L.acc_bytes;
-    // rank-space accumulators t[M, r_g + r_u + r_d] (fp32) and the bf16 hidden rows h[M, ffn]
+    // rank-space accumulators t[M, r_g + r_u + r_d] (fp32), the bf16 hidden rows h[M, ffn] and, for more
+    // than 8 token rows in a fused launch, the bf16 copy t16 of t
     float* t = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* h = fused ? (bf16_t*)L.staging : (bf16_t*)(L.staging + align256((size_t)M * r_all * 4));
+    bf16_t* t16 = (bf16_t*)(L.staging + align256((size_t)M * ffn * 2));
     const int64_t want = fused ? G : env_int("LOWRANK_DECODE_TILES", 512);
     DStage sa, sb, sc, sd;
-    SplitK a = {U_gu, r_gu, t};
     const int ca = pick_cpl(r_gu % 128 == 0 && r_d % 128 == 0), cc = ca;   // both split-K stages share one tile width
-    build_splitk(sa, x, d, M, d, &a, 1, r_all, want, ca);
+    const bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca));
+    int ctile = 0;
+    SplitK a = {U_gu, r_gu, t, use16 ? t16 : nullptr};
+    build_splitk(sa, x, d, M, d, &a, 1, r_all, want, ca, &ctile);
     {   // gate/up: both products of a 64-column tile in one workgroup, full K
         sb.nprob = 1; sb.M = (int)M;
         DProb& p = sb.p[0]; zero_prob(p);
-        p.W = (const bf16_t*)V_g; p.A = t; p.K = (int)r_g; p.lda = (int)r_all;
-        p.W2 = (const bf16_t*)V_u; p.A2 = t + r_g; p.K2 = (int)r_u; p.lda2 = (int)r_all;
+        p.W = (const bf16_t*)V_g; p.K = (int)r_g; p.lda = (int)r_all;
+        p.W2 = (const bf16_t*)V_u; p.K2 = (int)r_u; p.lda2 = (int)r_all;
+        if (use16) { p.A = t16; p.A2 = t16 + r_g; } else { p.A = t; p.A2 = t + r_g; }
         p.N = (int)ffn; p.Y = h; p.bias = (const bf16_t*)b_g; p.bias2 = (const bf16_t*)b_u;
         p.tiles_n = (int)(ffn / 64); p.KS = (int)r_g; p.tile_begin = 0;
         sb.total_tiles = p.tiles_n;
     }
-    SplitK c = {U_d, r_d, t + r_gu};
-    build_splitk(sc, h, ffn, M, ffn, &c, 1, r_all, want, cc);
-    Final f = {t + r_gu, r_d, V_d, d, b_d, out, {nullptr, nullptr, 0, 1}};
+    SplitK c = {U_d, r_d, t + r_gu, use16 ? t16 + r_gu : nullptr};
+    build_splitk(sc, h, ffn, M, ffn, &c, 1, r_all, want, cc, &ctile);
+    Final f = {use16 ? (const void*)(t16 + r_gu) : (const void*)(t + r_gu), r_d, V_d, d, b_d, out, {nullptr, nullptr, 0, 1}};
     const int cd = build_final(sd, &f, 1, r_all, M);
     if (fused) {
         FusedMlpArgs fa;
@@ -192,7 +214,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
         const DStage* src[4] = {&sa, &sb, &sc, &sd};
         DStageT<1>* dst[4] = {&fa.a, &fa.b, &fa.c, &fa.d};
         for (int i = 0; i < 4; ++i) { dst[i]->p[0] = src[i]->p[0]; dst[i]->nprob = 1; dst[i]->M = (int)M; dst[i]->total_tiles = src[i]->total_tiles; }
-        return decode_launch_fused_mlp(fa, ca, cc, cd, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, s);
+        return decode_launch_fused_mlp(fa, ca, cc, cd, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, use16, s);
     }
     int st = fill_zero(t, (size_t)M * r_all * 4, s);
     if (st != LR_OK) return st;

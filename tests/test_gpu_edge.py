@@ -226,6 +226,37 @@ def test_mixed_calls_share_one_workspace(G, oracle):
         assert max_rel_err(G.host64(y2), want_lin2) <= TOL["bf16"], rep
 
 
+@pytest.mark.parametrize("M", [4, 16, 32])
+def test_alternating_inputs_on_one_workspace(G, oracle, M):
+    """Calls with DIFFERENT inputs alternate on one workspace: intermediates of an earlier call that
+    survived anywhere (accumulator areas, bf16 copies, caches) would show up as a wrong result."""
+    B = G.B
+    ws_n = max(B.lowrank_workspace_bytes(B.LR_OP_QKV, M, 1024, 384, 3072, B.LR_BF16, "decode"),
+               B.lowrank_workspace_bytes(B.LR_OP_PACKED_MLP, M, 1024, 576, 2816, B.LR_BF16, "decode"))
+    ws = torch.empty(ws_n, dtype=torch.uint8, device="cuda")
+    B.lowrank_workspace_init(ws)
+    sets = []
+    for k in range(2):
+        wa = synth.attention_layer(M, d=1024, r=128, n_heads=8, S_max=8, seed=70 + k)
+        wm = synth.mlp_layer(M, d=1024, ffn=2816, r_g=192, r_u=192, r_d=192, seed=80 + k)
+        ta, tm = wa.t, wm.t
+        sets.append(dict(
+            x=G.dev(ta["x"]), Us=[G.dev(ta["U_" + n]) for n in "qkv"], Vs=[G.dev(ta["V_" + n]) for n in "qkv"],
+            xm=G.dev(tm["x"]), mlp=[G.dev(tm[n]) for n in ("U_gu", "V_g", "V_u", "U_d", "V_d")],
+            want_qkv=oracle.qkv(ta["x"].f64, [ta["U_" + n].f64 for n in "qkv"], [ta["V_" + n].f64 for n in "qkv"]),
+            want_mlp=oracle.packed_mlp(tm["x"].f64, tm["U_gu"].f64, tm["V_g"].f64, tm["V_u"].f64, tm["U_d"].f64, tm["V_d"].f64)))
+    for rep in range(6):
+        sset = sets[rep % 2]
+        outs = [torch.full((M, 1024), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+        om = torch.full((M, 1024), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.lowrank_qkv(sset["x"], sset["Us"], sset["Vs"], None, outs, None, "decode", ws)
+        B.lowrank_packed_mlp(sset["xm"], *sset["mlp"], None, None, None, om, "decode", ws)
+        B.lowrank_workspace_status(ws)
+        for i in range(3):
+            assert max_rel_err(G.host64(outs[i]), sset["want_qkv"][i]) <= TOL["bf16"], (rep, i)
+        assert max_rel_err(G.host64(om), sset["want_mlp"]) <= TOL["bf16"], rep
+
+
 def test_error_codes(G):
     B = G.B
     x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
