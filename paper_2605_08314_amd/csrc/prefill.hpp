@@ -24,6 +24,7 @@ struct PArgs {
     int tiles_m;        // ceil(M / BM)
     int tiles_n_max;    // max over problems of ceil(N / BN)
     int group_m;        // tile rows per L2 group of the tile order
+    unsigned long long* trace;   // timeline buffer of trace builds, else NULL
 };
 
 bool prefill_shape_ok(int64_t M, int64_t K, int64_t N);

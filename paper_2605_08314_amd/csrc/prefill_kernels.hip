@@ -13,6 +13,7 @@
 // staging tile; from there rows leave as 16-byte fully coalesced stores (to C and/or scattered to
 // the dense KV cache).  Epilogues: + bias, or the gate/up pair -> SiLU(g + b_g) * (u + b_u).
 #include "prefill.hpp"
+#include "decode.hpp"
 
 namespace lr {
 
@@ -170,10 +171,227 @@ __device__ __forceinline__ void gemm_loop(f32x16_t (&acc)[BM / 64][BN / 64], con
     }
 }
 
-template <int BM, int BN, int EPI, int MINB>
+// ---- direct-to-LDS pipeline ---------------------------------------------------------------------
+// Measured on this chip: loads that return through the vector registers deliver at most ~76 B/ns per
+// CU (a 256 x 256 x 64 tile step then needs as long for its 64 KB as for its 2048 MFMA cycles, and
+// with one wave per SIMD the two do not overlap), while global_load_lds_dwordx4 streams 126-144 B/ns
+// per CU into LDS with no register, no ds_write and no issue slot beyond the instruction itself.
+// So both operands travel global -> LDS directly, as they are in memory:
+//   A tile [BM rows][32 k]: row = 4 units of 16 bytes; unit c of row m sits at m*4 + (c ^ ((m >> 2) & 3)),
+//     which makes the 16-byte fragment reads of 16 consecutive rows sweep all 64 banks;
+//   B tile [32 k][BN columns], n contiguous as in memory: unit u of row k sits at k*(BN/8) + (u ^ ((k & 3) << 2));
+//     ds_read_b64_tr_b16 turns 4 k-rows x 16 columns into "4 consecutive k of one column per lane",
+//     two of them make the 8-k MFMA fragment; the XOR spreads the 4 rows of one read over the banks.
+// The permutation costs nothing: a lane of the load writes LDS unit (block base + lane) and simply
+// fetches the global unit that belongs there.
+// Ring of 4 stages of 32 k; per step one barrier, placed between the two 16-k substeps so the
+// fragments of the next stage are read under the second substep's MFMAs.  The tile of step kt+4 is
+// requested right after the barrier of step kt (which frees its stage) and is first needed after
+// the barrier of step kt+3.
+constexpr int DBK = 32;                 // k per stage
+constexpr int DSTAGES = 4;
+template <int BM, int BN> constexpr int dma_stage_bytes() { return BM * 64 + 32 * BN * 2; }
+template <int BM, int BN> constexpr int dma_lds_bytes() {
+    return DSTAGES * dma_stage_bytes<BM, BN>() > epi_bytes<BM, BN>() ? DSTAGES * dma_stage_bytes<BM, BN>() : epi_bytes<BM, BN>();
+}
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+
+// 64 lanes x 16 bytes: global (sbase + voff[lane]) -> LDS (lds_byte + 16 * lane); counted by vmcnt.
+__device__ __forceinline__ void dma16(uint32_t lds_byte, uint32_t voff, const void* sbase) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_byte), "v"(voff), "s"(sbase) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vm_lgkm0() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(N) : "memory");
+}
+
+template <int BM, int BN>
+struct DmaCtx {
+    static constexpr int NA = BM / 64, NR = BN / 64;      // load instructions per wave and step
+    static constexpr int UR = BN / 8;                     // 16-byte units per B row
+    const char* sa; const char* sb;                       // uniform: tile origin of A (row m0, k 0) and B (k 0, column n0)
+    uint32_t voa[NA], vob[NR];                            // per-lane byte offsets inside the step's tile
+    uint32_t step_a, step_b;                              // bytes per k-step
+    uint32_t lds0;                                        // LDS byte address of stage 0
+    int wave;
+};
+
+template <int BM, int BN>
+__device__ __forceinline__ void dma_setup(DmaCtx<BM, BN>& c, const bf16_t* A, int lda, const bf16_t* B, int N, int M, int m0, int n0, uint4* lds) {
+    constexpr int NA = DmaCtx<BM, BN>::NA, NR = DmaCtx<BM, BN>::NR, UR = DmaCtx<BM, BN>::UR;
+    const int tid = threadIdx.x, lane = tid & 63;
+    c.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    c.sa = reinterpret_cast<const char*>(A + (size_t)m0 * lda);
+    c.sb = reinterpret_cast<const char*>(B + n0);
+    c.step_a = DBK * 2; c.step_b = (uint32_t)DBK * (uint32_t)N * 2u;
+    c.lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int row = (c.wave * NA + j) * 16 + (lane >> 2), pos = lane & 3;
+        int m = m0 + row; m = m < M ? m : M - 1;          // rows past the end repeat the last row; never stored
+        c.voa[j] = (uint32_t)(m - m0) * (uint32_t)lda * 2u + (uint32_t)((pos ^ ((row >> 2) & 3)) * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        const int k = (c.wave * NR + j) * (64 / UR) + lane / UR, pos = lane % UR;
+        c.vob[j] = (uint32_t)k * (uint32_t)N * 2u + (uint32_t)((pos ^ ((k & 3) << 2)) * 16);
+    }
+}
+
+// request tile t (k range [32 t, 32 t + 32)) into its ring stage
+template <int BM, int BN>
+__device__ __forceinline__ void dma_issue(const DmaCtx<BM, BN>& c, int t) {
+    constexpr int NA = DmaCtx<BM, BN>::NA, NR = DmaCtx<BM, BN>::NR;
+    const uint32_t st = c.lds0 + (uint32_t)(t & (DSTAGES - 1)) * dma_stage_bytes<BM, BN>();
+    const char* ga = c.sa + (size_t)t * c.step_a;
+    const char* gb = c.sb + (size_t)t * c.step_b;
+#pragma unroll
+    for (int j = 0; j < NA; ++j) dma16(st + (uint32_t)(c.wave * NA + j) * 1024u, c.voa[j], ga);
+#pragma unroll
+    for (int j = 0; j < NR; ++j) dma16(st + (uint32_t)(BM * 64) + (uint32_t)(c.wave * NR + j) * 1024u, c.vob[j], gb);
+}
+
+template <int BM, int BN>
+struct FragAddr {
+    uint32_t a[2];              // byte offset in a stage of this lane's A unit for substep kk (row block 0)
+    uint32_t b[BN / 64];        // byte offset in a stage of this lane's B word for column block ni (substep 0, first half)
+};
+
+template <int BM, int BN>
+__device__ __forceinline__ void frag_setup(FragAddr<BM, BN>& f) {
+    constexpr int NI = BN / 64;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1, li = lane & 31, lg = lane >> 5;
+    const int row = wm * (BM / 2) + li;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) f.a[kk] = (uint32_t)(row * 64 + (((2 * kk + lg) ^ ((row >> 2) & 3)) * 16));
+    // transposing read: inside each block of 16 lanes, source lane s hands in row (s >> 2) and the
+    // 4 columns 4 * (s & 3)...; result lane i then holds column i of the block, 4 consecutive rows
+    const int s = lane & 15, blk = (lane >> 4) & 1, q = s >> 2;
+    const int k = lg * 8 + q;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int col = wn * (BN / 2) + ni * 32 + blk * 16 + 4 * (s & 3);
+        const int u = col >> 3, half = (col >> 2) & 1;
+        f.b[ni] = (uint32_t)(BM * 64 + k * (BN * 2) + ((u ^ (q << 2)) * 16) + half * 8);
+    }
+}
+
+template <int BM, int BN, int MI_ONE>
+__device__ __forceinline__ bf16x8_t dma_read_a(const char* stage, const FragAddr<BM, BN>& f, int kk) {
+    return frag_of(*reinterpret_cast<const uint4*>(stage + f.a[kk] + MI_ONE * 32 * 64));
+}
+template <int BM, int BN, int NI_ONE>
+__device__ __forceinline__ bf16x8_t dma_read_b(const char* stage, const FragAddr<BM, BN>& f, int kk) {
+    union { struct { s16x4_t lo, hi; } h; bf16x8_t b; } x;
+    const char* p = stage + f.b[NI_ONE] + kk * 16 * (BN * 2);
+    x.h.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p));
+    x.h.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p + 4 * (BN * 2)));
+    return x.b;
+}
+
+// Fragment reads of one "chunk" C (one of the MI row blocks of the wave tile): A fragment C and the
+// B fragments dealt evenly over the chunks.
+template <int BM, int BN, int C, int NIi>
+__device__ __forceinline__ void dma_maybe_read_b(bf16x8_t (&bfn)[BN / 64], const char* stage, const FragAddr<BM, BN>& f, int kk) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    if constexpr (NIi < NI) {
+        if constexpr ((NIi * MI) / NI == C) {
+#ifndef LR_ABLATE_READS_B
+            bfn[NIi] = dma_read_b<BM, BN, NIi>(stage, f, kk);
+#endif
+        }
+    }
+}
+template <int BM, int BN, int C>
+__device__ __forceinline__ void dma_read_chunk(bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* stage, const FragAddr<BM, BN>& f, int kk) {
+#ifndef LR_ABLATE_READS
+#ifndef LR_ABLATE_READS_A
+    afn[C] = dma_read_a<BM, BN, C>(stage, f, kk);
+#endif
+    dma_maybe_read_b<BM, BN, C, 0>(bfn, stage, f, kk);
+    dma_maybe_read_b<BM, BN, C, 1>(bfn, stage, f, kk);
+    dma_maybe_read_b<BM, BN, C, 2>(bfn, stage, f, kk);
+    dma_maybe_read_b<BM, BN, C, 3>(bfn, stage, f, kk);
+#endif
+}
+
+// chunk C of a substep: its share of the next substep's fragment reads, then the MFMAs of row block C
+template <int BM, int BN, int C>
+__device__ __forceinline__ void dma_chunk(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64],
+                                          bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* nstage,
+                                          const FragAddr<BM, BN>& f, int nkk) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    if constexpr (C < MI) {
+        dma_read_chunk<BM, BN, C>(afn, bfn, nstage, f, nkk);
+#ifndef LR_ABLATE_MFMA
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            acc[C][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[ni], afc[C], acc[C][ni], 0, 0, 0);
+#endif
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void dma_substep(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64],
+                                            bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* nstage,
+                                            const FragAddr<BM, BN>& f, int nkk) {
+    dma_chunk<BM, BN, 0>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+    dma_chunk<BM, BN, 1>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+    dma_chunk<BM, BN, 2>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+    dma_chunk<BM, BN, 3>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void gemm_loop_dma(f32x16_t (&acc)[BM / 64][BN / 64], const bf16_t* __restrict__ A, int lda,
+                                              const bf16_t* __restrict__ B, int N, int K, int M, int m0, int n0, uint4* lds) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    constexpr int L = DmaCtx<BM, BN>::NA + DmaCtx<BM, BN>::NR;     // loads per wave and tile
+    constexpr int SB = dma_stage_bytes<BM, BN>();
+    DmaCtx<BM, BN> c;
+    FragAddr<BM, BN> f;
+    dma_setup<BM, BN>(c, A, lda, B, N, M, m0, n0, lds);
+    frag_setup<BM, BN>(f);
+    const char* ring = reinterpret_cast<const char*>(lds);
+    const int nk = K / DBK;
+
+    // all waves are past their last use of this LDS (a previous K loop or nothing)
+    __builtin_amdgcn_s_barrier();
+    for (int t = 0; t < DSTAGES; ++t) if (t < nk) dma_issue<BM, BN>(c, t);
+    if (nk >= DSTAGES) wait_vm_lgkm0<3 * L>(); else wait_vm_lgkm0<0>();
+    __builtin_amdgcn_s_barrier();
+    bf16x8_t af0[MI], bf0[NI], af1[MI], bf1[NI];
+    dma_read_chunk<BM, BN, 0>(af0, bf0, ring, f, 0);
+    if constexpr (MI > 1) dma_read_chunk<BM, BN, 1>(af0, bf0, ring, f, 0);
+    if constexpr (MI > 2) dma_read_chunk<BM, BN, 2>(af0, bf0, ring, f, 0);
+    if constexpr (MI > 3) dma_read_chunk<BM, BN, 3>(af0, bf0, ring, f, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const char* cur = ring + (kt & (DSTAGES - 1)) * SB;
+        const char* nxt = ring + ((kt + 1) & (DSTAGES - 1)) * SB;
+        const bool more = kt + DSTAGES < nk;          // uniform
+        dma_substep<BM, BN>(acc, af0, bf0, af1, bf1, cur, f, 1);
+        // own part of tile kt+1 has landed (tiles kt+2, kt+3 may still fly; near the end simply wait for
+        // everything) and own reads of stage kt are done
+        if (more) wait_vm_lgkm0<2 * L>(); else wait_vm_lgkm0<0>();
+        __builtin_amdgcn_s_barrier();
+#ifndef LR_ABLATE_DMA
+        if (more) dma_issue<BM, BN>(c, kt + DSTAGES); // the stage of tile kt is free now
+#endif
+        __builtin_amdgcn_sched_barrier(0);
+        // after the last step this reads a stale stage: in bounds, never used
+        dma_substep<BM, BN>(acc, af1, bf1, af0, bf0, nxt, f, 0);
+    }
+}
+
+template <int BM, int BN, int EPI, int MINB, bool DMA>
 __global__ void __launch_bounds__(256, MINB) k_prefill_gemm(PArgs pa) {
     constexpr int MI = BM / 64, NI = BN / 64;
-    __shared__ uint4 lds[lds_bytes<BM, BN>() / 16];
+    __shared__ uint4 lds[(DMA ? dma_lds_bytes<BM, BN>() : lds_bytes<BM, BN>()) / 16];
     // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own 4 MB L2: workgroup
     // id -> (id % 8) * total/8 + id / 8 gives every XCD a contiguous range of the logical order, and the
     // logical order walks groups of pa.group_m tile rows column by column, so the workgroups that run
@@ -199,7 +417,8 @@ __global__ void __launch_bounds__(256, MINB) k_prefill_gemm(PArgs pa) {
         for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-    gemm_loop<BM, BN>(acc, P.A, P.lda, P.B, P.N, P.K, M, m0, n0, lds);
+    if constexpr (DMA) gemm_loop_dma<BM, BN>(acc, P.A, P.lda, P.B, P.N, P.K, M, m0, n0, lds);
+    else gemm_loop<BM, BN>(acc, P.A, P.lda, P.B, P.N, P.K, M, m0, n0, lds);
 
     f32x16_t acc2[(EPI == PEPI_GATEUP) ? MI : 1][(EPI == PEPI_GATEUP) ? NI : 1];
     if constexpr (EPI == PEPI_GATEUP) {
@@ -209,7 +428,8 @@ __global__ void __launch_bounds__(256, MINB) k_prefill_gemm(PArgs pa) {
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc2[mi][ni][v] = 0.f;
-        gemm_loop<BM, BN>(acc2, P.A2, P.lda2, P.B2, P.N, P.K2, M, m0, n0, lds);
+        if constexpr (DMA) gemm_loop_dma<BM, BN>(acc2, P.A2, P.lda2, P.B2, P.N, P.K2, M, m0, n0, lds);
+        else gemm_loop<BM, BN>(acc2, P.A2, P.lda2, P.B2, P.N, P.K2, M, m0, n0, lds);
     }
 
     // ---- epilogue: registers -> bf16 staging tile in LDS -> coalesced 16-byte row stores
@@ -280,26 +500,22 @@ bool prefill_shape_ok(int64_t M, int64_t K, int64_t N) {
            K < (1 << 24) && N < (1 << 24);
 }
 
-template <int BM, int BN, int EPI, int MINB>
+template <int BM, int BN, int EPI, int MINB, bool DMA>
 static int launch_cfg(PArgs a, hipStream_t s) {
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n_max = 0;
     for (int i = 0; i < a.nprob; ++i) { const int t = (a.p[i].N + BN - 1) / BN; if (t > a.tiles_n_max) a.tiles_n_max = t; }
     const int total = a.tiles_m * a.tiles_n_max * a.nprob;
     a.group_m = 8;
-    hipLaunchKernelGGL((k_prefill_gemm<BM, BN, EPI, MINB>), dim3((unsigned)total), dim3(256), 0, s, a);
+    a.trace = g_trace_buffer;
+    hipLaunchKernelGGL((k_prefill_gemm<BM, BN, EPI, MINB, DMA>), dim3((unsigned)total), dim3(256), 0, s, a);
     return launch_status("prefill gemm");
 }
 
-static int env_shape() {
-    static int force = -2;
-    if (force == -2) { const char* v = getenv("LOWRANK_PREFILL_SHAPE"); force = v ? atoi(v) : -1; }
-    return force;
-}
+static int env_int(const char* name) { const char* v = getenv(name); return v ? atoi(v) : -1; }
+static int env_shape() { static int v = env_int("LOWRANK_PREFILL_SHAPE"); return v; }
+static int env_gu() { static int v = env_int("LOWRANK_PREFILL_GU"); return v; }
 
-// Tile shape of a plain launch: 256 x 128 tiles (more reuse per LDS byte; measured 941 vs 856 TFLOP/s
-// on an 8192^3 product) when they still give every CU several rounds of work, else 128 x 128
-// (three workgroups per CU, less idle tail on the small-N rank-space products).
 static bool want_bm256(const PArgs& a) {
     long tiles = 0;
     for (int i = 0; i < a.nprob; ++i) tiles += (long)((a.M + 255) / 256) * (a.p[i].N / 128);
@@ -308,10 +524,25 @@ static bool want_bm256(const PArgs& a) {
 
 int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
     if (a.M <= 0 || a.nprob <= 0) return LR_OK;
-    const int force = env_shape();
-    if (epi == PEPI_GATEUP) return launch_cfg<128, 128, PEPI_GATEUP, 2>(a, s);
-    if (force == 1 || (force != 2 && want_bm256(a))) return launch_cfg<256, 128, PEPI_STORE, 2>(a, s);
-    return launch_cfg<128, 128, PEPI_STORE, 2>(a, s);
+    bool n256 = true;
+    for (int i = 0; i < a.nprob; ++i) n256 = n256 && (a.p[i].N % 256 == 0);
+    if (epi == PEPI_GATEUP) {
+        switch (env_gu()) {
+            case 0: return launch_cfg<128, 128, PEPI_GATEUP, 2, false>(a, s);
+            case 2: return launch_cfg<256, 128, PEPI_GATEUP, 1, true>(a, s);
+            default: return launch_cfg<128, 128, PEPI_GATEUP, 2, true>(a, s);
+        }
+    }
+    switch (env_shape()) {
+        case 0: if (n256) return launch_cfg<256, 256, PEPI_STORE, 1, true>(a, s); break;
+        case 1: return launch_cfg<256, 128, PEPI_STORE, 2, false>(a, s);
+        case 2: return launch_cfg<128, 128, PEPI_STORE, 2, false>(a, s);
+        case 3: return launch_cfg<256, 128, PEPI_STORE, 1, true>(a, s);
+        case 4: if (n256) return launch_cfg<128, 256, PEPI_STORE, 1, true>(a, s); break;
+        case 5: return launch_cfg<128, 128, PEPI_STORE, 2, true>(a, s);
+        default: break;
+    }
+    return launch_cfg<128, 128, PEPI_STORE, 2, true>(a, s);
 }
 
 }  // namespace lr
