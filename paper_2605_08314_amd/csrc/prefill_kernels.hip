@@ -1,17 +1,17 @@
-// Prefill-phase GEMM (bf16 MFMA, LDS-staged): C[M, N] = A[M, K] * B[K, N] with A, B, C row-major.
+// Prefill-phase GEMM (bf16 MFMA): C[M, N] = A[M, K] * B[K, N] with A, B, C row-major, as a persistent
+// kernel whose operands travel global memory -> LDS directly (global_load_lds_dwordx4).
 //
-// Tile: BM x BN x 64 per workgroup of 4 waves (2 x 2), each wave (BM/2) x (BN/2) built from
-// v_mfma_f32_32x32x16_bf16.  Both operands sit in LDS "chunk-major": the 8 consecutive k of one
-// row are one 16-byte unit, units of one k-chunk are contiguous over rows (one pad unit every
-// 8 rows), so a fragment read (lane = row, 16 bytes) is linear and conflict-free.  A comes from
-// global memory in that shape already (k contiguous); B is row-major [K, N] (n contiguous), so each
-// thread loads 4 k-rows x 8 columns and transposes them inside the lane with v_perm_b32 before the
-// LDS write -- the factors are used as stored, no repacked copy of U or V exists.
+// Tile BM x BN per workgroup of 4 waves (2 x 2), each wave (BM/2) x (BN/2) built from
+// v_mfma_f32_32x32x16_bf16.  The factors are used as stored -- no repacked copy of U or V exists:
+// A is k-contiguous in memory and its 16-byte units are read back as MFMA fragments as they are;
+// B is [K, N] with n contiguous and its fragments ("8 consecutive k of one column per lane") are
+// produced by the transposing LDS read ds_read_b64_tr_b16.
 //
 // The MFMA is issued with the B fragment as the row operand: a lane then holds, for one token row,
-// 4 consecutive output columns per accumulator group, which packs to 8-byte bf16 stores into an LDS
-// staging tile; from there rows leave as 16-byte fully coalesced stores (to C and/or scattered to
-// the dense KV cache).  Epilogues: + bias, or the gate/up pair -> SiLU(g + b_g) * (u + b_u).
+// 4 consecutive output columns per accumulator group, which packs to 8-byte bf16 writes into a small
+// per-wave LDS patch; from there rows leave as 16-byte stores covering whole 128-byte lines (to C
+// and/or scattered to the dense KV cache).  Epilogues: + bias, or the gate/up pair ->
+// SiLU(g + b_g) * (u + b_u).
 #include "prefill.hpp"
 #include "decode.hpp"
 
@@ -21,17 +21,6 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
-constexpr int PBK = 64;
-
-__host__ __device__ constexpr int plane_units(int rows) { return rows + rows / 8 + 1; }
-__device__ __forceinline__ int unit_of(int plane, int chunk, int row) { return chunk * plane + row + (row >> 3); }
-
-template <int BM, int BN> constexpr int stage_units() { return 8 * plane_units(BM) + 8 * plane_units(BN); }
-template <int BM, int BN> constexpr int epi_bytes() { return BM * (BN + 4) * 2; }
-template <int BM, int BN> constexpr int lds_bytes() {
-    return stage_units<BM, BN>() * 16 > epi_bytes<BM, BN>() ? stage_units<BM, BN>() * 16 : epi_bytes<BM, BN>();
-}
 
 __device__ __forceinline__ uint32_t ppack2(float lo, float hi) {
     union { bf16x2_t v; uint32_t u; } x;
@@ -43,132 +32,6 @@ __device__ __forceinline__ bf16x8_t frag_of(const uint4& v) {
     union { uint4 u; bf16x8_t b; } x;
     x.u = v;
     return x.b;
-}
-
-__device__ __forceinline__ uint32_t dword_of(const uint4& v, int q) { return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w; }
-
-// Global -> register loads of one k-step (64 k): NA 16-byte chunks of A per thread; of B, NR k-rows x 8
-// columns per thread (NR = BN / 32: the 256 threads cover 64 k-rows x BN columns).
-template <int NA, int NR, int BN>
-__device__ __forceinline__ void load_tiles(uint4 (&ra)[NA], uint4 (&rb)[NR], const bf16_t* __restrict__ A, int lda,
-                                           const bf16_t* __restrict__ B, int N, int M, int m0, int n0, int k0, int tid) {
-#pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-        const int m = m0 + row;
-        if (m < M) ra[i] = *reinterpret_cast<const uint4*>(A + (size_t)m * lda + k0 + kc * 8);
-        else ra[i] = make_uint4(0u, 0u, 0u, 0u);
-    }
-    constexpr int CGS = BN / 8;                          // column groups of 8
-    const int cg = tid % CGS, rg = tid / CGS;            // rg: group of NR consecutive k-rows
-    const bf16_t* bp = B + (size_t)(k0 + rg * NR) * N + n0 + cg * 8;
-#pragma unroll
-    for (int a = 0; a < NR; ++a) rb[a] = *reinterpret_cast<const uint4*>(bp + (size_t)a * N);
-}
-
-// Registers -> LDS: A chunks as they are; B transposed inside the lane: the NR k-values of one column
-// become NR*2 contiguous bytes of that column's 16-byte unit.
-template <int NA, int NR, int BM, int BN>
-__device__ __forceinline__ void store_tiles(const uint4 (&ra)[NA], const uint4 (&rb)[NR], uint4* As, uint4* Bs, int tid) {
-    constexpr int PA = plane_units(BM), PB = plane_units(BN);
-#pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-        As[unit_of(PA, kc, row)] = ra[i];
-    }
-    constexpr int CGS = BN / 8;
-    const int cg = tid % CGS, rg = tid / CGS;
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-        const uint32_t sel = (b & 1) ? 0x07060302u : 0x05040100u;
-        if constexpr (NR == 8) {
-            uint4 v;
-            v.x = __builtin_amdgcn_perm(dword_of(rb[1], b >> 1), dword_of(rb[0], b >> 1), sel);
-            v.y = __builtin_amdgcn_perm(dword_of(rb[3], b >> 1), dword_of(rb[2], b >> 1), sel);
-            v.z = __builtin_amdgcn_perm(dword_of(rb[5], b >> 1), dword_of(rb[4], b >> 1), sel);
-            v.w = __builtin_amdgcn_perm(dword_of(rb[7], b >> 1), dword_of(rb[6], b >> 1), sel);
-            Bs[unit_of(PB, rg, cg * 8 + b)] = v;
-        } else {
-            uint2 v;
-            v.x = __builtin_amdgcn_perm(dword_of(rb[1], b >> 1), dword_of(rb[0], b >> 1), sel);   // k rows 4rg+0, 4rg+1 of column b
-            v.y = __builtin_amdgcn_perm(dword_of(rb[3], b >> 1), dword_of(rb[2], b >> 1), sel);   // k rows 4rg+2, 4rg+3
-            reinterpret_cast<uint2*>(Bs)[unit_of(PB, rg >> 1, cg * 8 + b) * 2 + (rg & 1)] = v;
-        }
-    }
-}
-
-template <int MI, int NI>
-__device__ __forceinline__ void load_frags(bf16x8_t (&af)[MI], bf16x8_t (&bf)[NI], const uint4* a_base, const uint4* b_base,
-                                           int a_step, int b_step) {
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) af[mi] = frag_of(a_base[a_step + mi * 36]);   // 32 rows = 36 units (pad every 8)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) bf[ni] = frag_of(b_base[b_step + ni * 36]);
-}
-
-template <int MI, int NI>
-__device__ __forceinline__ void mma_step(f32x16_t (&acc)[MI][NI], const bf16x8_t (&af)[MI], const bf16x8_t (&bf)[NI]) {
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ni], af[mi], acc[mi][ni], 0, 0, 0);
-}
-
-// The matrix work of one k-step from the LDS stage at `st`.  Each sched_barrier pins the order
-// "reads of substep kk+1, then MFMAs of substep kk", so the fragments of the next substep are in
-// flight for a whole substep of matrix work.
-template <int BM, int BN>
-__device__ __forceinline__ void compute_stage(f32x16_t (&acc)[BM / 64][BN / 64], const uint4* st, int a_off, int b_off) {
-    constexpr int MI = BM / 64, NI = BN / 64;
-    constexpr int PA = plane_units(BM), PB = plane_units(BN);
-    const uint4* a_base = st + a_off;
-    const uint4* b_base = st + b_off;
-    bf16x8_t af0[MI], bf0[NI], af1[MI], bf1[NI];
-    load_frags<MI, NI>(af0, bf0, a_base, b_base, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags<MI, NI>(af1, bf1, a_base, b_base, 2 * PA, 2 * PB);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step<MI, NI>(acc, af0, bf0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags<MI, NI>(af0, bf0, a_base, b_base, 4 * PA, 4 * PB);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step<MI, NI>(acc, af1, bf1);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags<MI, NI>(af1, bf1, a_base, b_base, 6 * PA, 6 * PB);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step<MI, NI>(acc, af0, bf0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step<MI, NI>(acc, af1, bf1);
-    __builtin_amdgcn_sched_barrier(0);
-}
-
-// One K loop: acc[mi][ni] += (B tile)^T x (A tile)^T over k in [0, K).  One LDS buffer, two barriers
-// per k-step, global data of the next step prefetched into registers; two or three workgroups per
-// CU overlap each other's store phases.  (A two-buffer variant with one barrier per step and a
-// 256 x 256 tile were measured slower on this chip: 786 / 909 vs 941 TFLOP/s on an 8192^3 product.)
-template <int BM, int BN>
-__device__ __forceinline__ void gemm_loop(f32x16_t (&acc)[BM / 64][BN / 64], const bf16_t* __restrict__ A, int lda,
-                                          const bf16_t* __restrict__ B, int N, int K, int M, int m0, int n0, uint4* lds) {
-    constexpr int NA = BM / 32, NR = BN / 32;
-    constexpr int PA = plane_units(BM), PB = plane_units(BN);
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int li = lane & 31, lg = lane >> 5;
-    // fragment offsets of this lane for k-substep 0 (chunk lg); substep kk adds 2*kk planes
-    const int a_off = unit_of(PA, lg, wm * (BM / 2) + li);
-    const int b_off = 8 * PA + unit_of(PB, lg, wn * (BN / 2) + li);
-
-    uint4 ra[NA], rb[NR];
-    const int nk = K / PBK;
-    load_tiles<NA, NR, BN>(ra, rb, A, lda, B, N, M, m0, n0, 0, tid);
-    for (int kt = 0; kt < nk; ++kt) {
-        __syncthreads();                 // everyone finished reading the previous tile
-        store_tiles<NA, NR, BM, BN>(ra, rb, lds, lds + 8 * PA, tid);
-        __syncthreads();
-        if (kt + 1 < nk) load_tiles<NA, NR, BN>(ra, rb, A, lda, B, N, M, m0, n0, (kt + 1) * PBK, tid);
-        compute_stage<BM, BN>(acc, lds, a_off, b_off);
-    }
 }
 
 // ---- direct-to-LDS pipeline ---------------------------------------------------------------------
@@ -191,10 +54,6 @@ __device__ __forceinline__ void gemm_loop(f32x16_t (&acc)[BM / 64][BN / 64], con
 constexpr int DBK = 32;                 // k per stage
 constexpr int DSTAGES = 4;
 template <int BM, int BN> constexpr int dma_stage_bytes() { return BM * 64 + 32 * BN * 2; }
-template <int BM, int BN> constexpr int dma_lds_bytes() {
-    return DSTAGES * dma_stage_bytes<BM, BN>() > epi_bytes<BM, BN>() ? DSTAGES * dma_stage_bytes<BM, BN>() : epi_bytes<BM, BN>();
-}
-
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
@@ -205,52 +64,6 @@ __device__ __forceinline__ void dma16(uint32_t lds_byte, uint32_t voff, const vo
 }
 template <int N> __device__ __forceinline__ void wait_vm_lgkm0() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(N) : "memory");
-}
-
-template <int BM, int BN>
-struct DmaCtx {
-    static constexpr int NA = BM / 64, NR = BN / 64;      // load instructions per wave and step
-    static constexpr int UR = BN / 8;                     // 16-byte units per B row
-    const char* sa; const char* sb;                       // uniform: tile origin of A (row m0, k 0) and B (k 0, column n0)
-    uint32_t voa[NA], vob[NR];                            // per-lane byte offsets inside the step's tile
-    uint32_t step_a, step_b;                              // bytes per k-step
-    uint32_t lds0;                                        // LDS byte address of stage 0
-    int wave;
-};
-
-template <int BM, int BN>
-__device__ __forceinline__ void dma_setup(DmaCtx<BM, BN>& c, const bf16_t* A, int lda, const bf16_t* B, int N, int M, int m0, int n0, uint4* lds) {
-    constexpr int NA = DmaCtx<BM, BN>::NA, NR = DmaCtx<BM, BN>::NR, UR = DmaCtx<BM, BN>::UR;
-    const int tid = threadIdx.x, lane = tid & 63;
-    c.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    c.sa = reinterpret_cast<const char*>(A + (size_t)m0 * lda);
-    c.sb = reinterpret_cast<const char*>(B + n0);
-    c.step_a = DBK * 2; c.step_b = (uint32_t)DBK * (uint32_t)N * 2u;
-    c.lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
-#pragma unroll
-    for (int j = 0; j < NA; ++j) {
-        const int row = (c.wave * NA + j) * 16 + (lane >> 2), pos = lane & 3;
-        int m = m0 + row; m = m < M ? m : M - 1;          // rows past the end repeat the last row; never stored
-        c.voa[j] = (uint32_t)(m - m0) * (uint32_t)lda * 2u + (uint32_t)((pos ^ ((row >> 2) & 3)) * 16);
-    }
-#pragma unroll
-    for (int j = 0; j < NR; ++j) {
-        const int k = (c.wave * NR + j) * (64 / UR) + lane / UR, pos = lane % UR;
-        c.vob[j] = (uint32_t)k * (uint32_t)N * 2u + (uint32_t)((pos ^ ((k & 3) << 2)) * 16);
-    }
-}
-
-// request tile t (k range [32 t, 32 t + 32)) into its ring stage
-template <int BM, int BN>
-__device__ __forceinline__ void dma_issue(const DmaCtx<BM, BN>& c, int t) {
-    constexpr int NA = DmaCtx<BM, BN>::NA, NR = DmaCtx<BM, BN>::NR;
-    const uint32_t st = c.lds0 + (uint32_t)(t & (DSTAGES - 1)) * dma_stage_bytes<BM, BN>();
-    const char* ga = c.sa + (size_t)t * c.step_a;
-    const char* gb = c.sb + (size_t)t * c.step_b;
-#pragma unroll
-    for (int j = 0; j < NA; ++j) dma16(st + (uint32_t)(c.wave * NA + j) * 1024u, c.voa[j], ga);
-#pragma unroll
-    for (int j = 0; j < NR; ++j) dma16(st + (uint32_t)(BM * 64) + (uint32_t)(c.wave * NR + j) * 1024u, c.vob[j], gb);
 }
 
 template <int BM, int BN>
@@ -319,178 +132,367 @@ __device__ __forceinline__ void dma_read_chunk(bf16x8_t (&afn)[BM / 64], bf16x8_
 }
 
 // chunk C of a substep: its share of the next substep's fragment reads, then the MFMAs of row block C
-template <int BM, int BN, int C>
+template <int BM, int BN, int C, bool ZERO = false, bool READ = true>
 __device__ __forceinline__ void dma_chunk(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64],
                                           bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* nstage,
                                           const FragAddr<BM, BN>& f, int nkk) {
     constexpr int MI = BM / 64, NI = BN / 64;
     if constexpr (C < MI) {
-        dma_read_chunk<BM, BN, C>(afn, bfn, nstage, f, nkk);
+        if constexpr (READ) dma_read_chunk<BM, BN, C>(afn, bfn, nstage, f, nkk);
 #ifndef LR_ABLATE_MFMA
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            acc[C][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[ni], afc[C], acc[C][ni], 0, 0, 0);
+        for (int ni = 0; ni < NI; ++ni) {
+            if constexpr (ZERO) {       // first product of a tile: the accumulator starts from the constant 0
+                const f32x16_t z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                acc[C][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[ni], afc[C], z, 0, 0, 0);
+            } else {
+                acc[C][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[ni], afc[C], acc[C][ni], 0, 0, 0);
+            }
+        }
 #endif
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool ZERO = false, bool READ = true>
 __device__ __forceinline__ void dma_substep(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64],
                                             bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* nstage,
                                             const FragAddr<BM, BN>& f, int nkk) {
-    dma_chunk<BM, BN, 0>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
-    dma_chunk<BM, BN, 1>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
-    dma_chunk<BM, BN, 2>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
-    dma_chunk<BM, BN, 3>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+    dma_chunk<BM, BN, 0, ZERO, READ>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+    dma_chunk<BM, BN, 1, ZERO, READ>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+    dma_chunk<BM, BN, 2, ZERO, READ>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+    dma_chunk<BM, BN, 3, ZERO, READ>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+}
+
+// ---- persistent form ----------------------------------------------------------------------------
+// One workgroup per CU slot walks a list of tiles; the request ring never drains between tiles: while
+// a tile's last steps are multiplied and its result leaves, the first stages of the next tile are
+// already on their way.  Each wave stores its own part of the result through a private 4 KB LDS patch
+// (32 rows x 64 columns, 16-byte units XOR-swizzled by row), so the epilogue needs no workgroup
+// barrier and the rows leave as full 128-byte lines.
+template <int BM, int BN> constexpr int persist_lds_bytes() { return DSTAGES * dma_stage_bytes<BM, BN>() + 4 * 4096; }
+
+// what the requester needs to know about one operand pair (A, B over K) of one tile
+template <int BM, int BN>
+struct Stream {
+    const char* sa; const char* sb;
+    uint32_t voa[BM / 64], vob[BN / 64];
+    uint32_t step_b;
+    int nk;
+};
+
+template <int BM, int BN>
+__device__ __forceinline__ void stream_setup(Stream<BM, BN>& c, const bf16_t* A, int lda, const bf16_t* B, int N, int K,
+                                             int M, int m0, int n0, int wave, int lane) {
+    constexpr int NA = BM / 64, NR = BN / 64, UR = BN / 8;
+    c.sa = reinterpret_cast<const char*>(A + (size_t)m0 * lda);
+    c.sb = reinterpret_cast<const char*>(B + n0);
+    c.step_b = (uint32_t)DBK * (uint32_t)N * 2u;
+    c.nk = K / DBK;
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int row = (wave * NA + j) * 16 + (lane >> 2), pos = lane & 3;
+        int m = m0 + row; m = m < M ? m : M - 1;          // rows past the end repeat the last row; never stored
+        c.voa[j] = (uint32_t)(m - m0) * (uint32_t)lda * 2u + (uint32_t)((pos ^ ((row >> 2) & 3)) * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        const int k = (wave * NR + j) * (64 / UR) + lane / UR, pos = lane % UR;
+        int col = (pos ^ ((k & 3) << 2)) * 8;
+        col = (n0 + col + 8 <= N) ? col : N - 8 - n0;     // columns past the end repeat the last unit; never stored
+        c.vob[j] = (uint32_t)k * (uint32_t)N * 2u + (uint32_t)(col * 2);
+    }
 }
 
 template <int BM, int BN>
-__device__ __forceinline__ void gemm_loop_dma(f32x16_t (&acc)[BM / 64][BN / 64], const bf16_t* __restrict__ A, int lda,
-                                              const bf16_t* __restrict__ B, int N, int K, int M, int m0, int n0, uint4* lds) {
-    constexpr int MI = BM / 64, NI = BN / 64;
-    constexpr int L = DmaCtx<BM, BN>::NA + DmaCtx<BM, BN>::NR;     // loads per wave and tile
-    constexpr int SB = dma_stage_bytes<BM, BN>();
-    DmaCtx<BM, BN> c;
-    FragAddr<BM, BN> f;
-    dma_setup<BM, BN>(c, A, lda, B, N, M, m0, n0, lds);
-    frag_setup<BM, BN>(f);
-    const char* ring = reinterpret_cast<const char*>(lds);
-    const int nk = K / DBK;
+__device__ __forceinline__ void stream_issue(const Stream<BM, BN>& c, int kt, uint32_t stage_lds, int wave) {
+    constexpr int NA = BM / 64, NR = BN / 64;
+    const char* ga = c.sa + (size_t)kt * (DBK * 2);
+    const char* gb = c.sb + (size_t)kt * c.step_b;
+#pragma unroll
+    for (int j = 0; j < NA; ++j) dma16(stage_lds + (uint32_t)(wave * NA + j) * 1024u, c.voa[j], ga);
+#pragma unroll
+    for (int j = 0; j < NR; ++j) dma16(stage_lds + (uint32_t)(BM * 64) + (uint32_t)(wave * NR + j) * 1024u, c.vob[j], gb);
+}
 
-    // all waves are past their last use of this LDS (a previous K loop or nothing)
-    __builtin_amdgcn_s_barrier();
-    for (int t = 0; t < DSTAGES; ++t) if (t < nk) dma_issue<BM, BN>(c, t);
-    if (nk >= DSTAGES) wait_vm_lgkm0<3 * L>(); else wait_vm_lgkm0<0>();
-    __builtin_amdgcn_s_barrier();
-    bf16x8_t af0[MI], bf0[NI], af1[MI], bf1[NI];
-    dma_read_chunk<BM, BN, 0>(af0, bf0, ring, f, 0);
-    if constexpr (MI > 1) dma_read_chunk<BM, BN, 1>(af0, bf0, ring, f, 0);
-    if constexpr (MI > 2) dma_read_chunk<BM, BN, 2>(af0, bf0, ring, f, 0);
-    if constexpr (MI > 3) dma_read_chunk<BM, BN, 3>(af0, bf0, ring, f, 0);
-    __builtin_amdgcn_sched_barrier(0);
+// The tiles of one workgroup.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2):
+// XCD x owns a contiguous eighth of the logical tile order, and its workgroups take consecutive
+// logical tiles together, round after round.  The logical order walks groups of group_m tile rows
+// column by column, so tiles in flight on one XCD share A row-panels and B column-panels.
+struct TileWalk { int next, end, stride; };
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const char* cur = ring + (kt & (DSTAGES - 1)) * SB;
-        const char* nxt = ring + ((kt + 1) & (DSTAGES - 1)) * SB;
-        const bool more = kt + DSTAGES < nk;          // uniform
-        dma_substep<BM, BN>(acc, af0, bf0, af1, bf1, cur, f, 1);
-        // own part of tile kt+1 has landed (tiles kt+2, kt+3 may still fly; near the end simply wait for
-        // everything) and own reads of stage kt are done
-        if (more) wait_vm_lgkm0<2 * L>(); else wait_vm_lgkm0<0>();
-        __builtin_amdgcn_s_barrier();
-#ifndef LR_ABLATE_DMA
-        if (more) dma_issue<BM, BN>(c, kt + DSTAGES); // the stage of tile kt is free now
-#endif
-        __builtin_amdgcn_sched_barrier(0);
-        // after the last step this reads a stale stage: in bounds, never used
-        dma_substep<BM, BN>(acc, af1, bf1, af0, bf0, nxt, f, 0);
+__device__ __forceinline__ TileWalk walk_begin(const PArgs& pa) {
+    const int total = pa.tiles_m * pa.tiles_n_max * pa.nprob;
+    const int per_xcd = (total + 7) >> 3;
+    const int x = blockIdx.x & 7, j = blockIdx.x >> 3, slots = gridDim.x >> 3;
+    TileWalk w;
+    w.next = x * per_xcd + j;
+    w.end = (x + 1) * per_xcd < total ? (x + 1) * per_xcd : total;
+    w.stride = slots;
+    return w;
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ bool walk_next(TileWalk& w, const PArgs& pa, int& prob, int& m0, int& n0) {
+    const int per_prob = pa.tiles_m * pa.tiles_n_max;
+    const int gsz = pa.group_m * pa.tiles_n_max;
+    while (w.next < w.end) {
+        const int id = w.next;
+        w.next += w.stride;
+        const int pr = id / per_prob, rem = id - pr * per_prob;
+        const int mg = rem / gsz, r = rem - mg * gsz;
+        const int rows_here = (pa.tiles_m - mg * pa.group_m) < pa.group_m ? (pa.tiles_m - mg * pa.group_m) : pa.group_m;
+        const int tn = r / rows_here, tm = mg * pa.group_m + (r - tn * rows_here);
+        if (tn * BN < pa.p[pr].N) { prob = pr; m0 = tm * BM; n0 = tn * BN; return true; }
+    }
+    return false;
+}
+
+template <int BM, int BN, int EPI>
+struct Requester {
+    TileWalk w;
+    Stream<BM, BN> st;
+    int kt, phase, prob, m0, n0;
+    bool live;
+    uint32_t issued;
+};
+
+template <int BM, int BN, int EPI>
+__device__ __forceinline__ void requester_open(Requester<BM, BN, EPI>& q, const PArgs& pa, int wave, int lane) {
+    const PProb& P = pa.p[q.prob];
+    if (q.phase == 0) stream_setup<BM, BN>(q.st, P.A, P.lda, P.B, P.N, P.K, pa.M, q.m0, q.n0, wave, lane);
+    else stream_setup<BM, BN>(q.st, P.A2, P.lda2, P.B2, P.N, P.K2, pa.M, q.m0, q.n0, wave, lane);
+    q.kt = 0;
+}
+
+template <int BM, int BN, int EPI>
+__device__ __forceinline__ void requester_step(Requester<BM, BN, EPI>& q, const PArgs& pa, uint32_t lds0, int wave, int lane) {
+    if (!q.live) return;
+    stream_issue<BM, BN>(q.st, q.kt, lds0 + (q.issued & (DSTAGES - 1)) * dma_stage_bytes<BM, BN>(), wave);
+    ++q.issued;
+    if (++q.kt == q.st.nk) {
+        if (EPI == PEPI_GATEUP && q.phase == 0) { q.phase = 1; }
+        else { q.phase = 0; q.live = walk_next<BM, BN>(q.w, pa, q.prob, q.m0, q.n0); }
+        if (q.live) requester_open<BM, BN, EPI>(q, pa, wave, lane);
     }
 }
 
-template <int BM, int BN, int EPI, int MINB, bool DMA>
-__global__ void __launch_bounds__(256, MINB) k_prefill_gemm(PArgs pa) {
-    constexpr int MI = BM / 64, NI = BN / 64;
-    __shared__ uint4 lds[(DMA ? dma_lds_bytes<BM, BN>() : lds_bytes<BM, BN>()) / 16];
-    // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own 4 MB L2: workgroup
-    // id -> (id % 8) * total/8 + id / 8 gives every XCD a contiguous range of the logical order, and the
-    // logical order walks groups of pa.group_m tile rows column by column, so the workgroups that run
-    // together on one XCD share both a few A row-tiles and a few B column-tiles.
-    const int per_prob = pa.tiles_m * pa.tiles_n_max;
-    const int total = per_prob * pa.nprob;
-    int id = blockIdx.x;
-    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
-    const int prob = id / per_prob;
-    const int rem = id - prob * per_prob;
-    const int gsz = pa.group_m * pa.tiles_n_max;
-    const int mg = rem / gsz, r = rem - mg * gsz;
-    const int rows_here = (pa.tiles_m - mg * pa.group_m) < pa.group_m ? (pa.tiles_m - mg * pa.group_m) : pa.group_m;
-    const int tn = r / rows_here, tm = mg * pa.group_m + (r - tn * rows_here);
-    const PProb& P = pa.p[prob];
-    if (tn * BN >= P.N) return;
-    const int m0 = tm * BM, n0 = tn * BN, M = pa.M;
+// wait until at most `groups` request groups of this wave (L instructions each) are still in flight;
+// requests complete in order, so the older groups have landed then -- whatever stores are also pending
+template <int L>
+__device__ __forceinline__ void wait_groups(int groups) {
+    if (groups >= 2) wait_vm_lgkm0<2 * L>();
+    else if (groups == 1) wait_vm_lgkm0<L>();
+    else wait_vm_lgkm0<0>();
+}
 
-    f32x16_t acc[MI][NI];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-    if constexpr (DMA) gemm_loop_dma<BM, BN>(acc, P.A, P.lda, P.B, P.N, P.K, M, m0, n0, lds);
-    else gemm_loop<BM, BN>(acc, P.A, P.lda, P.B, P.N, P.K, M, m0, n0, lds);
+// one k-step of the persistent loop on accumulator set `acc`.  ZERO: first step of a tile.  LAST: last
+// step of a tile -- the fragments of the following step are not read ahead, so that nothing but the
+// accumulators has to survive the epilogue.
+template <int BM, int BN, int EPI, bool ZERO, bool LAST>
+__device__ __forceinline__ void persist_step(f32x16_t (&acc)[BM / 64][BN / 64], bf16x8_t (&af0)[BM / 64], bf16x8_t (&bf0)[BN / 64],
+                                             bf16x8_t (&af1)[BM / 64], bf16x8_t (&bf1)[BN / 64], const char* ring, const FragAddr<BM, BN>& f,
+                                             Requester<BM, BN, EPI>& q, const PArgs& pa, uint32_t lds0, uint32_t& done, int wave, int lane) {
+    constexpr int L = BM / 64 + BN / 64;
+    constexpr int SB = dma_stage_bytes<BM, BN>();
+    const char* cur = ring + (done & (DSTAGES - 1)) * SB;
+    const char* nxt = ring + ((done + 1) & (DSTAGES - 1)) * SB;
+    dma_substep<BM, BN, ZERO>(acc, af0, bf0, af1, bf1, cur, f, 1);
+    wait_groups<L>((int)(q.issued - done) - 2);       // group done+1 has landed (own part), own reads of this stage are done
+    __builtin_amdgcn_s_barrier();
+    requester_step<BM, BN, EPI>(q, pa, lds0, wave, lane);   // into the stage just read by everyone
+    __builtin_amdgcn_sched_barrier(0);
+    dma_substep<BM, BN, false, !LAST>(acc, af1, bf1, af0, bf0, nxt, f, 0);
+    ++done;
+}
 
-    f32x16_t acc2[(EPI == PEPI_GATEUP) ? MI : 1][(EPI == PEPI_GATEUP) ? NI : 1];
-    if constexpr (EPI == PEPI_GATEUP) {
+// fragments of substep 0 of the stage at `stage` (which has landed and is barrier-visible)
+template <int BM, int BN>
+__device__ __forceinline__ void read_first_frags(bf16x8_t (&af)[BM / 64], bf16x8_t (&bf)[BN / 64], const char* stage, const FragAddr<BM, BN>& f) {
+    constexpr int MI = BM / 64;
+    dma_read_chunk<BM, BN, 0>(af, bf, stage, f, 0);
+    if constexpr (MI > 1) dma_read_chunk<BM, BN, 1>(af, bf, stage, f, 0);
+    if constexpr (MI > 2) dma_read_chunk<BM, BN, 2>(af, bf, stage, f, 0);
+    if constexpr (MI > 3) dma_read_chunk<BM, BN, 3>(af, bf, stage, f, 0);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// One accumulator element, read from where the MFMA left it.  Written as an explicit accvgpr read so
+// that the register allocator keeps the whole tile in the accumulator file until the moment of use
+// (left alone it moves every remaining element into vector registers at once and spills the rest).
+// The caller guarantees the MFMA -> read distance (s_nop after the last MFMA).
+__device__ __forceinline__ float acc_elem(float a) {
+    float r;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(a));
+    return r;
+}
+
+// Dense-cache row index (batch * S_max + position) of the 4 rows this lane stores for one block of 32
+// tile rows starting at row r0 (uniform), or -1.  With at least 32 tokens per sequence the block
+// touches at most two sequences and their positions come through the scalar path.
+__device__ __forceinline__ void cache_rows(int (&crow)[4], const int32_t* pos, int T, int S_max, int M, int r0, int rrow) {
+    if (T >= 32) {
+        const int rc = r0 < M ? r0 : M - 1;
+        const int bi0 = __builtin_amdgcn_readfirstlane(rc / T);
+        const int bl = (M - 1) / T;
+        const int bi1 = bi0 + 1 < bl ? bi0 + 1 : bl;
+        const int p0 = pos[bi0], p1 = pos[bi1];
+        const int edge = (bi0 + 1) * T;
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+        for (int it = 0; it < 4; ++it) {
+            const int m = r0 + it * 8 + rrow;
+            const bool second = m >= edge;
+            const int bi = second ? bi0 + 1 : bi0;
+            const int64_t pp = (int64_t)(second ? p1 : p0) + (m - bi * T);
+            crow[it] = (m < M && pp >= 0 && pp < S_max) ? bi * S_max + (int)pp : -1;
+        }
+    } else {
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc2[mi][ni][v] = 0.f;
-        if constexpr (DMA) gemm_loop_dma<BM, BN>(acc2, P.A2, P.lda2, P.B2, P.N, P.K2, M, m0, n0, lds);
-        else gemm_loop<BM, BN>(acc2, P.A2, P.lda2, P.B2, P.N, P.K2, M, m0, n0, lds);
+        for (int it = 0; it < 4; ++it) {
+            const int m = r0 + it * 8 + rrow;
+            const int mc = m < M ? m : M - 1;
+            const int bi = mc / T;
+            const int64_t pp = (int64_t)pos[bi] + (mc - bi * T);
+            crow[it] = (m < M && pp >= 0 && pp < S_max) ? bi * S_max + (int)pp : -1;
+        }
     }
+}
 
-    // ---- epilogue: registers -> bf16 staging tile in LDS -> coalesced 16-byte row stores
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+template <int BM, int BN, int EPI>
+__device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN / 64],
+                                              const f32x16_t (&acc2)[(EPI == PEPI_GATEUP) ? BM / 64 : 1][(EPI == PEPI_GATEUP) ? BN / 64 : 1],
+                                              const PProb& P, int M, int m0, int n0, char* patch, int wave, int lane) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    // the lane index goes through an opaque move: everything derived from it is recomputed here, per
+    // tile, instead of being hoisted out of the tile loop and held (or spilled) across the main loop
+    // ... and the matrix pipeline gets the distance it needs before its results are read (32 wait states)
+    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(lane));
     const int wm = wave >> 1, wn = wave & 1, li = lane & 31, lg = lane >> 5;
-    constexpr int CS = BN + 4;                        // staging row stride in bf16: 8-byte lanes of a wave sweep the banks
-    __syncthreads();                                  // main-loop LDS no longer needed
-    bf16_t* Cs = reinterpret_cast<bf16_t*>(lds);
+    const int rrow = lane >> 3, runit = lane & 7;                 // this lane's row (of 8) and unit when rows are read back
+    // the fields of this tile's problem, fetched once
+    bf16_t* const C = P.C; const int ldc = P.ldc, N = P.N;
+    const bf16_t* const bias = P.bias; const bf16_t* const bias2 = P.bias2;
+    bf16_t* const cache = (EPI == PEPI_STORE) ? reinterpret_cast<bf16_t*>(P.cache) : nullptr;
+    const int32_t* const pos = P.pos; const int S_max = P.S_max, T = P.T;
+    char* const wr = patch + li * 128 + lg * 8;                   // this lane's row of the patch when written
+    const int wsw = (li >> 1) & 7;
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+    for (int pr = 0; pr < NI / 2; ++pr) {
+        uint2 bgp[2][4], bup[2][4];                               // bias of this lane's columns, bf16 pairs as loaded
 #pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-            const int col = wn * (BN / 2) + ni * 32 + 8 * vg + 4 * lg;    // first of this lane's 4 consecutive columns
-            float bg[4] = {0.f, 0.f, 0.f, 0.f}, bu[4] = {0.f, 0.f, 0.f, 0.f};
-            if (P.bias) {
-                const uint2 raw = *reinterpret_cast<const uint2*>(P.bias + n0 + col);
-                bg[0] = __uint_as_float(raw.x << 16); bg[1] = __uint_as_float(raw.x & 0xffff0000u);
-                bg[2] = __uint_as_float(raw.y << 16); bg[3] = __uint_as_float(raw.y & 0xffff0000u);
-            }
-            if constexpr (EPI == PEPI_GATEUP) {
-                if (P.bias2) {
-                    const uint2 raw = *reinterpret_cast<const uint2*>(P.bias2 + n0 + col);
-                    bu[0] = __uint_as_float(raw.x << 16); bu[1] = __uint_as_float(raw.x & 0xffff0000u);
-                    bu[2] = __uint_as_float(raw.y << 16); bu[3] = __uint_as_float(raw.y & 0xffff0000u);
+        for (int p2 = 0; p2 < 2; ++p2)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) { bgp[p2][vg] = make_uint2(0u, 0u); bup[p2][vg] = make_uint2(0u, 0u); }
+        if (bias || (EPI == PEPI_GATEUP && bias2)) {
+#pragma unroll
+            for (int p2 = 0; p2 < 2; ++p2)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    int gcol = n0 + wn * (BN / 2) + (pr * 2 + p2) * 32 + 8 * vg + 4 * lg;
+                    gcol = gcol < N ? gcol : N - 4;                // clamped columns are never stored
+                    if (bias) bgp[p2][vg] = *reinterpret_cast<const uint2*>(bias + gcol);
+                    if constexpr (EPI == PEPI_GATEUP) { if (bias2) bup[p2][vg] = *reinterpret_cast<const uint2*>(bias2 + gcol); }
+                }
+        }
+        const int gcol = n0 + wn * (BN / 2) + pr * 64 + runit * 8;   // first of the 8 columns this lane stores
+        const bool col_ok = gcol < N;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int r0 = m0 + wm * (BM / 2) + mi * 32;
+            int crow[4] = {-1, -1, -1, -1};
+            if constexpr (EPI == PEPI_STORE) { if (cache) cache_rows(crow, pos, T, S_max, M, r0, rrow); }
+#pragma unroll
+            for (int p2 = 0; p2 < 2; ++p2)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    const int ni = pr * 2 + p2;
+                    const uint2 rg = bgp[p2][vg], ru = bup[p2][vg];
+                    const float bg[4] = {__uint_as_float(rg.x << 16), __uint_as_float(rg.x & 0xffff0000u),
+                                         __uint_as_float(rg.y << 16), __uint_as_float(rg.y & 0xffff0000u)};
+                    const float bu[4] = {__uint_as_float(ru.x << 16), __uint_as_float(ru.x & 0xffff0000u),
+                                         __uint_as_float(ru.y << 16), __uint_as_float(ru.y & 0xffff0000u)};
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if constexpr (EPI == PEPI_GATEUP)
+                            v[e] = silu_bf16out(acc_elem(acc[mi][ni][4 * vg + e]) + bg[e]) * (acc_elem(acc2[mi][ni][4 * vg + e]) + bu[e]);
+                        else
+                            v[e] = acc_elem(acc[mi][ni][4 * vg + e]) + bg[e];
+                    }
+                    uint2 o; o.x = ppack2(v[0], v[1]); o.y = ppack2(v[2], v[3]);
+                    *reinterpret_cast<uint2*>(wr + (((p2 * 4 + vg) ^ wsw) * 16)) = o;
+                }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {               // two rows in flight at a time: enough to cover the LDS latency
+                uint4 val[2];
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2) {
+                    const int row = (2 * h + i2) * 8 + rrow;
+                    val[i2] = *reinterpret_cast<const uint4*>(patch + row * 128 + ((runit ^ ((row >> 1) & 7)) * 16));
+                }
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2) {
+                    const int it = 2 * h + i2;
+                    const int m = r0 + it * 8 + rrow;
+                    if (C && col_ok && m < M) *reinterpret_cast<uint4*>(C + (size_t)m * ldc + gcol) = val[i2];
+                    if constexpr (EPI == PEPI_STORE) {
+                        if (col_ok && crow[it] >= 0) *reinterpret_cast<uint4*>(cache + (size_t)crow[it] * N + gcol) = val[i2];
+                    }
                 }
             }
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                const int row = wm * (BM / 2) + mi * 32 + li;             // token row inside the tile
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if constexpr (EPI == PEPI_GATEUP)
-                        v[e] = silu_f32(acc[mi][ni][4 * vg + e] + bg[e]) * (acc2[mi][ni][4 * vg + e] + bu[e]);
-                    else
-                        v[e] = acc[mi][ni][4 * vg + e] + bg[e];
-                }
-                uint2 o; o.x = ppack2(v[0], v[1]); o.y = ppack2(v[2], v[3]);
-                *reinterpret_cast<uint2*>(Cs + row * CS + col) = o;
-            }
+            __builtin_amdgcn_sched_barrier(0);      // keep the accumulator reads of later blocks from piling up in registers
         }
-    __syncthreads();
-    constexpr int CPR = BN / 8;                       // 16-byte chunks per tile row
-    constexpr int CHUNKS = BM * CPR;
-#pragma unroll 4
-    for (int c = tid; c < CHUNKS; c += 256) {
-        const int row = c / CPR, ch = c % CPR;
-        const int m = m0 + row;
-        if (m >= M) continue;
-        const uint2 lo = *reinterpret_cast<const uint2*>(Cs + row * CS + ch * 8);
-        const uint2 hi = *reinterpret_cast<const uint2*>(Cs + row * CS + ch * 8 + 4);
-        const uint4 val = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        if (P.C) *reinterpret_cast<uint4*>(P.C + (size_t)m * P.ldc + n0 + ch * 8) = val;
-        if constexpr (EPI == PEPI_STORE) {
-            if (P.cache) {
-                const int bi = m / P.T, s = m - bi * P.T;
-                const int64_t pp = (int64_t)P.pos[bi] + s;
-                if (pp >= 0 && pp < P.S_max)
-                    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(P.cache) + ((size_t)bi * P.S_max + (size_t)pp) * P.N + n0 + ch * 8) = val;
-            }
+    }
+}
+
+template <int BM, int BN, int EPI, int MINB>
+__global__ void __launch_bounds__(256, MINB) k_prefill_persist(PArgs pa) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    constexpr int L = MI + NI;
+    __shared__ uint4 lds[persist_lds_bytes<BM, BN>() / 16];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const char* ring = reinterpret_cast<const char*>(lds);
+    char* patch = reinterpret_cast<char*>(lds) + DSTAGES * dma_stage_bytes<BM, BN>() + wave * 4096;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
+
+    FragAddr<BM, BN> f;
+    frag_setup<BM, BN>(f);
+
+    Requester<BM, BN, EPI> q;
+    q.w = walk_begin(pa); q.issued = 0; q.phase = 0; q.kt = 0;
+    q.live = walk_next<BM, BN>(q.w, pa, q.prob, q.m0, q.n0);
+    if (!q.live) return;                                    // no tile for this workgroup (whole workgroup leaves)
+    requester_open<BM, BN, EPI>(q, pa, wave, lane);
+    for (int i = 0; i < DSTAGES; ++i) requester_step<BM, BN, EPI>(q, pa, lds0, wave, lane);
+
+    TileWalk cw = walk_begin(pa);
+    int prob, m0, n0;
+    uint32_t done = 0;
+    wait_groups<L>((int)q.issued - 1);                      // group 0 has landed
+    __builtin_amdgcn_s_barrier();
+    bf16x8_t af0[MI], bf0[NI], af1[MI], bf1[NI];
+
+    while (walk_next<BM, BN>(cw, pa, prob, m0, n0)) {
+        const PProb& P = pa.p[prob];
+        f32x16_t acc[MI][NI];
+        f32x16_t acc2[(EPI == PEPI_GATEUP) ? MI : 1][(EPI == PEPI_GATEUP) ? NI : 1];
+        const int nk = P.K / DBK;                  // >= 2
+        read_first_frags<BM, BN>(af0, bf0, ring + (done & (DSTAGES - 1)) * dma_stage_bytes<BM, BN>(), f);
+        persist_step<BM, BN, EPI, true, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+        for (int kt = 2; kt < nk; ++kt)
+            persist_step<BM, BN, EPI, false, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+        if constexpr (EPI == PEPI_GATEUP) {
+            const int nk2 = P.K2 / DBK;
+            persist_step<BM, BN, EPI, false, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+            persist_step<BM, BN, EPI, true, false>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+            for (int kt = 2; kt < nk2; ++kt)
+                persist_step<BM, BN, EPI, false, false>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+            persist_step<BM, BN, EPI, false, true>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+        } else {
+            persist_step<BM, BN, EPI, false, true>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
         }
+        wave_epilogue<BM, BN, EPI>(acc, acc2, P, pa.M, m0, n0, patch, wave, lane);
     }
 }
 
@@ -500,15 +502,17 @@ bool prefill_shape_ok(int64_t M, int64_t K, int64_t N) {
            K < (1 << 24) && N < (1 << 24);
 }
 
-template <int BM, int BN, int EPI, int MINB, bool DMA>
-static int launch_cfg(PArgs a, hipStream_t s) {
+template <int BM, int BN, int EPI, int MINB>
+static int launch_persist(PArgs a, hipStream_t s) {
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n_max = 0;
     for (int i = 0; i < a.nprob; ++i) { const int t = (a.p[i].N + BN - 1) / BN; if (t > a.tiles_n_max) a.tiles_n_max = t; }
     const int total = a.tiles_m * a.tiles_n_max * a.nprob;
     a.group_m = 8;
     a.trace = g_trace_buffer;
-    hipLaunchKernelGGL((k_prefill_gemm<BM, BN, EPI, MINB, DMA>), dim3((unsigned)total), dim3(256), 0, s, a);
+    const int per_xcd = (total + 7) / 8;
+    const int slots = per_xcd < 32 * MINB ? per_xcd : 32 * MINB;      // workgroups per XCD
+    hipLaunchKernelGGL((k_prefill_persist<BM, BN, EPI, MINB>), dim3((unsigned)(8 * slots)), dim3(256), 0, s, a);
     return launch_status("prefill gemm");
 }
 
@@ -516,33 +520,37 @@ static int env_int(const char* name) { const char* v = getenv(name); return v ? 
 static int env_shape() { static int v = env_int("LOWRANK_PREFILL_SHAPE"); return v; }
 static int env_gu() { static int v = env_int("LOWRANK_PREFILL_GU"); return v; }
 
-static bool want_bm256(const PArgs& a) {
-    long tiles = 0;
-    for (int i = 0; i < a.nprob; ++i) tiles += (long)((a.M + 255) / 256) * (a.p[i].N / 128);
-    return tiles >= 4 * 512;
+// Tile shape of a plain launch, from a two-line cost model fitted to measurements on this chip, in
+// units of "one 256 x 256 tile on one CU": the 256 x 256 kernel (one workgroup per CU) does one unit
+// per round; the 128 x 128 kernel needs 0.46 for its quarter-size tile when every tile has a CU to
+// itself, and 0.64 per round of two tiles per CU otherwise.  Big-N products with short K (the
+// reconstruction x V) go to 256 x 256, the rank-space products with few columns to 128 x 128.
+static bool want_256(const PArgs& a) {
+    long t256 = 0, t128 = 0;
+    for (int i = 0; i < a.nprob; ++i) {
+        t256 += (long)((a.M + 255) / 256) * ((a.p[i].N + 255) / 256);
+        t128 += (long)((a.M + 127) / 128) * ((a.p[i].N + 127) / 128);
+    }
+    const double c256 = (double)((t256 + 255) / 256);
+    const double c128 = t128 <= 256 ? 0.46 : 0.64 * (double)((t128 + 511) / 512);
+    return c256 <= c128;
 }
 
 int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
     if (a.M <= 0 || a.nprob <= 0) return LR_OK;
-    bool n256 = true;
-    for (int i = 0; i < a.nprob; ++i) n256 = n256 && (a.p[i].N % 256 == 0);
     if (epi == PEPI_GATEUP) {
-        switch (env_gu()) {
-            case 0: return launch_cfg<128, 128, PEPI_GATEUP, 2, false>(a, s);
-            case 2: return launch_cfg<256, 128, PEPI_GATEUP, 1, true>(a, s);
-            default: return launch_cfg<128, 128, PEPI_GATEUP, 2, true>(a, s);
-        }
+        if (env_gu() == 0) return launch_persist<256, 128, PEPI_GATEUP, 1>(a, s);
+        return launch_persist<128, 128, PEPI_GATEUP, 2>(a, s);
     }
-    switch (env_shape()) {
-        case 0: if (n256) return launch_cfg<256, 256, PEPI_STORE, 1, true>(a, s); break;
-        case 1: return launch_cfg<256, 128, PEPI_STORE, 2, false>(a, s);
-        case 2: return launch_cfg<128, 128, PEPI_STORE, 2, false>(a, s);
-        case 3: return launch_cfg<256, 128, PEPI_STORE, 1, true>(a, s);
-        case 4: if (n256) return launch_cfg<128, 256, PEPI_STORE, 1, true>(a, s); break;
-        case 5: return launch_cfg<128, 128, PEPI_STORE, 2, true>(a, s);
+    switch (env_shape()) {      // measurement override
+        case 0: return launch_persist<256, 256, PEPI_STORE, 1>(a, s);
+        case 1: return launch_persist<128, 128, PEPI_STORE, 2>(a, s);
+        case 2: return launch_persist<256, 128, PEPI_STORE, 1>(a, s);
+        case 3: return launch_persist<128, 256, PEPI_STORE, 1>(a, s);
         default: break;
     }
-    return launch_cfg<128, 128, PEPI_STORE, 2, true>(a, s);
+    if (want_256(a)) return launch_persist<256, 256, PEPI_STORE, 1>(a, s);
+    return launch_persist<128, 128, PEPI_STORE, 2>(a, s);
 }
 
 }  // namespace lr
