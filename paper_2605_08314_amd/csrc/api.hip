@@ -59,13 +59,13 @@ static Plan pick_plan(int dtype, int phase, int64_t M, bool decode_ok, bool pref
 }
 
 static size_t ws_bytes_for(int op, int64_t M, int64_t r_total, int64_t d_out) {
-    // header | accumulator area 0 | accumulator area 1 | staging (two quarters), see ws_layout().
+    // header | accumulator area 0 | accumulator area 1 | staging (two quarters) | shared-K tail, see ws_layout().
     // A quarter holds the fp32 rank-space rows [M, r_total]; for the MLP also fp32 [M, ffn], so
     // that the staging half fits rank-space rows plus hidden rows in any kernel family.
     size_t q = align256((size_t)M * (size_t)r_total * 4);
     if (op == LR_OP_PACKED_MLP) { const size_t hq = align256((size_t)M * (size_t)d_out * 4); if (hq > q) q = hq; }
     if (q < 256) q = 256;
-    return kHeaderBytes + 4 * q;
+    return kHeaderBytes + 4 * q + sk_tail_bytes(M);
 }
 
 }  // namespace lr
@@ -140,7 +140,7 @@ int lowrank_linear(const void* x, const void* U, const void* V, const void* bias
                                 prefill_shape_ok(M, d_in, r) && prefill_shape_ok(M, r, d_out), al);
     if (plan == PLAN_DECODE) return decode_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
     if (plan == PLAN_PREFILL) return prefill_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
-    float* t = (float*)ws_layout(workspace, workspace_bytes).staging;
+    float* t = (float*)ws_layout(workspace, workspace_bytes, M).staging;
     CacheDst none = {nullptr, nullptr, 0, 1};
     st = generic_stage1(x, false, U, t, r, M, d_in, r, dtype, s);
     if (st != LR_OK) return st;
@@ -205,7 +205,7 @@ int lowrank_qkv(const void* x, const void* const* U, const void* const* V, const
         return decode_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, workspace_bytes, s);
     if (plan == PLAN_PREFILL)
         return prefill_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, workspace_bytes, s);
-    float* t = (float*)ws_layout(workspace, workspace_bytes).staging;
+    float* t = (float*)ws_layout(workspace, workspace_bytes, M).staging;
     const int64_t ldt = R > 0 ? R : 1;
     for (int i = 0; i < n_proj; ++i)
         if (base_of[i] == i) {
@@ -246,7 +246,7 @@ int lowrank_packed_mlp(const void* x, const void* U_gu, const void* V_g, const v
         return decode_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, workspace_bytes, s);
     if (plan == PLAN_PREFILL)
         return prefill_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, workspace_bytes, s);
-    char* base = ws_layout(workspace, workspace_bytes).staging;
+    char* base = ws_layout(workspace, workspace_bytes, M).staging;
     float* t = (float*)base;                                   // [M, r_g + r_u + r_d]
     float* h = (float*)(base + align256((size_t)M * (size_t)r_total * 4));       // [M, ffn]
     const int64_t ldt = r_total > 0 ? r_total : 1;

@@ -44,17 +44,32 @@ struct Ctrl {
 };
 static_assert(sizeof(Ctrl) <= kHeaderBytes, "control block must fit the workspace header");
 
-// Where the parts of a workspace of `ws_bytes` bytes sit: header | acc area 0 | acc area 1 | staging.
+// Tail of a workspace that may serve a prefill call (more than 32 token rows): flags and fp32 partial
+// tiles of products whose K range is shared between workgroups (256 slots of one 256 x 256 tile, or
+// 512 of 128 x 128).  Zero when prepared; every call leaves the flags zero.
+constexpr size_t kSkFlagBytes = 4096;
+constexpr size_t kSkSlotBytes = (size_t)256 * 256 * 256 * 4;
+constexpr size_t kSkBytes = kSkFlagBytes + kSkSlotBytes;
+inline size_t sk_tail_bytes(int64_t M) { return M > 32 ? kSkBytes : 0; }
+
+// Where the parts of a workspace of `ws_bytes` bytes for M token rows sit:
+// header | acc area 0 | acc area 1 | staging | shared-K tail (M > 32 only).
 struct WsLayout {
     Ctrl* ctrl; char* acc0; size_t acc_bytes; char* staging; size_t staging_bytes;
+    uint32_t* sk_flags; float* sk_slots;       // NULL without the tail
 };
-inline WsLayout ws_layout(void* ws, size_t ws_bytes) {
+inline WsLayout ws_layout(void* ws, size_t ws_bytes, int64_t M) {
     WsLayout L;
+    const size_t tail = sk_tail_bytes(M);
+    const size_t body = ws_bytes - tail;
     L.ctrl = (Ctrl*)ws;
-    L.acc_bytes = ((ws_bytes - kHeaderBytes) / 4) & ~(size_t)255;
+    L.acc_bytes = ((body - kHeaderBytes) / 4) & ~(size_t)255;
     L.acc0 = (char*)ws + kHeaderBytes;
     L.staging = L.acc0 + 2 * L.acc_bytes;
-    L.staging_bytes = ws_bytes - kHeaderBytes - 2 * L.acc_bytes;
+    L.staging_bytes = body - kHeaderBytes - 2 * L.acc_bytes;
+    char* t = (char*)ws + (body & ~(size_t)255);
+    L.sk_flags = tail ? (uint32_t*)t : nullptr;
+    L.sk_slots = tail ? (float*)(t + kSkFlagBytes) : nullptr;
     return L;
 }
 

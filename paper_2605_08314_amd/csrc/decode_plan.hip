@@ -113,7 +113,7 @@ static bool use_t16(int64_t M, int64_t col_tiles) {
 
 static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* sk_in, int nb, const Final* fin_in,
                          int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s) {
-    const WsLayout L = ws_layout(ws, ws_bytes);
+    const WsLayout L = ws_layout(ws, ws_bytes, M);
     size_t factor_bytes = 0;
     for (int i = 0; i < nb; ++i) factor_bytes += (size_t)d_in * sk_in[i].N * 2;
     for (int i = 0; i < nf; ++i) factor_bytes += (size_t)fin_in[i].r * fin_in[i].N * 2;
@@ -179,7 +179,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
                int64_t M, int64_t d, int64_t ffn, int64_t r_g, int64_t r_u, int64_t r_d,
                void* ws, size_t ws_bytes, hipStream_t s) {
     const int64_t r_gu = r_g + r_u, r_all = r_gu + r_d;
-    const WsLayout L = ws_layout(ws, ws_bytes);
+    const WsLayout L = ws_layout(ws, ws_bytes, M);
     const int G = fused_grid(((size_t)d * r_gu + (size_t)(r_g + r_u) * ffn + (size_t)ffn * r_d + (size_t)r_d * d) * 2);
     const bool fused = G > 0 && (size_t)M * r_all * 4 <= L.acc_bytes;
     // rank-space accumulators t[M, r_g + r_u + r_d] (fp32), the bf16 hidden rows h[M, ffn] and, for more

@@ -25,6 +25,10 @@ struct PArgs {
     int tiles_n_max;    // max over problems of ceil(N / BN)
     int group_m;        // tile rows per L2 group of the tile order
     unsigned long long* trace;   // timeline buffer of trace builds, else NULL
+    // products whose K range is shared between workgroups: flags, fp32 partial-tile slots, error word
+    uint32_t* sk_flags; float* sk_slots; uint32_t* err;
+    int sk;             // 1: the launch walks k-step ranges, not tiles
+    int sk_nk;          // k-steps (of 32) per tile in that case
 };
 
 bool prefill_shape_ok(int64_t M, int64_t K, int64_t N);

@@ -132,36 +132,68 @@ __device__ __forceinline__ void dma_read_chunk(bf16x8_t (&afn)[BM / 64], bf16x8_
 }
 
 // chunk C of a substep: its share of the next substep's fragment reads, then the MFMAs of row block C
-template <int BM, int BN, int C, bool ZERO = false, bool READ = true>
-__device__ __forceinline__ void dma_chunk(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64],
-                                          bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* nstage,
-                                          const FragAddr<BM, BN>& f, int nkk) {
-    constexpr int MI = BM / 64, NI = BN / 64;
-    if constexpr (C < MI) {
-        if constexpr (READ) dma_read_chunk<BM, BN, C>(afn, bfn, nstage, f, nkk);
+// No requests between the MFMAs of a substep.
+struct NoIssue { template <int J> __device__ __forceinline__ void issue() const {} };
+
+// MFMA number NIi of chunk C, followed by the request instruction (if any) that belongs behind it: the
+// L request instructions of a step are spread evenly over the MI * NI MFMAs of a substep.  A request
+// occupies the issue port for tens of cycles while the memory pipeline takes it in; right behind an
+// MFMA it hides under that MFMA's 32 cycles, whereas a burst of 8 stalls the matrix pipeline.
+template <int BM, int BN, int C, int NIi, bool ZERO, class IS>
+__device__ __forceinline__ void dma_mfma_one(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64], const IS& is) {
+    constexpr int MI = BM / 64, NI = BN / 64, S = MI * NI, L = MI + NI;
+    if constexpr (NIi < NI) {
 #ifndef LR_ABLATE_MFMA
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            if constexpr (ZERO) {       // first product of a tile: the accumulator starts from the constant 0
-                const f32x16_t z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                acc[C][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[ni], afc[C], z, 0, 0, 0);
-            } else {
-                acc[C][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[ni], afc[C], acc[C][ni], 0, 0, 0);
-            }
+        if constexpr (ZERO) {       // first product of a tile: the accumulator starts from the constant 0
+            const f32x16_t z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            acc[C][NIi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[NIi], afc[C], z, 0, 0, 0);
+        } else {
+            acc[C][NIi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[NIi], afc[C], acc[C][NIi], 0, 0, 0);
         }
 #endif
+        constexpr int slot = C * NI + NIi;
+        constexpr int j = (slot * L + S - 1) / S;           // the request whose place floor(j * S / L) could be this slot
+        if constexpr (j < L && (j * S) / L == slot) {
+            __builtin_amdgcn_sched_barrier(0);
+            is.template issue<j>();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// chunk C of a substep: its share of the next substep's fragment reads, then the MFMAs of row block C
+template <int BM, int BN, int C, bool ZERO, bool READ, class IS>
+__device__ __forceinline__ void dma_chunk(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64],
+                                          bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* nstage,
+                                          const FragAddr<BM, BN>& f, int nkk, const IS& is) {
+    constexpr int MI = BM / 64;
+    if constexpr (C < MI) {
+        // the reads are packed into the first chunks so that the last ones are a chunk of MFMAs old when
+        // the wave waits for them in front of the barrier
+        if constexpr (READ) {
+            if constexpr (C == 0) {
+                dma_read_chunk<BM, BN, 0>(afn, bfn, nstage, f, nkk);
+                if constexpr (MI > 1) dma_read_chunk<BM, BN, 1>(afn, bfn, nstage, f, nkk);
+            } else if constexpr (C + 1 < MI) {
+                dma_read_chunk<BM, BN, C + 1>(afn, bfn, nstage, f, nkk);
+            }
+        }
+        dma_mfma_one<BM, BN, C, 0, ZERO, IS>(acc, afc, bfc, is);
+        dma_mfma_one<BM, BN, C, 1, ZERO, IS>(acc, afc, bfc, is);
+        dma_mfma_one<BM, BN, C, 2, ZERO, IS>(acc, afc, bfc, is);
+        dma_mfma_one<BM, BN, C, 3, ZERO, IS>(acc, afc, bfc, is);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-template <int BM, int BN, bool ZERO = false, bool READ = true>
+template <int BM, int BN, bool ZERO, bool READ, class IS>
 __device__ __forceinline__ void dma_substep(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64],
                                             bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* nstage,
-                                            const FragAddr<BM, BN>& f, int nkk) {
-    dma_chunk<BM, BN, 0, ZERO, READ>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
-    dma_chunk<BM, BN, 1, ZERO, READ>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
-    dma_chunk<BM, BN, 2, ZERO, READ>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
-    dma_chunk<BM, BN, 3, ZERO, READ>(acc, afc, bfc, afn, bfn, nstage, f, nkk);
+                                            const FragAddr<BM, BN>& f, int nkk, const IS& is) {
+    dma_chunk<BM, BN, 0, ZERO, READ, IS>(acc, afc, bfc, afn, bfn, nstage, f, nkk, is);
+    dma_chunk<BM, BN, 1, ZERO, READ, IS>(acc, afc, bfc, afn, bfn, nstage, f, nkk, is);
+    dma_chunk<BM, BN, 2, ZERO, READ, IS>(acc, afc, bfc, afn, bfn, nstage, f, nkk, is);
+    dma_chunk<BM, BN, 3, ZERO, READ, IS>(acc, afc, bfc, afn, bfn, nstage, f, nkk, is);
 }
 
 // ---- persistent form ----------------------------------------------------------------------------
@@ -178,7 +210,6 @@ struct Stream {
     const char* sa; const char* sb;
     uint32_t voa[BM / 64], vob[BN / 64];
     uint32_t step_b;
-    int nk;
 };
 
 template <int BM, int BN>
@@ -188,7 +219,6 @@ __device__ __forceinline__ void stream_setup(Stream<BM, BN>& c, const bf16_t* A,
     c.sa = reinterpret_cast<const char*>(A + (size_t)m0 * lda);
     c.sb = reinterpret_cast<const char*>(B + n0);
     c.step_b = (uint32_t)DBK * (uint32_t)N * 2u;
-    c.nk = K / DBK;
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
         const int row = (wave * NA + j) * 16 + (lane >> 2), pos = lane & 3;
@@ -204,75 +234,148 @@ __device__ __forceinline__ void stream_setup(Stream<BM, BN>& c, const bf16_t* A,
     }
 }
 
-template <int BM, int BN>
-__device__ __forceinline__ void stream_issue(const Stream<BM, BN>& c, int kt, uint32_t stage_lds, int wave) {
-    constexpr int NA = BM / 64, NR = BN / 64;
-    const char* ga = c.sa + (size_t)kt * (DBK * 2);
-    const char* gb = c.sb + (size_t)kt * c.step_b;
-#pragma unroll
-    for (int j = 0; j < NA; ++j) dma16(stage_lds + (uint32_t)(wave * NA + j) * 1024u, c.voa[j], ga);
-#pragma unroll
-    for (int j = 0; j < NR; ++j) dma16(stage_lds + (uint32_t)(BM * 64) + (uint32_t)(wave * NR + j) * 1024u, c.vob[j], gb);
+// a wave-uniform pointer, said so to the compiler (it then sits in scalar registers)
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>((uintptr_t)(((uint64_t)hi << 32) | lo));
 }
 
-// The tiles of one workgroup.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2):
-// XCD x owns a contiguous eighth of the logical tile order, and its workgroups take consecutive
-// logical tiles together, round after round.  The logical order walks groups of group_m tile rows
-// column by column, so tiles in flight on one XCD share A row-panels and B column-panels.
-struct TileWalk { int next, end, stride; };
+// The request instructions of one k-step, to be issued one by one (issue<J>, J < NA + NR).
+template <int BM, int BN>
+struct StepIssue {
+    static constexpr int NA = BM / 64, NR = BN / 64;
+    const Stream<BM, BN>* st;
+    const char* ga; const char* gb;         // uniform: this step's origin in A and B
+    uint32_t stage_lds;                     // uniform: LDS byte address of the ring stage
+    int wave;
+    bool on;                                // uniform: false when nothing is left to request
+    template <int J> __device__ __forceinline__ void issue() const {
+        if (on) {
+            if constexpr (J < NA) dma16(stage_lds + (uint32_t)(wave * NA + J) * 1024u, st->voa[J], ga);
+            else dma16(stage_lds + (uint32_t)(BM * 64) + (uint32_t)(wave * NR + (J - NA)) * 1024u, st->vob[J - NA], gb);
+        }
+    }
+};
 
-__device__ __forceinline__ TileWalk walk_begin(const PArgs& pa) {
-    const int total = pa.tiles_m * pa.tiles_n_max * pa.nprob;
-    const int per_xcd = (total + 7) >> 3;
-    const int x = blockIdx.x & 7, j = blockIdx.x >> 3, slots = gridDim.x >> 3;
-    TileWalk w;
-    w.next = x * per_xcd + j;
-    w.end = (x + 1) * per_xcd < total ? (x + 1) * per_xcd : total;
-    w.stride = slots;
+template <int BM, int BN>
+__device__ __forceinline__ StepIssue<BM, BN> stream_step(const Stream<BM, BN>& c, int kt, uint32_t stage_lds, int wave, bool on) {
+    StepIssue<BM, BN> is;
+    is.st = &c;
+    is.ga = uniform_ptr(c.sa + (size_t)kt * (DBK * 2));
+    is.gb = uniform_ptr(c.sb + (size_t)kt * c.step_b);
+    is.stage_lds = __builtin_amdgcn_readfirstlane(stage_lds);
+    is.wave = wave; is.on = on;
+    return is;
+}
+
+template <int BM, int BN, int J>
+__device__ __forceinline__ void issue_all(const StepIssue<BM, BN>& is) {
+    if constexpr (J < BM / 64 + BN / 64) { is.template issue<J>(); issue_all<BM, BN, J + 1>(is); }
+}
+
+// The work of one workgroup, as a sequence of segments: a tile and a range of its k-steps.
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so "logical" workgroup
+// (id % 8) * (grid / 8) + id / 8 makes the workgroups of one XCD neighbours in the logical order.
+// The logical tile order walks groups of group_m tile rows column by column, so tiles in flight on
+// one XCD share A row-panels and B column-panels.
+//   tile walk (pa.sk == 0): XCD x owns a contiguous eighth of the tiles and its workgroups take
+//     consecutive tiles together, round after round; every segment is a whole tile.
+//   shared-K walk (pa.sk == 1, all problems of one shape): the launch is one long sequence of k-steps
+//     (tile after tile), cut into equal ranges, one per logical workgroup.  A workgroup whose range
+//     starts inside a tile hands its partial sums (fp32) to the workgroup holding the tile's k = 0 step.
+struct Seg { int prob, m0, n0, kb, ke; };
+struct Walk { int next, end, stride; };      // tile walk: tile ids; shared-K walk: k-step units [next, end)
+
+__device__ __forceinline__ int logical_wg() { return (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3); }
+__device__ __forceinline__ int sk_unit_begin(const PArgs& pa, int wl) {   // first k-step unit of logical workgroup wl
+    const long long units = (long long)pa.tiles_m * pa.tiles_n_max * pa.nprob * pa.sk_nk;
+    return (int)(units * wl / (int)gridDim.x);
+}
+
+__device__ __forceinline__ Walk walk_begin(const PArgs& pa) {
+    Walk w;
+    if (pa.sk) {
+        const int wl = logical_wg();
+        w.next = sk_unit_begin(pa, wl); w.end = sk_unit_begin(pa, wl + 1); w.stride = 0;
+    } else {
+        const int total = pa.tiles_m * pa.tiles_n_max * pa.nprob;
+        const int per_xcd = (total + 7) >> 3;
+        const int x = blockIdx.x & 7, j = blockIdx.x >> 3, slots = gridDim.x >> 3;
+        w.next = x * per_xcd + j;
+        w.end = (x + 1) * per_xcd < total ? (x + 1) * per_xcd : total;
+        w.stride = slots;
+    }
     return w;
 }
 
 template <int BM, int BN>
-__device__ __forceinline__ bool walk_next(TileWalk& w, const PArgs& pa, int& prob, int& m0, int& n0) {
+__device__ __forceinline__ bool tile_of(const PArgs& pa, int id, Seg& sg) {
     const int per_prob = pa.tiles_m * pa.tiles_n_max;
     const int gsz = pa.group_m * pa.tiles_n_max;
+    const int pr = id / per_prob, rem = id - pr * per_prob;
+    const int mg = rem / gsz, r = rem - mg * gsz;
+    const int rows_here = (pa.tiles_m - mg * pa.group_m) < pa.group_m ? (pa.tiles_m - mg * pa.group_m) : pa.group_m;
+    const int tn = r / rows_here, tm = mg * pa.group_m + (r - tn * rows_here);
+    sg.prob = pr; sg.m0 = tm * BM; sg.n0 = tn * BN;
+    return tn * BN < pa.p[pr].N;
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ bool walk_next(Walk& w, const PArgs& pa, Seg& sg) {
+    if (pa.sk) {
+        if (w.next >= w.end) return false;
+        const int tile = w.next / pa.sk_nk;
+        sg.kb = w.next - tile * pa.sk_nk;
+        const int left = w.end - w.next;
+        sg.ke = sg.kb + left < pa.sk_nk ? sg.kb + left : pa.sk_nk;
+        w.next += sg.ke - sg.kb;
+        tile_of<BM, BN>(pa, tile, sg);           // every tile of a shared-K launch is a real one
+        return true;
+    }
     while (w.next < w.end) {
         const int id = w.next;
         w.next += w.stride;
-        const int pr = id / per_prob, rem = id - pr * per_prob;
-        const int mg = rem / gsz, r = rem - mg * gsz;
-        const int rows_here = (pa.tiles_m - mg * pa.group_m) < pa.group_m ? (pa.tiles_m - mg * pa.group_m) : pa.group_m;
-        const int tn = r / rows_here, tm = mg * pa.group_m + (r - tn * rows_here);
-        if (tn * BN < pa.p[pr].N) { prob = pr; m0 = tm * BM; n0 = tn * BN; return true; }
+        if (tile_of<BM, BN>(pa, id, sg)) { sg.kb = 0; sg.ke = pa.p[sg.prob].K / DBK; return true; }
     }
     return false;
 }
 
 template <int BM, int BN, int EPI>
 struct Requester {
-    TileWalk w;
+    Walk w;
+    Seg sg;
     Stream<BM, BN> st;
-    int kt, phase, prob, m0, n0;
+    int kt, kend, phase;
     bool live;
     uint32_t issued;
 };
 
 template <int BM, int BN, int EPI>
 __device__ __forceinline__ void requester_open(Requester<BM, BN, EPI>& q, const PArgs& pa, int wave, int lane) {
-    const PProb& P = pa.p[q.prob];
-    if (q.phase == 0) stream_setup<BM, BN>(q.st, P.A, P.lda, P.B, P.N, P.K, pa.M, q.m0, q.n0, wave, lane);
-    else stream_setup<BM, BN>(q.st, P.A2, P.lda2, P.B2, P.N, P.K2, pa.M, q.m0, q.n0, wave, lane);
-    q.kt = 0;
+    const PProb& P = pa.p[q.sg.prob];
+    if (q.phase == 0) {
+        stream_setup<BM, BN>(q.st, P.A, P.lda, P.B, P.N, P.K, pa.M, q.sg.m0, q.sg.n0, wave, lane);
+        q.kt = q.sg.kb; q.kend = q.sg.ke;
+    } else {
+        stream_setup<BM, BN>(q.st, P.A2, P.lda2, P.B2, P.N, P.K2, pa.M, q.sg.m0, q.sg.n0, wave, lane);
+        q.kt = 0; q.kend = P.K2 / DBK;
+    }
 }
 
+// the requests of the next step, not yet issued
 template <int BM, int BN, int EPI>
-__device__ __forceinline__ void requester_step(Requester<BM, BN, EPI>& q, const PArgs& pa, uint32_t lds0, int wave, int lane) {
+__device__ __forceinline__ StepIssue<BM, BN> requester_next(const Requester<BM, BN, EPI>& q, uint32_t lds0, int wave) {
+    return stream_step<BM, BN>(q.st, q.kt, lds0 + (q.issued & (DSTAGES - 1)) * dma_stage_bytes<BM, BN>(), wave, q.live);
+}
+// ... and the bookkeeping once they have been issued
+template <int BM, int BN, int EPI>
+__device__ __forceinline__ void requester_advance(Requester<BM, BN, EPI>& q, const PArgs& pa, int wave, int lane) {
     if (!q.live) return;
-    stream_issue<BM, BN>(q.st, q.kt, lds0 + (q.issued & (DSTAGES - 1)) * dma_stage_bytes<BM, BN>(), wave);
     ++q.issued;
-    if (++q.kt == q.st.nk) {
+    if (++q.kt == q.kend) {
         if (EPI == PEPI_GATEUP && q.phase == 0) { q.phase = 1; }
-        else { q.phase = 0; q.live = walk_next<BM, BN>(q.w, pa, q.prob, q.m0, q.n0); }
+        else { q.phase = 0; q.live = walk_next<BM, BN>(q.w, pa, q.sg); }
         if (q.live) requester_open<BM, BN, EPI>(q, pa, wave, lane);
     }
 }
@@ -297,12 +400,16 @@ __device__ __forceinline__ void persist_step(f32x16_t (&acc)[BM / 64][BN / 64], 
     constexpr int SB = dma_stage_bytes<BM, BN>();
     const char* cur = ring + (done & (DSTAGES - 1)) * SB;
     const char* nxt = ring + ((done + 1) & (DSTAGES - 1)) * SB;
-    dma_substep<BM, BN, ZERO>(acc, af0, bf0, af1, bf1, cur, f, 1);
+    dma_substep<BM, BN, ZERO, true, NoIssue>(acc, af0, bf0, af1, bf1, cur, f, 1, NoIssue());
     wait_groups<L>((int)(q.issued - done) - 2);       // group done+1 has landed (own part), own reads of this stage are done
     __builtin_amdgcn_s_barrier();
-    requester_step<BM, BN, EPI>(q, pa, lds0, wave, lane);   // into the stage just read by everyone
+    // the next requests go into the stage just read by everyone.  (Spreading them between the MFMAs of
+    // the second substep instead of issuing them together was measured: no gain for 256 x 256 tiles,
+    // a loss for 128 x 128.)
+    issue_all<BM, BN, 0>(requester_next<BM, BN, EPI>(q, lds0, wave));
+    requester_advance<BM, BN, EPI>(q, pa, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
-    dma_substep<BM, BN, false, !LAST>(acc, af1, bf1, af0, bf0, nxt, f, 0);
+    dma_substep<BM, BN, false, !LAST, NoIssue>(acc, af1, bf1, af0, bf0, nxt, f, 0, NoIssue());
     ++done;
 }
 
@@ -325,6 +432,55 @@ __device__ __forceinline__ float acc_elem(float a) {
     float r;
     asm("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(a));
     return r;
+}
+
+// 8-byte accesses that are coherent across the whole device (they go past this XCD's L2): for the
+// partial sums and flags that workgroups of one launch hand to each other.
+__device__ __forceinline__ uint2 ld_dev_b64(const void* p) {
+    const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+}
+__device__ __forceinline__ void st_dev_b64(void* p, float lo, float hi) {
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), (uint64_t)__float_as_uint(lo) | ((uint64_t)__float_as_uint(hi) << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Slot layout of a partial tile: float4 index ((wave * MI * NI + mi * NI + ni) * 4 + vg) * 64 + lane holds
+// accumulator elements 4 vg .. 4 vg + 3 of block (mi, ni) -- every store instruction of a wave covers
+// 1 KB of consecutive memory, and the reader is the same lane of the same wave of another workgroup.
+template <int BM, int BN>
+__device__ __forceinline__ size_t part_index(int wave, int mi, int ni, int vg, int lane) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    return ((size_t)((wave * MI * NI + mi * NI + ni) * 4 + vg) * 64 + lane) * 4;
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void store_partial(const f32x16_t (&acc)[BM / 64][BN / 64], float* slot, int wave, int lane) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(lane));    // MFMA -> accumulator read distance
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                float* d = slot + part_index<BM, BN>(wave, mi, ni, vg, lane);
+                st_dev_b64(d, acc_elem(acc[mi][ni][4 * vg + 0]), acc_elem(acc[mi][ni][4 * vg + 1]));
+                st_dev_b64(d + 2, acc_elem(acc[mi][ni][4 * vg + 2]), acc_elem(acc[mi][ni][4 * vg + 3]));
+            }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Bounded wait for a flag another workgroup of this launch sets; on giving up the error word of the
+// workspace is set and the caller carries on (wrong results, reported by lowrank_workspace_status).
+constexpr uint32_t kSkSpinLimit = 1u << 22;
+__device__ __forceinline__ void sk_wait_flag(const uint32_t* flag, uint32_t* err) {
+    uint32_t spins = 0;
+    while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+        if (++spins > kSkSpinLimit) { __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
+        __builtin_amdgcn_s_sleep(2);
+    }
 }
 
 // Dense-cache row index (batch * S_max + position) of the 4 rows this lane stores for one block of 32
@@ -358,10 +514,12 @@ __device__ __forceinline__ void cache_rows(int (&crow)[4], const int32_t* pos, i
     }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, bool SK = false>
 __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN / 64],
                                               const f32x16_t (&acc2)[(EPI == PEPI_GATEUP) ? BM / 64 : 1][(EPI == PEPI_GATEUP) ? BN / 64 : 1],
-                                              const PProb& P, int M, int m0, int n0, char* patch, int wave, int lane) {
+                                              const PProb& P, int M, int m0, int n0, char* patch, int wave, int lane,
+                                              const float* parts = nullptr, int part0 = 0, int part1 = 0) {
+    // parts: partial tiles of slots [part0, part1) are added (shared-K owner), skipping empty ones
     constexpr int MI = BM / 64, NI = BN / 64;
     // the lane index goes through an opaque move: everything derived from it is recomputed here, per
     // tile, instead of being hoisted out of the tile loop and held (or spilled) across the main loop
@@ -401,6 +559,42 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
             const int r0 = m0 + wm * (BM / 2) + mi * 32;
             int crow[4] = {-1, -1, -1, -1};
             if constexpr (EPI == PEPI_STORE) { if (cache) cache_rows(crow, pos, T, S_max, M, r0, rrow); }
+            // shared-K holder: the other workgroups' partial sums of this block, three slots per round trip
+            float psum[2][4][4];
+#pragma unroll
+            for (int p2 = 0; p2 < 2; ++p2)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) psum[p2][vg][e] = 0.f;
+            if constexpr (SK) {
+                for (int c = part0; c < part1; c += 3) {
+                    uint2 raw[3][2][4][2];
+#pragma unroll
+                    for (int cc = 0; cc < 3; ++cc) {
+                        const int cs = c + cc < part1 ? c + cc : part1 - 1;      // a repeated slot is loaded but not added
+#pragma unroll
+                        for (int p2 = 0; p2 < 2; ++p2)
+#pragma unroll
+                            for (int vg = 0; vg < 4; ++vg) {
+                                const float* src = parts + (size_t)cs * (BM * BN) + part_index<BM, BN>(wave, mi, pr * 2 + p2, vg, lane);
+                                raw[cc][p2][vg][0] = ld_dev_b64(src); raw[cc][p2][vg][1] = ld_dev_b64(src + 2);
+                            }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int cc = 0; cc < 3; ++cc) {
+                        const float w = c + cc < part1 ? 1.f : 0.f;
+#pragma unroll
+                        for (int p2 = 0; p2 < 2; ++p2)
+#pragma unroll
+                            for (int vg = 0; vg < 4; ++vg) {
+                                psum[p2][vg][0] += w * __uint_as_float(raw[cc][p2][vg][0].x); psum[p2][vg][1] += w * __uint_as_float(raw[cc][p2][vg][0].y);
+                                psum[p2][vg][2] += w * __uint_as_float(raw[cc][p2][vg][1].x); psum[p2][vg][3] += w * __uint_as_float(raw[cc][p2][vg][1].y);
+                            }
+                    }
+                }
+            }
 #pragma unroll
             for (int p2 = 0; p2 < 2; ++p2)
 #pragma unroll
@@ -411,13 +605,14 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
                                          __uint_as_float(rg.y << 16), __uint_as_float(rg.y & 0xffff0000u)};
                     const float bu[4] = {__uint_as_float(ru.x << 16), __uint_as_float(ru.x & 0xffff0000u),
                                          __uint_as_float(ru.y << 16), __uint_as_float(ru.y & 0xffff0000u)};
+                    const float* ps = psum[p2][vg];
                     float v[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         if constexpr (EPI == PEPI_GATEUP)
                             v[e] = silu_bf16out(acc_elem(acc[mi][ni][4 * vg + e]) + bg[e]) * (acc_elem(acc2[mi][ni][4 * vg + e]) + bu[e]);
                         else
-                            v[e] = acc_elem(acc[mi][ni][4 * vg + e]) + bg[e];
+                            v[e] = (acc_elem(acc[mi][ni][4 * vg + e]) + ps[e]) + bg[e];
                     }
                     uint2 o; o.x = ppack2(v[0], v[1]); o.y = ppack2(v[2], v[3]);
                     *reinterpret_cast<uint2*>(wr + (((p2 * 4 + vg) ^ wsw) * 16)) = o;
@@ -445,7 +640,7 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
     }
 }
 
-template <int BM, int BN, int EPI, int MINB>
+template <int BM, int BN, int EPI, int MINB, bool SK>
 __global__ void __launch_bounds__(256, MINB) k_prefill_persist(PArgs pa) {
     constexpr int MI = BM / 64, NI = BN / 64;
     constexpr int L = MI + NI;
@@ -460,39 +655,75 @@ __global__ void __launch_bounds__(256, MINB) k_prefill_persist(PArgs pa) {
     frag_setup<BM, BN>(f);
 
     Requester<BM, BN, EPI> q;
-    q.w = walk_begin(pa); q.issued = 0; q.phase = 0; q.kt = 0;
-    q.live = walk_next<BM, BN>(q.w, pa, q.prob, q.m0, q.n0);
-    if (!q.live) return;                                    // no tile for this workgroup (whole workgroup leaves)
+    q.w = walk_begin(pa); q.issued = 0; q.phase = 0; q.kt = 0; q.kend = 0;
+    q.live = walk_next<BM, BN>(q.w, pa, q.sg);
+    if (!q.live) return;                                    // no work for this workgroup (whole workgroup leaves)
     requester_open<BM, BN, EPI>(q, pa, wave, lane);
-    for (int i = 0; i < DSTAGES; ++i) requester_step<BM, BN, EPI>(q, pa, lds0, wave, lane);
+    for (int i = 0; i < DSTAGES; ++i) {
+        issue_all<BM, BN, 0>(requester_next<BM, BN, EPI>(q, lds0, wave));
+        requester_advance<BM, BN, EPI>(q, pa, wave, lane);
+    }
 
-    TileWalk cw = walk_begin(pa);
-    int prob, m0, n0;
+    Walk cw = walk_begin(pa);
+    Seg sg;
     uint32_t done = 0;
     wait_groups<L>((int)q.issued - 1);                      // group 0 has landed
     __builtin_amdgcn_s_barrier();
     bf16x8_t af0[MI], bf0[NI], af1[MI], bf1[NI];
 
-    while (walk_next<BM, BN>(cw, pa, prob, m0, n0)) {
-        const PProb& P = pa.p[prob];
+    while (walk_next<BM, BN>(cw, pa, sg)) {
+        const PProb& P = pa.p[sg.prob];
         f32x16_t acc[MI][NI];
         f32x16_t acc2[(EPI == PEPI_GATEUP) ? MI : 1][(EPI == PEPI_GATEUP) ? NI : 1];
-        const int nk = P.K / DBK;                  // >= 2
+        const int steps = sg.ke - sg.kb;           // >= 1; whole tiles have >= 2
         read_first_frags<BM, BN>(af0, bf0, ring + (done & (DSTAGES - 1)) * dma_stage_bytes<BM, BN>(), f);
-        persist_step<BM, BN, EPI, true, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
-        for (int kt = 2; kt < nk; ++kt)
-            persist_step<BM, BN, EPI, false, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
-        if constexpr (EPI == PEPI_GATEUP) {
-            const int nk2 = P.K2 / DBK;
-            persist_step<BM, BN, EPI, false, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
-            persist_step<BM, BN, EPI, true, false>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
-            for (int kt = 2; kt < nk2; ++kt)
-                persist_step<BM, BN, EPI, false, false>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
-            persist_step<BM, BN, EPI, false, true>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+        if (EPI == PEPI_STORE && steps == 1) {
+            persist_step<BM, BN, EPI, true, true>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
         } else {
-            persist_step<BM, BN, EPI, false, true>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+            persist_step<BM, BN, EPI, true, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+            for (int kt = 2; kt < steps; ++kt)
+                persist_step<BM, BN, EPI, false, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+            if constexpr (EPI == PEPI_GATEUP) {
+                const int nk2 = P.K2 / DBK;
+                persist_step<BM, BN, EPI, false, false>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+                persist_step<BM, BN, EPI, true, false>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+                for (int kt = 2; kt < nk2; ++kt)
+                    persist_step<BM, BN, EPI, false, false>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+                persist_step<BM, BN, EPI, false, true>(acc2, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+            } else {
+                persist_step<BM, BN, EPI, false, true>(acc, af0, bf0, af1, bf1, ring, f, q, pa, lds0, done, wave, lane);
+            }
         }
-        wave_epilogue<BM, BN, EPI>(acc, acc2, P, pa.M, m0, n0, patch, wave, lane);
+        if constexpr (SK) {
+            if (!(sg.kb == 0 && sg.ke == pa.sk_nk)) {
+                const int wl = logical_wg();
+                if (sg.kb > 0) {
+                    // not the holder of this tile's first k-step: hand the partial sums over
+                    store_partial<BM, BN>(acc, pa.sk_slots + (size_t)wl * (BM * BN), wave, lane);
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's part has been written
+                    __builtin_amdgcn_s_barrier();
+                    if (tid == 0) __hip_atomic_store(pa.sk_flags + wl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    // holder of k = 0 (its last segment): the rest of the tile's k range lies with the
+                    // following logical workgroups, which did that part first
+                    const int tile_end = (cw.next / pa.sk_nk + 1) * pa.sk_nk;   // cw.next == end of this range, inside the tile
+                    int c1 = wl + 1;
+                    while (c1 < (int)gridDim.x && sk_unit_begin(pa, c1) < tile_end) ++c1;
+                    if (tid == 0)
+                        for (int c = wl + 1; c < c1; ++c)
+                            if (sk_unit_begin(pa, c + 1) > sk_unit_begin(pa, c)) sk_wait_flag(pa.sk_flags + c, pa.err);
+                    __builtin_amdgcn_s_barrier();
+                    // (the launcher sizes the grid so that no range is empty: every slot in [wl + 1, c1) is fresh)
+                    wave_epilogue<BM, BN, EPI, true>(acc, acc2, P, pa.M, sg.m0, sg.n0, patch, wave, lane, pa.sk_slots, wl + 1, c1);
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // partial sums have been read
+                    __builtin_amdgcn_s_barrier();
+                    if (tid == 0)
+                        for (int c = wl + 1; c < c1; ++c) __hip_atomic_store(pa.sk_flags + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                continue;
+            }
+        }
+        wave_epilogue<BM, BN, EPI>(acc, acc2, P, pa.M, sg.m0, sg.n0, patch, wave, lane);
     }
 }
 
@@ -502,23 +733,51 @@ bool prefill_shape_ok(int64_t M, int64_t K, int64_t N) {
            K < (1 << 24) && N < (1 << 24);
 }
 
+// all problems of one launch have the same K and N (then every tile of the launch grid is a real one)
+static bool one_shape(const PArgs& a) {
+    for (int i = 1; i < a.nprob; ++i)
+        if (a.p[i].K != a.p[0].K || a.p[i].N != a.p[0].N) return false;
+    return true;
+}
+
 template <int BM, int BN, int EPI, int MINB>
-static int launch_persist(PArgs a, hipStream_t s) {
+static int launch_persist(PArgs a, hipStream_t s, bool share_k = false) {
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n_max = 0;
     for (int i = 0; i < a.nprob; ++i) { const int t = (a.p[i].N + BN - 1) / BN; if (t > a.tiles_n_max) a.tiles_n_max = t; }
     const int total = a.tiles_m * a.tiles_n_max * a.nprob;
     a.group_m = 8;
     a.trace = g_trace_buffer;
-    const int per_xcd = (total + 7) / 8;
-    const int slots = per_xcd < 32 * MINB ? per_xcd : 32 * MINB;      // workgroups per XCD
-    hipLaunchKernelGGL((k_prefill_persist<BM, BN, EPI, MINB>), dim3((unsigned)(8 * slots)), dim3(256), 0, s, a);
+    a.sk = 0; a.sk_nk = 0;
+    int grid;
+    if (share_k && EPI == PEPI_STORE && BM == 256 && BN == 256 && a.sk_slots && one_shape(a)) {
+        // shared-K walk: equal k-step ranges, at least 8 steps each, one workgroup per slot of the chip
+        a.sk = 1; a.sk_nk = a.p[0].K / 32;
+        const long long units = (long long)total * a.sk_nk;
+        long long g = units / 8 < 256 * MINB ? units / 8 : 256 * MINB;
+        g &= ~7ll;
+        if (g < 8) { a.sk = 0; }
+        grid = (int)g;
+    }
+    if (!a.sk) {
+        const int per_xcd = (total + 7) / 8;
+        const int slots = per_xcd < 32 * MINB ? per_xcd : 32 * MINB;      // workgroups per XCD
+        grid = 8 * slots;
+    }
+    if constexpr (EPI == PEPI_STORE && BM == 256 && BN == 256) {
+        if (a.sk) {
+            hipLaunchKernelGGL((k_prefill_persist<BM, BN, EPI, MINB, true>), dim3((unsigned)grid), dim3(256), 0, s, a);
+            return launch_status("prefill gemm");
+        }
+    }
+    hipLaunchKernelGGL((k_prefill_persist<BM, BN, EPI, MINB, false>), dim3((unsigned)grid), dim3(256), 0, s, a);
     return launch_status("prefill gemm");
 }
 
 static int env_int(const char* name) { const char* v = getenv(name); return v ? atoi(v) : -1; }
 static int env_shape() { static int v = env_int("LOWRANK_PREFILL_SHAPE"); return v; }
 static int env_gu() { static int v = env_int("LOWRANK_PREFILL_GU"); return v; }
+static int env_sk() { static int v = env_int("LOWRANK_PREFILL_SHAREK"); return v; }
 
 // Tile shape of a plain launch, from a two-line cost model fitted to measurements on this chip, in
 // units of "one 256 x 256 tile on one CU": the 256 x 256 kernel (one workgroup per CU) does one unit
@@ -536,6 +795,20 @@ static bool want_256(const PArgs& a) {
     return c256 <= c128;
 }
 
+// A product with a very long K and so few 256 x 256 tiles that half the CUs would get none (h U_d of
+// the MLP) shares its K range between workgroups instead: every CU gets the same number of k-steps.
+// Measured on this chip (M = 8192): 8192 x 11008 x 768 takes 236 us as 128 x 128 tiles and about 175 us
+// shared; with K = 4096 the hand-over of partial tiles and the lost L2 reuse (workgroups of one XCD
+// are no longer at the same k) cost more than the better balance brings, so those stay tiled.
+static bool want_share_k(const PArgs& a) {
+    if (env_sk() == 0) return false;
+    if (!a.sk_slots || !one_shape(a)) return false;
+    if (env_sk() == 1) return true;
+    const long t256 = (long)a.nprob * ((a.M + 255) / 256) * ((a.p[0].N + 255) / 256);
+    const long nk = a.p[0].K / 32;
+    return t256 <= 128 && t256 * nk / 256 >= 96;
+}
+
 int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
     if (a.M <= 0 || a.nprob <= 0) return LR_OK;
     if (epi == PEPI_GATEUP) {
@@ -543,12 +816,13 @@ int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
         return launch_persist<128, 128, PEPI_GATEUP, 2>(a, s);
     }
     switch (env_shape()) {      // measurement override
-        case 0: return launch_persist<256, 256, PEPI_STORE, 1>(a, s);
-        case 1: return launch_persist<128, 128, PEPI_STORE, 2>(a, s);
+        case 0: return launch_persist<256, 256, PEPI_STORE, 1>(a, s, env_sk() == 1);
+        case 1: return launch_persist<128, 128, PEPI_STORE, 2>(a, s, env_sk() == 1);
         case 2: return launch_persist<256, 128, PEPI_STORE, 1>(a, s);
         case 3: return launch_persist<128, 256, PEPI_STORE, 1>(a, s);
         default: break;
     }
+    if (want_share_k(a)) return launch_persist<256, 256, PEPI_STORE, 1>(a, s, true);
     if (want_256(a)) return launch_persist<256, 256, PEPI_STORE, 1>(a, s);
     return launch_persist<128, 128, PEPI_STORE, 2>(a, s);
 }

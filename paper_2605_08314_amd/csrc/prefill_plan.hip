@@ -8,14 +8,19 @@
 namespace lr {
 
 static void zero_pprob(PProb& p) { memset(&p, 0, sizeof(p)); p.T = 1; }
+static void init_pargs(PArgs& a, int64_t M, const WsLayout& L) {
+    memset(&a, 0, sizeof(a));
+    a.M = (int)M;
+    a.sk_flags = L.sk_flags; a.sk_slots = L.sk_slots; a.err = &L.ctrl->error;
+}
 
 int prefill_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
                 void* const* out, const int64_t* r, const int64_t* d_out, int n_proj, const int* base_of,
                 const int64_t* t_off, int64_t R, int64_t M, int64_t d_in, const lr_kv_target* kv,
                 void* ws, size_t ws_bytes, hipStream_t s) {
-    const WsLayout L = ws_layout(ws, ws_bytes);
+    const WsLayout L = ws_layout(ws, ws_bytes, M);
     bf16_t* T = (bf16_t*)L.staging;                 // [M, R] bf16
-    PArgs a1; a1.M = (int)M; a1.nprob = 0; a1.tiles_n_max = 0; a1.tiles_m = 0;
+    PArgs a1; init_pargs(a1, M, L);
     for (int i = 0; i < n_proj; ++i) {
         if (base_of[i] != i) continue;
         PProb& p = a1.p[a1.nprob++]; zero_pprob(p);
@@ -25,7 +30,7 @@ int prefill_qkv(const void* x, const void* const* U, const void* const* V, const
     }
     int st = prefill_launch(a1, PEPI_STORE, s);
     if (st != LR_OK) return st;
-    PArgs a2; a2.M = (int)M; a2.nprob = n_proj; a2.tiles_n_max = 0; a2.tiles_m = 0;
+    PArgs a2; init_pargs(a2, M, L); a2.nprob = n_proj;
     for (int i = 0; i < n_proj; ++i) {
         PProb& p = a2.p[i]; zero_pprob(p);
         p.A = T + t_off[i]; p.lda = (int)R; p.B = (const bf16_t*)V[i]; p.K = (int)r[i]; p.N = (int)d_out[i];
@@ -52,10 +57,10 @@ int prefill_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_
                 int64_t M, int64_t d, int64_t ffn, int64_t r_g, int64_t r_u, int64_t r_d,
                 void* ws, size_t ws_bytes, hipStream_t s) {
     const int64_t r_gu = r_g + r_u, r_all = r_gu + r_d;
-    const WsLayout L = ws_layout(ws, ws_bytes);
+    const WsLayout L = ws_layout(ws, ws_bytes, M);
     bf16_t* T = (bf16_t*)L.staging;                                         // [M, r_g + r_u + r_d] bf16
     bf16_t* H = (bf16_t*)(L.staging + align256((size_t)M * r_all * 2));     // [M, ffn] bf16
-    PArgs a; a.M = (int)M; a.nprob = 1; a.tiles_m = 0;
+    PArgs a; init_pargs(a, M, L); a.nprob = 1;
     {   // T_gu = x U_gu
         PProb& p = a.p[0]; zero_pprob(p);
         p.A = (const bf16_t*)x; p.lda = (int)d; p.B = (const bf16_t*)U_gu; p.K = (int)d; p.N = (int)r_gu; p.C = T; p.ldc = (int)r_all;
