@@ -274,3 +274,65 @@ def test_error_codes(G):
     with pytest.raises(B.LowrankError) as e:
         B.lowrank_linear(x, U, V, None, y, "decode", ws[1:])
     assert e.value.status == -4
+
+
+# ------------------------------------------------------------------ prefill fast path: ragged tiles, several sequences, biases
+@pytest.mark.parametrize("case", [
+    # (sequences, tokens per sequence, d_in, ranks, heads, head_dim): M = sequences * tokens
+    (3, 50, 256, (128, 256, 128), 2, 128),       # small tiles, sequence borders inside a 32-row block, ragged M
+    (30, 5, 256, (128, 128, 128), 2, 128),       # fewer than 32 tokens per sequence: per-row cache positions
+    (3, 1000, 256, (128, 128, 256), 41, 128),    # 3000 x 5248 outputs: big tiles, ragged in M and in N, mixed ranks
+    (600, 5, 256, (128, 128, 128), 41, 128),     # the same with short sequences
+])
+def test_prefill_qkv_fast_path_cache_bias_ragged(G, oracle, case):
+    B = G.B
+    Bn, T, d_in, ranks, H, E = case
+    M, d_out, S_max = Bn * T, H * E, T + 24
+    rng = np.random.default_rng(1000 + M + H)
+    x = rand_t(rng, (M, d_in), "bf16")
+    Us = [rand_t(rng, (d_in, r), "bf16", d_in ** -0.5) for r in ranks]
+    Vs = [rand_t(rng, (r, d_out), "bf16", r ** -0.5) for r in ranks]
+    bs = [rand_t(rng, (d_out,), "bf16"), None, rand_t(rng, (d_out,), "bf16")]
+    pos = rng.integers(0, 24, size=Bn).astype(np.int32)
+    assert B.lowrank_plan_name(B.LR_OP_QKV, M, d_in, sum(ranks), 3 * d_out, B.LR_BF16, "prefill", 1) == "prefill_mfma"
+    SENT = -65536.0
+    kc = torch.full((Bn, S_max, H, E), SENT, dtype=torch.bfloat16, device="cuda")
+    vc = torch.full((Bn, S_max, H, E), SENT, dtype=torch.bfloat16, device="cuda")
+    q = torch.full((M, d_out), float("nan"), dtype=torch.bfloat16, device="cuda")
+    v = torch.full((M, d_out), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = B.new_workspace(B.LR_OP_QKV, M, d_in, sum(ranks), 3 * d_out, B.LR_BF16, "prefill")
+    B.lowrank_qkv(G.dev(x), [G.dev(u) for u in Us], [G.dev(w) for w in Vs],
+                  [None if b is None else G.dev(b) for b in bs], [q, None, v],        # K only to the cache
+                  dict(k_cache=kc, v_cache=vc, pos=G.dev(pos), tokens_per_seq=T, k_index=1, v_index=2), "prefill", ws)
+    B.lowrank_workspace_status(ws)
+    # the oracle on a row sample: tile borders, sequence borders, the ragged tail, and seeded rows
+    rows = sorted(set([0, 1, 31, 32, 127, 128, 255, 256, M - 257, M - 129, M - 2, M - 1] +
+                      [b * T for b in range(0, Bn, max(1, Bn // 7))] + [b * T + T - 1 for b in range(0, Bn, max(1, Bn // 5))] +
+                      list(rng.integers(0, M, size=24))))
+    rows = [r for r in rows if 0 <= r < M]
+    want = oracle.qkv(x.f64[rows], [u.f64 for u in Us], [w.f64 for w in Vs], [None if b is None else b.f64 for b in bs])
+    assert max_rel_err(G.host64(q[rows]), want[0]) <= TOL["bf16"]
+    assert max_rel_err(G.host64(v[rows]), want[2]) <= TOL["bf16"]
+    kh, vh = G.host64(kc), G.host64(vc)
+    for i, m in enumerate(rows):
+        b, s = divmod(m, T)
+        assert max_rel_err(kh[b, pos[b] + s].reshape(1, -1), want[1][i:i + 1]) <= TOL["bf16"]
+    # every slot: written exactly where a token belongs, V cache bit-identical to the V output
+    written = np.zeros((Bn, S_max), dtype=bool)
+    for b in range(Bn):
+        written[b, pos[b]:pos[b] + T] = True
+    assert np.array_equal((kh != SENT).all(axis=(2, 3)), written) and np.array_equal((kh != SENT).any(axis=(2, 3)), written)
+    assert np.array_equal((vh != SENT).any(axis=(2, 3)), written)
+    vb, ob = G.bits(vc), G.bits(v)
+    for b in range(0, Bn, max(1, Bn // 11)):
+        assert np.array_equal(vb[b, pos[b]:pos[b] + T].reshape(T, d_out), ob[b * T:(b + 1) * T])
+
+
+@pytest.mark.parametrize("M", [300, 1000])
+def test_prefill_mlp_fast_path_with_bias(G, oracle, M):
+    w = synth.mlp_layer(M, d=512, ffn=1024, r_g=128, r_u=256, r_d=128, seed=321 + M, dtype="bf16", with_bias=True)
+    out = G.run_mlp(w, "prefill")          # every dimension fits the MFMA path: K % 64 == 0, N % 128 == 0
+    t = w.t
+    want = oracle.packed_mlp(t["x"].f64, t["U_gu"].f64, t["V_g"].f64, t["V_u"].f64, t["U_d"].f64, t["V_d"].f64,
+                             t["b_g"].f64, t["b_u"].f64, t["b_d"].f64)
+    assert max_rel_err(G.host64(out), want) <= TOL["bf16"]
