@@ -94,6 +94,37 @@ def time_region(torch, fn, iters, warmup):
     return e0.elapsed_time(e1) / iters
 
 
+def run_prefill(torch, B, gen, ly, S):
+    """One layer at S rows (QKV with cache write, O, packed MLP): time and TFLOP/s (algorithmic flops)."""
+    bf = torch.bfloat16
+    xs = torch.randn((S, D), device="cuda", generator=gen).to(bf)
+    qs, os_, ms_ = (torch.empty((S, D), device="cuda", dtype=bf) for _ in range(3))
+    kcs = torch.zeros((1, S, HEADS, HEAD_DIM), device="cuda", dtype=bf)
+    vcs = torch.zeros_like(kcs)
+    pos0 = torch.zeros((1,), device="cuda", dtype=torch.int32)
+    wq = B.new_workspace(B.LR_OP_QKV, S, D, 3 * R_ATTN, 3 * D, B.LR_BF16, "prefill")
+    wo = B.new_workspace(B.LR_OP_LINEAR, S, D, R_ATTN, D, B.LR_BF16, "prefill")
+    wm = B.new_workspace(B.LR_OP_PACKED_MLP, S, D, 3 * R_MLP, FFN, B.LR_BF16, "prefill")
+
+    def prefill_layer():
+        # K and V go where attention reads them: the dense cache only
+        B.lowrank_qkv(xs, ly.U[:3], ly.V[:3], None, [qs, None, None],
+                      dict(k_cache=kcs, v_cache=vcs, pos=pos0, tokens_per_seq=S, k_index=1, v_index=2), "prefill", wq)
+        B.lowrank_linear(xs, ly.U[3], ly.V[3], None, os_, "prefill", wo)
+        B.lowrank_packed_mlp(xs, ly.U_gu, ly.V_g, ly.V_u, ly.U_d, ly.V_d, None, None, None, ms_, "prefill", wm)
+
+    plan = B.lowrank_plan_name(B.LR_OP_PACKED_MLP, S, D, 3 * R_MLP, FFN, B.LR_BF16, "prefill")
+    iters = 10 if plan != "generic" else 1
+    pms = time_region(torch, prefill_layer, iters, 2)
+    for w in (wq, wo, wm):
+        B.lowrank_workspace_status(w)
+    pfl = attn_flops(S) + mlp_flops(S)
+    tf = pfl / (pms * 1e-3) / 1e12
+    return {"workload": f"one layer, S={S}, ranks {R_ATTN}/{R_MLP}", "plan": plan, "ms": round(pms, 3),
+            "TFLOPs": round(tf, 1), "frac_mfma_bf16_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+            "tokens_per_s": round(S / (pms * 1e-3), 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -104,6 +135,7 @@ def main():
     ap.add_argument("--prefill-rows", type=int, default=8192)
     ap.add_argument("--eager", action="store_true", help="plain launches instead of HIP-graph replay")
     ap.add_argument("--quick", action="store_true", help="skip the per-batch table, prefill and the CPU baseline")
+    ap.add_argument("--prefill-only", action="store_true", help="only the prefill layer (for profiling): one JSON line with its numbers")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for rocprofv3 --pmc runs: a 256 MiB plain copy (known traffic) and 32 eager decode-MLP launches, nothing else")
     args = ap.parse_args()
@@ -121,6 +153,9 @@ def main():
     L, Bt = args.layers, args.batch
     if args.pmc_mode:
         L = min(L, 8)
+    if args.prefill_only:
+        print(json.dumps({"prefill_only": True, "prefill": run_prefill(torch, B, gen, Layer(torch, gen=gen), args.prefill_rows)}))
+        return
     layers = [Layer(torch, gen=gen) for _ in range(L)]
     S_max = 64
     bf = torch.bfloat16
@@ -240,33 +275,7 @@ def main():
                 del b2
         out["decode_ops"] = table
 
-        # ---- prefill: one layer at S rows (QKV with cache write, O, packed MLP)
-        S = args.prefill_rows
-        ly = layers[0]
-        xs = torch.randn((S, D), device="cuda", generator=gen).to(bf)
-        qs, ks, vs, os_, ms_ = (torch.empty((S, D), device="cuda", dtype=bf) for _ in range(5))
-        kcs = torch.zeros((1, S, HEADS, HEAD_DIM), device="cuda", dtype=bf)
-        vcs = torch.zeros_like(kcs)
-        pos0 = torch.zeros((1,), device="cuda", dtype=torch.int32)
-        wq = B.new_workspace(B.LR_OP_QKV, S, D, 3 * R_ATTN, 3 * D, B.LR_BF16, "prefill")
-        wo = B.new_workspace(B.LR_OP_LINEAR, S, D, R_ATTN, D, B.LR_BF16, "prefill")
-        wm = B.new_workspace(B.LR_OP_PACKED_MLP, S, D, 3 * R_MLP, FFN, B.LR_BF16, "prefill")
-
-        def prefill_layer():
-            B.lowrank_qkv(xs, ly.U[:3], ly.V[:3], None, [qs, ks, vs],
-                          dict(k_cache=kcs, v_cache=vcs, pos=pos0, tokens_per_seq=S, k_index=1, v_index=2), "prefill", wq)
-            B.lowrank_linear(xs, ly.U[3], ly.V[3], None, os_, "prefill", wo)
-            B.lowrank_packed_mlp(xs, ly.U_gu, ly.V_g, ly.V_u, ly.U_d, ly.V_d, None, None, None, ms_, "prefill", wm)
-
-        plan = B.lowrank_plan_name(B.LR_OP_PACKED_MLP, S, D, 3 * R_MLP, FFN, B.LR_BF16, "prefill")
-        iters = 10 if plan != "generic" else 1
-        pms = time_region(torch, prefill_layer, iters, 1)
-        pfl = attn_flops(S) + mlp_flops(S)
-        tf = pfl / (pms * 1e-3) / 1e12
-        out["prefill"] = {"workload": f"one layer, S={S}, ranks 384/768", "plan": plan, "ms": round(pms, 3),
-                          "TFLOPs": round(tf, 1), "frac_mfma_bf16_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                          "tokens_per_s": round(S / (pms * 1e-3), 1)}
-        del xs, qs, ks, vs, os_, ms_, kcs, vcs
+        out["prefill"] = run_prefill(torch, B, gen, layers[0], args.prefill_rows)
 
         # ---- CPU baseline: the oracle as it stands, on this machine's host cores, bounded sample
         import numpy as np
