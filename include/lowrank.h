@@ -142,8 +142,9 @@ int lowrank_pack_concat(const void *const *U_list, const int64_t *r_list, int n,
  *   LR_OP_LINEAR      d_in, r_total = r,                 d_out
  *   LR_OP_QKV         d_in, r_total = sum of r[i],       d_out = sum of d_out[i]
  *   LR_OP_PACKED_MLP  d_in = d, r_total = r_g + r_u + r_d, d_out = ffn
- * Returns 0 for invalid arguments.  The value is an upper bound over both phases when phase is
- * LR_PHASE_AUTO.
+ * Returns 0 for invalid arguments.  The value covers both phases whatever `phase` says.  For more
+ * than 32 token rows it includes a fixed area of 64 MiB + 4 KiB in which the workgroups of a prefill
+ * product that share one tile's K range hand their partial sums to each other.
  */
 size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
                                int dtype, int phase);
@@ -153,8 +154,9 @@ int lowrank_workspace_init(void *workspace, size_t workspace_bytes, void *stream
 
 /*
  * Diagnostic, the only function here that SYNCHRONISES `stream`: reads the workspace's control
- * block back and returns LR_OK, or LR_ERR_LAUNCH if a bounded device-side wait between the stages
- * of a fused decode call gave up (then that call's results are invalid and the workspace must be
+ * block back and returns LR_OK, or LR_ERR_LAUNCH if a bounded device-side wait gave up -- between
+ * the stages of a fused decode call, or for the partial sums of a prefill product whose K range is
+ * shared between workgroups (then that call's results are invalid and the workspace must be
  * prepared again).
  */
 int lowrank_workspace_status(const void *workspace, void *stream);
