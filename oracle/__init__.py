@@ -165,3 +165,40 @@ def pack_concat(U_list: Sequence[np.ndarray]) -> np.ndarray:
     packed = np.empty((d_in, sum(u.shape[1] for u in Us)), dtype=dt)
     _load().lr_oracle_pack_concat(ptrs, rs, ctypes.c_int(n), _i64(d_in), _i64(dt.itemsize), _p(packed))
     return packed
+
+
+def rope(x, positions, H: int, E: int, base: float = 10000.0) -> np.ndarray:
+    """Rotary position embedding, rotate-half pairing (i, i + E/2), angle p * base**(-2i/E);
+    x [rows, H*E], positions [rows] (Section 4: RoPE on q and k)."""
+    x = _f64(x)
+    rows = x.shape[0]
+    assert x.shape == (rows, H * E)
+    p = np.ascontiguousarray(positions, dtype=np.int64)
+    assert p.shape == (rows,)
+    y = np.empty_like(x)
+    rc = _load().lr_oracle_rope(_p(x), _p(y), _p(p), _i64(rows), _i64(H), _i64(E), ctypes.c_double(base))
+    assert rc == 0, rc
+    return y
+
+
+def decode_attention(q, k_cache: np.ndarray, v_cache: np.ndarray, pos, T: int, scale: float,
+                     rope_base: float = 0.0) -> np.ndarray:
+    """Causal attention of T new tokens per sequence over the dense cache [B, S_max, H, E]
+    (Section 3.1, decode attention).  Rows pos[b]..pos[b]+T-1 of the caches hold the new raw k / v;
+    with rope_base > 0 the new k rows are rotated in place in ``k_cache`` and q is rotated first.
+    Returns out [B*T, H*E]."""
+    q = _f64(q)
+    assert k_cache.dtype == np.float64 and k_cache.flags.c_contiguous and k_cache.ndim == 4
+    v_cache = _f64(v_cache)
+    B, S_max, H, E = k_cache.shape
+    assert v_cache.shape == k_cache.shape and q.shape == (B * T, H * E)
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    assert pos.shape == (B,)
+    out = np.empty((B * T, H * E), dtype=np.float64)
+    rc = _load().lr_oracle_decode_attention(_p(q), _p(k_cache), _p(v_cache), _p(pos), _p(out), _i64(B), _i64(T),
+                                            _i64(S_max), _i64(H), _i64(E), ctypes.c_double(scale),
+                                            ctypes.c_double(rope_base))
+    if rc == -1:
+        raise ValueError("cache position out of range")
+    assert rc == 0, rc
+    return out

@@ -19,6 +19,9 @@
  * may run under OpenMP; that is the only parallelism.  There is no blocking,
  * fusion or re-association.
  *
+ * The last two functions (rotary embedding, attention over the dense cache) define
+ * the step that reads the cache this path writes (Section 3.1, decode attention).
+ *
  * Every function below is pinned by tests/test_oracle_pins.py (brute force on
  * integer inputs, dense reconstruction, full-rank SVD recovery, closed forms,
  * invariants); nothing here is "parity unpinned".
@@ -181,6 +184,103 @@ int lr_oracle_pack_concat(const void *const *U_list, const int64_t *r_list, int 
         col0 += r_list[i];
     }
     return 0;
+}
+
+/*
+ * Rotary position embedding in the "rotate-half" pairing that LLaMA checkpoints in the common
+ * exchange format use (the paper's aligned baseline "applies external RoPE", Section 4; the paper
+ * does not write the formula -- this is the standard one): for head dimension E, pair
+ * (i, i + E/2), i < E/2, is rotated by the angle p * base^(-2i/E):
+ *     y[i]       = x[i] * cos(a) - x[i + E/2] * sin(a)
+ *     y[i + E/2] = x[i + E/2] * cos(a) + x[i] * sin(a)
+ * x, y: [rows, H * E] (column h * E + e); p[rows]: position of each row.  y may equal x.
+ */
+int lr_oracle_rope(const double *x, double *y, const int64_t *p, int64_t rows, int64_t H, int64_t E, double base)
+{
+    if (E % 2 != 0) return -2;
+    const int64_t half = E / 2;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t h = 0; h < H; ++h) {
+            const double *xi = x + ((size_t)r * (size_t)H + (size_t)h) * (size_t)E;
+            double *yi = y + ((size_t)r * (size_t)H + (size_t)h) * (size_t)E;
+            for (int64_t i = 0; i < half; ++i) {
+                const double a = (double)p[r] * pow(base, -2.0 * (double)i / (double)E);
+                const double c = cos(a), sn = sin(a);
+                const double lo = xi[i], hi = xi[i + half];
+                yi[i] = lo * c - hi * sn;
+                yi[i + half] = hi * c + lo * sn;
+            }
+        }
+    return 0;
+}
+
+/*
+ * Decode attention over the dense KV cache (Section 3.1, decode-attention paragraph: the present
+ * token's q/k/v are reconstructed once, the past is read from a standard dense cache
+ * [batch, position, head, head_dim]; Section 4: RoPE is applied to q and k).
+ *
+ * q[B*T, H*E]: the queries of T new tokens per sequence; row b*T+s sits at position pos[b]+s.
+ * k_cache, v_cache[B, S_max, H, E]: rows pos[b] .. pos[b]+T-1 already hold the new tokens' raw k and v.
+ * If rope_base > 0, first the T new k rows of every sequence are rotated IN PLACE (the cache then
+ * holds rotated keys, as it does for all earlier positions) and the queries are rotated (not in
+ * place).  Then, for every row and head, with n = pos[b]+s+1 visible positions (causal):
+ *     score[j] = scale * sum_e q[e] * K[b, j, h, e],  j < n
+ *     w[j]     = exp(score[j] - max_j score) / sum_j exp(score[j] - max_j score)
+ *     out[e]   = sum_j w[j] * V[b, j, h, e]
+ * Returns 0; -1 if a position falls outside [0, S_max); -2 for odd E with RoPE.
+ */
+int lr_oracle_decode_attention(const double *q, double *k_cache, const double *v_cache, const int32_t *pos,
+                               double *out, int64_t B, int64_t T, int64_t S_max, int64_t H, int64_t E,
+                               double scale, double rope_base)
+{
+    const int64_t d = H * E;
+    for (int64_t b = 0; b < B; ++b)
+        if (pos[b] < 0 || (int64_t)pos[b] + T > S_max) return -1;
+    double *qr = (double *)malloc(sizeof(double) * (size_t)(B * T > 0 ? B * T : 1) * (size_t)(d > 0 ? d : 1));
+    if (!qr) return -3;
+    if (rope_base > 0.0) {
+        if (E % 2 != 0) { free(qr); return -2; }
+        for (int64_t b = 0; b < B; ++b)
+            for (int64_t s = 0; s < T; ++s) {
+                const int64_t p = (int64_t)pos[b] + s;
+                double *krow = k_cache + ((size_t)b * (size_t)S_max + (size_t)p) * (size_t)d;
+                lr_oracle_rope(krow, krow, &p, 1, H, E, rope_base);
+                lr_oracle_rope(q + (size_t)(b * T + s) * (size_t)d, qr + (size_t)(b * T + s) * (size_t)d, &p, 1, H, E, rope_base);
+            }
+    } else {
+        memcpy(qr, q, sizeof(double) * (size_t)(B * T) * (size_t)d);
+    }
+    int failed = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < B * T; ++r) {
+        const int64_t b = r / T, s = r - b * T;
+        const int64_t n = (int64_t)pos[b] + s + 1;
+        double *w = (double *)malloc(sizeof(double) * (size_t)n);
+        if (!w) { failed = 1; continue; }
+        for (int64_t h = 0; h < H; ++h) {
+            const double *qh = qr + (size_t)r * (size_t)d + (size_t)h * (size_t)E;
+            double mx = -INFINITY;
+            for (int64_t j = 0; j < n; ++j) {
+                const double *kj = k_cache + (((size_t)b * (size_t)S_max + (size_t)j) * (size_t)H + (size_t)h) * (size_t)E;
+                double sc = 0.0;
+                for (int64_t e = 0; e < E; ++e) sc += qh[e] * kj[e];
+                w[j] = sc * scale;
+                if (w[j] > mx) mx = w[j];
+            }
+            double den = 0.0;
+            for (int64_t j = 0; j < n; ++j) { w[j] = exp(w[j] - mx); den += w[j]; }
+            double *oh = out + (size_t)r * (size_t)d + (size_t)h * (size_t)E;
+            for (int64_t e = 0; e < E; ++e) oh[e] = 0.0;
+            for (int64_t j = 0; j < n; ++j) {
+                const double *vj = v_cache + (((size_t)b * (size_t)S_max + (size_t)j) * (size_t)H + (size_t)h) * (size_t)E;
+                const double wj = w[j] / den;
+                for (int64_t e = 0; e < E; ++e) oh[e] += wj * vj[e];
+            }
+        }
+        free(w);
+    }
+    free(qr);
+    return failed ? -3 : 0;
 }
 
 int lr_oracle_num_threads(void)

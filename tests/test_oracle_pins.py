@@ -290,3 +290,127 @@ def test_workload_shapes_match_configs():
     assert np.array_equal(m.t["U_gu"].dev[:, :8], m.t["U_g"].dev)
     rows = synth.prefill_row_sample(300)
     assert rows[0] == 0 and rows[-1] == 299 and 127 in rows and 128 in rows and 255 in rows and 256 in rows
+
+
+# ---------------------------------------------------------------- rotary embedding (Section 4: RoPE on q and k)
+def test_rope_unit_vectors_pin_pairing_frequency_and_sign(oracle):
+    H, E, base, p = 2, 8, 10000.0, 7
+    for h in range(H):
+        for i in range(E // 2):
+            a = p * base ** (-2.0 * i / E)
+            x = np.zeros((1, H * E)); x[0, h * E + i] = 1.0                 # low partner of pair i
+            y = oracle.rope(x, [p], H, E, base)
+            want = np.zeros_like(x); want[0, h * E + i] = math.cos(a); want[0, h * E + i + E // 2] = math.sin(a)
+            assert np.allclose(y, want, rtol=0, atol=1e-15)
+            x = np.zeros((1, H * E)); x[0, h * E + i + E // 2] = 1.0        # high partner
+            y = oracle.rope(x, [p], H, E, base)
+            want = np.zeros_like(x); want[0, h * E + i] = -math.sin(a); want[0, h * E + i + E // 2] = math.cos(a)
+            assert np.allclose(y, want, rtol=0, atol=1e-15)
+
+
+def test_rope_identity_norm_composition_and_relative_property(oracle):
+    rng = np.random.default_rng(11)
+    H, E = 3, 16
+    x = rng.standard_normal((5, H * E)); k = rng.standard_normal((5, H * E))
+    assert np.array_equal(oracle.rope(x, [0] * 5, H, E), x)                                  # position 0: identity
+    pos = np.array([1, 17, 300, 4095, 8191])
+    y = oracle.rope(x, pos, H, E)
+    pair_norm = lambda z: z.reshape(5, H, 2, E // 2)[:, :, 0] ** 2 + z.reshape(5, H, 2, E // 2)[:, :, 1] ** 2
+    assert np.allclose(pair_norm(y), pair_norm(x), rtol=1e-12)                               # a rotation of every pair
+    assert np.allclose(oracle.rope(oracle.rope(x, pos, H, E), [5] * 5, H, E), oracle.rope(x, pos + 5, H, E), atol=1e-9)
+    # scores depend on the position difference only
+    dots = lambda m, n: (oracle.rope(x, m, H, E).reshape(5, H, E) * oracle.rope(k, n, H, E).reshape(5, H, E)).sum(-1)
+    assert np.allclose(dots(pos, pos - 1), dots(pos + 100, pos + 99), atol=1e-9)
+    assert not np.allclose(dots(pos, pos - 1), dots(pos, pos - 2), atol=1e-3)
+    # E = 2: the plain planar rotation by p radians
+    z = oracle.rope(np.array([[1.0, 0.0], [0.0, 1.0]]), [2, 3], 1, 2)
+    assert np.allclose(z, [[math.cos(2), math.sin(2)], [-math.sin(3), math.cos(3)]], atol=1e-15)
+
+
+# ---------------------------------------------------------------- attention over the dense cache (Section 3.1)
+def _attention_brute(q, kc, vc, pos, T, scale):
+    """Pure-Python loops, no numpy arithmetic: softmax(q K^T scale) V, causal."""
+    B, S_max, H, E = kc.shape
+    out = [[0.0] * (H * E) for _ in range(B * T)]
+    for b in range(B):
+        for s in range(T):
+            n = int(pos[b]) + s + 1
+            for h in range(H):
+                sc = [scale * sum(float(q[b * T + s, h * E + e]) * float(kc[b, j, h, e]) for e in range(E)) for j in range(n)]
+                mx = max(sc)
+                w = [math.exp(v - mx) for v in sc]
+                den = sum(w)
+                for e in range(E):
+                    out[b * T + s][h * E + e] = sum(w[j] / den * float(vc[b, j, h, e]) for j in range(n))
+    return np.array(out)
+
+
+def test_attention_brute_force_and_causality(oracle):
+    rng = np.random.default_rng(12)
+    B, T, S_max, H, E = 2, 3, 9, 2, 4
+    q = rng.standard_normal((B * T, H * E))
+    kc = rng.standard_normal((B, S_max, H, E)); vc = rng.standard_normal((B, S_max, H, E))
+    pos = np.array([4, 0], dtype=np.int32)
+    want = _attention_brute(q, kc, vc, pos, T, 0.5)
+    got = oracle.decode_attention(q, kc.copy(), vc, pos, T, 0.5)
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-14)
+    # positions a row may not see do not matter: poison them
+    kp, vp = kc.copy(), vc.copy()
+    for b in range(B):
+        kp[b, pos[b] + T:] = np.nan; vp[b, pos[b] + T:] = np.nan
+    assert np.array_equal(oracle.decode_attention(q, kp, vp, pos, T, 0.5), got)
+    # causal inside the new tokens: row s of sequence 1 (pos 0) sees exactly s + 1 positions; row 0 returns v[0]
+    assert np.allclose(got[T * 1 + 0].reshape(H, E), vc[1, 0], rtol=1e-14)
+    with pytest.raises(ValueError):
+        oracle.decode_attention(q, kc.copy(), vc, np.array([7, 0], dtype=np.int32), T, 0.5)     # 7 + 3 > S_max
+
+
+def test_attention_closed_forms(oracle):
+    from scipy.special import softmax
+    rng = np.random.default_rng(13)
+    B, S_max, H, E, n = 1, 40, 2, 8, 33
+    q = rng.standard_normal((1, H * E))
+    kc = rng.standard_normal((B, S_max, H, E)); vc = rng.standard_normal((B, S_max, H, E))
+    pos = np.array([n - 1], dtype=np.int32)
+    scale = E ** -0.5
+    out = oracle.decode_attention(q, kc.copy(), vc, pos, 1, scale)
+    # library softmax + matmul
+    for h in range(H):
+        w = softmax(scale * kc[0, :n, h] @ q[0, h * E:(h + 1) * E])
+        assert np.allclose(out[0, h * E:(h + 1) * E], w @ vc[0, :n, h], rtol=1e-12)
+    # weights sum to one: V = const -> out = const;  identical keys -> plain mean of V
+    assert np.allclose(oracle.decode_attention(q, kc.copy(), np.full_like(vc, 3.25), pos, 1, scale), 3.25, rtol=1e-14)
+    same = np.broadcast_to(kc[:, :1], kc.shape).copy()
+    assert np.allclose(oracle.decode_attention(q, same, vc, pos, 1, scale).reshape(H, E), vc[0, :n].mean(axis=0), rtol=1e-13)
+    # adding one vector to every key shifts every score equally: same output
+    shifted = kc + rng.standard_normal((1, 1, H, E))
+    assert np.allclose(oracle.decode_attention(q, shifted, vc, pos, 1, scale), out, rtol=1e-10)
+    # huge scores: no overflow, the best key wins
+    big = oracle.decode_attention(q * 1e4, kc.copy(), vc, pos, 1, 1.0)
+    for h in range(H):
+        j = int(np.argmax(kc[0, :n, h] @ q[0, h * E:(h + 1) * E]))
+        assert np.allclose(big[0, h * E:(h + 1) * E], vc[0, j, h], rtol=1e-12)
+    # scale really multiplies the scores: scale 0 -> uniform weights
+    assert np.allclose(oracle.decode_attention(q, kc.copy(), vc, pos, 1, 0.0).reshape(H, E), vc[0, :n].mean(axis=0), rtol=1e-13)
+
+
+def test_attention_with_rope_rotates_new_keys_in_place_and_queries(oracle):
+    rng = np.random.default_rng(14)
+    B, T, S_max, H, E = 2, 2, 12, 2, 8
+    q = rng.standard_normal((B * T, H * E))
+    kc = rng.standard_normal((B, S_max, H, E)); vc = rng.standard_normal((B, S_max, H, E))
+    pos = np.array([5, 9], dtype=np.int32)
+    k_in = kc.copy()
+    out = oracle.decode_attention(q, kc, vc, pos, T, E ** -0.5, rope_base=10000.0)
+    # the cache: only the new rows changed, and they are the rotated raw rows
+    for b in range(B):
+        for j in range(S_max):
+            if pos[b] <= j < pos[b] + T:
+                assert np.allclose(kc[b, j].reshape(1, -1), oracle.rope(k_in[b, j].reshape(1, -1), [j], H, E), rtol=0, atol=1e-15)
+            else:
+                assert np.array_equal(kc[b, j], k_in[b, j])
+    # same as: rotate by hand, then attention without RoPE
+    rows_pos = np.array([pos[b] + s for b in range(B) for s in range(T)])
+    want = oracle.decode_attention(oracle.rope(q, rows_pos, H, E), kc.copy(), vc, pos, T, E ** -0.5, rope_base=0.0)
+    assert np.allclose(out, want, rtol=1e-13, atol=1e-15)
+    assert not np.allclose(out, oracle.decode_attention(q, k_in.copy(), vc, pos, T, E ** -0.5), atol=1e-3)
