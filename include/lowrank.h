@@ -66,7 +66,7 @@ typedef enum {
     LR_ERR_UNSUPPORTED = -8  /* combination not available */
 } lr_status;
 
-typedef enum { LR_OP_LINEAR = 0, LR_OP_QKV = 1, LR_OP_PACKED_MLP = 2 } lr_op;
+typedef enum { LR_OP_LINEAR = 0, LR_OP_QKV = 1, LR_OP_PACKED_MLP = 2, LR_OP_DECODE_ATTENTION = 3 } lr_op;
 
 /*
  * One factorized linear layer (Section 3.1, first paragraph):
@@ -130,6 +130,30 @@ int lowrank_packed_mlp(const void *x, const void *U_gu, const void *V_g, const v
                        int dtype, int phase, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Decode attention over the dense KV cache that lowrank_qkv writes (Section 3.1, second paragraph:
+ * the present token's q/k/v are reconstructed once and the history is read from a standard dense
+ * cache; Section 4: rotary position embedding on q and k).  kv describes the caches as for
+ * lowrank_qkv (k_index / v_index are ignored): M = B * tokens_per_seq token rows, row
+ * b*tokens_per_seq + s stands at position p = pos[b] + s, and rows pos[b] .. pos[b]+tokens_per_seq-1
+ * of both caches already hold the new tokens' k and v (every head: multi-head attention, one K/V
+ * head per query head).
+ *   1. If rope_base > 0: the new k rows are rotated IN PLACE in k_cache (so that the cache holds
+ *      rotated keys at every position, as after earlier calls) and the queries are rotated (q itself
+ *      is not written).  Pairing "rotate-half": for i < head_dim/2 and a = p * rope_base^(-2i/head_dim),
+ *      (x[i], x[i + head_dim/2]) -> (x[i] cos a - x[i + head_dim/2] sin a, x[i + head_dim/2] cos a + x[i] sin a).
+ *      Call this exactly once per new token after lowrank_qkv has written its raw k.
+ *   2. For every row and head h, over the n = p + 1 visible positions j (causal):
+ *      out[row, h*head_dim + e] = sum_j softmax_j(scale * <q_h, K[b, j, h, :]>) * V[b, j, h, e].
+ * q and out are [M, n_heads * head_dim], element type = dtype; out must not alias q.  head_dim must be
+ * even and at most 1024.  The caller guarantees 0 <= pos[b] and pos[b] + tokens_per_seq <= S_max
+ * (positions outside are clamped for memory safety, results for such rows are meaningless).
+ * Workspace: lowrank_workspace_bytes(LR_OP_DECODE_ATTENTION, ...), prepared like every workspace.
+ * Bound by streaming the visible K and V rows once; meant for the 1..32 rows of a decode step.
+ */
+int lowrank_decode_attention(const void *q, const lr_kv_target *kv, void *out, float scale, float rope_base,
+                             int dtype, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Offline prepack (Section 3.1, third paragraph; Figure 3): concatenate n (1..8) factors
  * U_list[i][d_in, r_list[i]] along the rank axis into U_packed[d_in, sum r_list].  U_list and
  * r_list are HOST arrays; the matrices are device memory.  Pure data movement: bit-exact.
@@ -142,6 +166,7 @@ int lowrank_pack_concat(const void *const *U_list, const int64_t *r_list, int n,
  *   LR_OP_LINEAR      d_in, r_total = r,                 d_out
  *   LR_OP_QKV         d_in, r_total = sum of r[i],       d_out = sum of d_out[i]
  *   LR_OP_PACKED_MLP  d_in = d, r_total = r_g + r_u + r_d, d_out = ffn
+ *   LR_OP_DECODE_ATTENTION  d_in = n_heads * head_dim, r_total = n_heads, d_out unused
  * Returns 0 for invalid arguments.  The value covers both phases whatever `phase` says.  For more
  * than 32 token rows it includes a fixed area of 64 MiB + 4 KiB in which the workgroups of a prefill
  * product that share one tile's K range hand their partial sums to each other.

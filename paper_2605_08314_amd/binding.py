@@ -24,7 +24,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 
 LR_F32, LR_BF16 = 0, 1
 LR_PHASE_DECODE, LR_PHASE_PREFILL, LR_PHASE_AUTO = 0, 1, 2
-LR_OP_LINEAR, LR_OP_QKV, LR_OP_PACKED_MLP = 0, 1, 2
+LR_OP_LINEAR, LR_OP_QKV, LR_OP_PACKED_MLP, LR_OP_DECODE_ATTENTION = 0, 1, 2, 3
 PHASES = {"decode": LR_PHASE_DECODE, "prefill": LR_PHASE_PREFILL, "auto": LR_PHASE_AUTO}
 
 _vp, _i64, _int, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
@@ -44,6 +44,8 @@ _lib.lowrank_qkv.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctyp
 _lib.lowrank_qkv.restype = _int
 _lib.lowrank_packed_mlp.argtypes = [_vp] * 10 + [_i64] * 6 + [_int, _int, _vp, _sz, _vp]
 _lib.lowrank_packed_mlp.restype = _int
+_lib.lowrank_decode_attention.argtypes = [_vp, ctypes.POINTER(lr_kv_target), _vp, ctypes.c_float, ctypes.c_float, _int, _vp, _sz, _vp]
+_lib.lowrank_decode_attention.restype = _int
 _lib.lowrank_pack_concat.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_i64), _int, _i64, _int, _vp, _vp]
 _lib.lowrank_pack_concat.restype = _int
 _lib.lowrank_workspace_bytes.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int]
@@ -181,6 +183,18 @@ def lowrank_packed_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, phase, w
                                    _ptr(b_g), _ptr(b_u), _ptr(b_d), _ptr(out), M, d, ffn, r_g, r_u, r_d,
                                    _dtype_code(x), _phase(phase), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def lowrank_decode_attention(q, k_cache, v_cache, pos, tokens_per_seq: int, out, scale: float, rope_base: float,
+                             workspace, stream=None) -> None:
+    """q, out [B * tokens_per_seq, n_heads * head_dim]; caches [B, S_max, n_heads, head_dim]; pos int32 [B].
+    Rotates the new k rows in place in ``k_cache`` when rope_base > 0."""
+    B, S_max, H, E = k_cache.shape
+    assert v_cache.shape == k_cache.shape and pos.dtype == torch.int32
+    assert q.shape == (B * tokens_per_seq, H * E) and out.shape == q.shape
+    kvs = lr_kv_target(_ptr(k_cache), _ptr(v_cache), _ptr(pos), B, S_max, H, E, tokens_per_seq, 0, 0)
+    _check(_lib.lowrank_decode_attention(_ptr(q), ctypes.byref(kvs), _ptr(out), scale, rope_base, _dtype_code(q),
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def lowrank_pack_concat(U_list: Sequence[torch.Tensor], U_packed: torch.Tensor, stream=None) -> None:

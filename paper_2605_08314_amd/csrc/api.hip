@@ -6,6 +6,7 @@
 #include "lr_common.hpp"
 #include "decode.hpp"
 #include "prefill.hpp"
+#include "attention.hpp"
 
 namespace lr {
 
@@ -83,10 +84,11 @@ const char* lowrank_version(void) { return "lowrank-mi355x 0.1 (gfx950)"; }
 
 size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
                                int dtype, int phase) {
-    if (op < LR_OP_LINEAR || op > LR_OP_PACKED_MLP) return 0;
+    if (op < LR_OP_LINEAR || op > LR_OP_DECODE_ATTENTION) return 0;
     if (M < 0 || d_in < 0 || r_total < 0 || d_out < 0) return 0;
     if (dtype != LR_F32 && dtype != LR_BF16) return 0;
     if (phase < LR_PHASE_DECODE || phase > LR_PHASE_AUTO) return 0;
+    if (op == LR_OP_DECODE_ATTENTION) return (r_total > 0 && d_in % r_total == 0) ? attn_ws_bytes(M, d_in, r_total) : 0;
     return ws_bytes_for(op, M, r_total, d_out);
 }
 
@@ -258,6 +260,25 @@ int lowrank_packed_mlp(const void* x, const void* U_gu, const void* V_g, const v
     st = generic_stage1(h, true, U_d, t + (r_g + r_u), ldt, M, ffn, r_d, dtype, s);
     if (st != LR_OK) return st;
     return generic_stage2(t + (r_g + r_u), ldt, V_d, b_d, out, M, r_d, d, none, dtype, s);
+}
+
+int lowrank_decode_attention(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base,
+                             int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    if (dtype != LR_F32 && dtype != LR_BF16) { set_error("unknown dtype %d", dtype); return LR_ERR_DTYPE; }
+    if (!kv) { set_error("kv is NULL"); return LR_ERR_NULL; }
+    if (kv->B < 0 || kv->tokens_per_seq < 1 || kv->S_max < kv->tokens_per_seq || kv->n_heads < 1 || kv->head_dim < 1) {
+        set_error("kv: bad cache shape"); return LR_ERR_SHAPE; }
+    if ((kv->head_dim & 1) || kv->head_dim > 1024) { set_error("head_dim must be even and at most 1024"); return LR_ERR_UNSUPPORTED; }
+    const int64_t M = kv->B * kv->tokens_per_seq, H = kv->n_heads, E = kv->head_dim;
+    if (M >= (1ll << 24) || H * E >= (1ll << 24) || kv->S_max >= (1ll << 30)) { set_error("size out of range"); return LR_ERR_SHAPE; }
+    if (M == 0) return LR_OK;
+    if (!q || !out || !kv->k_cache || !kv->v_cache || !kv->pos) { set_error("NULL operand"); return LR_ERR_NULL; }
+    if (!workspace) { set_error("workspace is NULL"); return LR_ERR_WORKSPACE; }
+    if (((uintptr_t)workspace) & 255u) { set_error("workspace must be 256-byte aligned"); return LR_ERR_ALIGN; }
+    const size_t need = attn_ws_bytes(M, H * E, H);
+    if (workspace_bytes < need) { set_error("workspace too small: %zu bytes given, %zu needed", workspace_bytes, need); return LR_ERR_WORKSPACE; }
+    const bool al = aligned16(q) && aligned16(out) && aligned16(kv->k_cache) && aligned16(kv->v_cache);
+    return attn_decode(q, kv, out, scale, rope_base, dtype, attn_fast_ok(dtype, E, al), workspace, (hipStream_t)stream);
 }
 
 int lowrank_pack_concat(const void* const* U_list, const int64_t* r_list, int n, int64_t d_in,

@@ -1,0 +1,137 @@
+"""Decode attention over the dense KV cache (with rotary embedding) against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2605_08314_amd import synth
+from util import TOL, max_rel_err
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+def make_case(rng, B, T, H, E, S_max, pos, dtype):
+    """Caches filled with history (already-rotated keys are just numbers), new raw k / v rows at pos .. pos+T-1."""
+    q = synth.to_dtype(rng.standard_normal((B * T, H * E)), dtype)
+    kc = synth.to_dtype(rng.standard_normal((B, S_max, H, E)), dtype)
+    vc = synth.to_dtype(rng.standard_normal((B, S_max, H, E)), dtype)
+    return q, kc, vc, np.asarray(pos, dtype=np.int32)
+
+
+def run_gpu(G, q, kc, vc, pos, T, scale, base, dtype, ws=None):
+    B = G.B
+    qd, kd, vd = G.dev(q), G.dev(kc), G.dev(vc)
+    Bn, S_max, H, E = kd.shape
+    out = torch.full(qd.shape, float("nan"), dtype=G.tdtype(dtype), device="cuda")
+    if ws is None:
+        ws = B.new_workspace(B.LR_OP_DECODE_ATTENTION, Bn * T, H * E, H, 0, G.code(dtype))
+    B.lowrank_decode_attention(qd, kd, vd, G.dev(pos), T, out, scale, base, ws)
+    torch.cuda.synchronize()
+    return out, kd, ws
+
+
+CASES = [  # (B, T, H, E, S_max, positions, dtype)  -- head_dim 64 / 128 / 256 in bf16 take the fast kernel
+    (1, 1, 32, 128, 2048, [2047], "bf16"),          # one long sequence: 24 splits per head
+    (1, 1, 32, 128, 8192, [5000], "bf16"),
+    (4, 1, 8, 128, 600, [0, 1, 37, 599], "bf16"),   # lengths 1, 2, 38, 600: mostly empty splits
+    (2, 3, 4, 64, 100, [0, 50], "bf16"),            # three new tokens per sequence, causal among them
+    (3, 1, 2, 256, 50, [49, 7, 20], "bf16"),
+    (32, 1, 32, 128, 300, list(range(100, 132)), "bf16"),   # a full decode batch: one split per (row, head)
+    (2, 2, 3, 32, 70, [5, 60], "bf16"),             # head_dim 32: generic kernel
+    (2, 2, 3, 16, 1100, [1000, 3], "f32"),          # fp32: generic kernel, several LDS chunks
+    (1, 1, 2, 128, 40, [39], "f32"),
+]
+
+
+@pytest.mark.parametrize("base", [0.0, 10000.0])
+@pytest.mark.parametrize("case", CASES)
+def test_decode_attention_matches_oracle(G, oracle, case, base):
+    Bn, T, H, E, S_max, pos, dtype = case
+    rng = np.random.default_rng(77 + S_max + H)
+    q, kc, vc, pos = make_case(rng, Bn, T, H, E, S_max, pos, dtype)
+    scale = E ** -0.5
+    out, kd, _ = run_gpu(G, q, kc, vc, pos, T, scale, base, dtype)
+    ok = kc.f64.copy()
+    want = oracle.decode_attention(q.f64, ok, vc.f64, pos, T, scale, rope_base=base)
+    assert max_rel_err(G.host64(out), want) <= TOL[dtype]
+    # the key cache: new rows rotated (rounded to the storage type), every other row untouched bit for bit
+    kb_in, kb_out, kh = kc.dev, G.bits(kd), G.host64(kd)
+    for b in range(Bn):
+        new = np.zeros(S_max, dtype=bool); new[pos[b]:pos[b] + T] = True
+        assert np.array_equal(kb_out[b][~new], (kb_in[b][~new].view(np.uint32) if dtype == "f32" else kb_in[b][~new]))
+        if base > 0:
+            assert max_rel_err(kh[b][new].reshape(T, -1), ok[b][new].reshape(T, -1)) <= (2.0 ** -8 if dtype == "bf16" else 1e-6)
+        else:
+            assert np.array_equal(kb_out[b][new], (kb_in[b][new].view(np.uint32) if dtype == "f32" else kb_in[b][new]))
+
+
+def test_repeated_calls_share_a_workspace(G, oracle):
+    """Counters and partials of the split reduction are left clean: long, short, long on one workspace."""
+    rng = np.random.default_rng(5)
+    H, E, S_max = 8, 128, 3000
+    ws = None
+    for n in (2999, 3, 1500):
+        q, kc, vc, pos = make_case(rng, 1, 1, H, E, S_max, [n - 1], "bf16")
+        out, _, ws = run_gpu(G, q, kc, vc, pos, 1, E ** -0.5, 10000.0, "bf16", ws)
+        want = oracle.decode_attention(q.f64, kc.f64.copy(), vc.f64, pos, 1, E ** -0.5, rope_base=10000.0)
+        assert max_rel_err(G.host64(out), want) <= TOL["bf16"]
+
+
+def test_single_position_returns_its_value_row(G):
+    rng = np.random.default_rng(6)
+    q, kc, vc, pos = make_case(rng, 2, 1, 4, 128, 16, [0, 0], "bf16")
+    out, _, _ = run_gpu(G, q, kc, vc, pos, 1, 0.1, 10000.0, "bf16")
+    assert np.array_equal(G.bits(out).reshape(2, 4, 128), vc.dev[:, 0])          # softmax over one position = 1: exact
+
+
+def test_decode_layer_chain_qkv_cache_rope_attention_o(G, oracle):
+    """lowrank_qkv writes raw k, v into the cache; attention rotates, attends; lowrank_linear projects."""
+    B = G.B
+    rng = np.random.default_rng(8)
+    Bn, H, E, S_max, d, r = 3, 4, 64, 40, 256, 64
+    pos = np.array([0, 17, 39], dtype=np.int32)
+    bf = lambda a: synth.to_dtype(a, "bf16")
+    x = bf(rng.standard_normal((Bn, d)))
+    Us = [bf(rng.standard_normal((d, r)) * d ** -0.5) for _ in range(4)]
+    Vs = [bf(rng.standard_normal((r, d)) * r ** -0.5) for _ in range(4)]
+    kc = bf(rng.standard_normal((Bn, S_max, H, E))); vc = bf(rng.standard_normal((Bn, S_max, H, E)))
+    kd, vd, pd = G.dev(kc), G.dev(vc), G.dev(pos)
+    qd = torch.empty((Bn, d), dtype=torch.bfloat16, device="cuda")
+    ad = torch.empty_like(qd); yd = torch.empty_like(qd)
+    w1 = B.new_workspace(B.LR_OP_QKV, Bn, d, 3 * r, 3 * d, B.LR_BF16, "decode")
+    w2 = B.new_workspace(B.LR_OP_DECODE_ATTENTION, Bn, d, H, 0, B.LR_BF16)
+    w3 = B.new_workspace(B.LR_OP_LINEAR, Bn, d, r, d, B.LR_BF16, "decode")
+    B.lowrank_qkv(G.dev(x), [G.dev(u) for u in Us[:3]], [G.dev(v) for v in Vs[:3]], None, [qd, None, None],
+                  dict(k_cache=kd, v_cache=vd, pos=pd, tokens_per_seq=1, k_index=1, v_index=2), "decode", w1)
+    B.lowrank_decode_attention(qd, kd, vd, pd, 1, ad, E ** -0.5, 10000.0, w2)
+    B.lowrank_linear(ad, G.dev(Us[3]), G.dev(Vs[3]), None, yd, "decode", w3)
+    for w in (w1, w3):
+        B.lowrank_workspace_status(w)
+    okc, ovc = kc.f64.copy(), vc.f64.copy()
+    qkv = oracle.qkv(x.f64, [u.f64 for u in Us[:3]], [v.f64 for v in Vs[:3]],
+                     kv=dict(k_cache=okc, v_cache=ovc, pos=pos, T=1, k_index=1, v_index=2))
+    att = oracle.decode_attention(qkv[0], okc, ovc, pos, 1, E ** -0.5, rope_base=10000.0)
+    want = oracle.linear(att, Us[3].f64, Vs[3].f64)
+    assert max_rel_err(G.host64(ad), att) <= TOL["bf16"]
+    assert max_rel_err(G.host64(yd), want) <= TOL["bf16"]
+
+
+def test_attention_error_codes(G):
+    B = G.B
+    q = torch.zeros((1, 6), dtype=torch.bfloat16, device="cuda")
+    kc = torch.zeros((1, 4, 2, 3), dtype=torch.bfloat16, device="cuda")        # odd head_dim
+    pos = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.LowrankError):
+        B.lowrank_decode_attention(q, kc, kc.clone(), pos, 1, torch.empty_like(q), 1.0, 0.0, ws)
+    q = torch.zeros((1, 8), dtype=torch.bfloat16, device="cuda")
+    kc = torch.zeros((1, 4, 2, 4), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.LowrankError):                                            # workspace too small
+        B.lowrank_decode_attention(q, kc, kc.clone(), pos, 1, torch.empty_like(q), 1.0, 0.0, ws[:256])
+    assert B.lowrank_workspace_bytes(B.LR_OP_DECODE_ATTENTION, 1, 8, 3, 0, B.LR_BF16, "decode") == 0   # 8 % 3 != 0
