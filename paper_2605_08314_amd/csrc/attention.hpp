@@ -6,11 +6,10 @@ namespace lr {
 
 constexpr int kAttnMaxSplit = 32;     // workgroups that may share the cached positions of one (row, head)
 
-// Workspace: header | rotated queries (8 bytes per element) | split partials | split counters.
+// Workspace: header | rotated queries (8 bytes per element) | partial results of the shares.
 struct AttnLayout {
     void* q_rot;                 // [M, H*E]: fp32 (fast path) or fp64 (generic path)
     float* part;                 // [M*H, kAttnMaxSplit, E + 2]: {max, sum, weighted V[E]}
-    uint32_t* counter;           // [M*H], zero between calls
 };
 size_t attn_ws_bytes(int64_t M, int64_t d, int64_t H);
 AttnLayout attn_layout(void* ws, int64_t M, int64_t d, int64_t H);

@@ -2,15 +2,18 @@
 // paragraph: the present token's q/k/v are reconstructed once, the history is read from a standard
 // dense cache [batch, position, head, head_dim]; Section 4: RoPE on q and k).
 //
-// Two launches per call:
-//   k_attn_prepare   rotates the T new key rows of every sequence in place in the cache and writes the
-//                    rotated queries (pre-scaled for the fast kernel) to the workspace;
-//   k_attn_decode    one workgroup per (token row, head, split of the visible positions): streams its
+//   k_attn_decode    one workgroup per (token row, head, share of the visible positions): streams its
 //                    share of K and V once (the step is bound by those bytes), online softmax per group
-//                    of E/8 lanes, groups combined through LDS, splits combined by the last workgroup
-//                    to arrive (partials and the arrival counter go through device-coherent accesses).
+//                    of E/8 lanes, groups combined through LDS.  With one new token per sequence it also
+//                    rotates its query and -- the workgroup whose share ends there -- the new key row.
+//   k_attn_combine   folds the shares of one (row, head).  (A combine by the last workgroup to arrive,
+//                    through device-coherent accesses and a counter, was measured slower than this
+//                    second launch: the arrivals at one counter serialise.)
+//   k_attn_prepare   only with several new tokens per sequence: rotates all new key rows in place first
+//                    and writes the rotated queries to the workspace.
 // A generic kernel (any head_dim, fp32 caches, fp64 arithmetic for fp32 data) covers what the fast one
 // does not.
+#include <stdlib.h>
 #include "attention.hpp"
 
 namespace lr {
@@ -18,7 +21,7 @@ namespace lr {
 size_t attn_ws_bytes(int64_t M, int64_t d, int64_t H) {
     const int64_t E = H > 0 ? d / H : 0;
     return kHeaderBytes + align256((size_t)M * (size_t)d * 8) +
-           align256((size_t)M * (size_t)H * kAttnMaxSplit * (size_t)(E + 2) * 4) + align256((size_t)M * (size_t)H * 4);
+           align256((size_t)M * (size_t)H * kAttnMaxSplit * (size_t)(E + 2) * 4);
 }
 
 AttnLayout attn_layout(void* ws, int64_t M, int64_t d, int64_t H) {
@@ -26,8 +29,7 @@ AttnLayout attn_layout(void* ws, int64_t M, int64_t d, int64_t H) {
     AttnLayout L;
     char* p = (char*)ws + kHeaderBytes;
     L.q_rot = p; p += align256((size_t)M * (size_t)d * 8);
-    L.part = (float*)p; p += align256((size_t)M * (size_t)H * kAttnMaxSplit * (size_t)(E + 2) * 4);
-    L.counter = (uint32_t*)p;
+    L.part = (float*)p;
     return L;
 }
 
@@ -48,12 +50,30 @@ template <> struct AIo<bf16_t> {
 
 struct AttnArgs {
     const void* q; void* q_rot; void* k_cache; const void* v_cache; const int32_t* pos; void* out;
-    float* part; uint32_t* counter;
+    float* part;
     int M, T, H, E, S_max, NS;
     float qscale;           // what the stored queries are multiplied by (fast path: scale * log2 e; generic: 1)
     float scale;
     double rope_base;       // <= 0: no rotation
 };
+
+// cos and sin of position * base^(-2i/E).  The angle is formed and reduced to [-pi, pi] in fp64 (a position of
+// 10^5 times a relative error of 10^-7 would already be 10^-2 rad); for bf16 data the functions themselves are
+// then evaluated in fp32, for fp32 data in fp64.
+template <typename QR>
+__device__ __forceinline__ void rope_cos_sin(long long p, int i, int E, double base, double& c, double& sn) {
+    const double theta = exp2(-2.0 * (double)i / (double)E * log2(base));
+    const double ang = (double)p * theta;
+    if constexpr (sizeof(QR) == 8) {
+        c = cos(ang); sn = sin(ang);
+    } else {
+        const double k = rint(ang * 0.15915494309189535);                    // 1 / (2 pi)
+        const double red = fma(-k, 1.2246467991473532e-16 * 2.0, fma(-k, 6.283185307179586, ang));
+        float sf, cf;
+        sincosf((float)red, &sf, &cf);
+        c = (double)cf; sn = (double)sf;
+    }
+}
 
 // ---- prepare: rotate-half RoPE, pair (i, i + E/2), angle = position * base^(-2i/E), in fp64 ------
 template <typename T, typename QR>
@@ -71,8 +91,8 @@ __global__ void __launch_bounds__(256) k_attn_prepare(AttnArgs a) {
         QR* qr = reinterpret_cast<QR*>(a.q_rot);
         double qlo = (double)AIo<T>::ld(q + qo), qhi = (double)AIo<T>::ld(q + qo + half);
         if (a.rope_base > 0.0) {
-            const double ang = (double)p * pow(a.rope_base, -2.0 * (double)i / (double)a.E);
-            const double c = cos(ang), sn = sin(ang);
+            double c, sn;
+            rope_cos_sin<QR>(p, i, a.E, a.rope_base, c, sn);
             const double lo = qlo * c - qhi * sn, hi = qhi * c + qlo * sn;
             qlo = lo; qhi = hi;
             if (p >= 0 && p < a.S_max) {
@@ -88,15 +108,6 @@ __global__ void __launch_bounds__(256) k_attn_prepare(AttnArgs a) {
 }
 
 // ---- fast kernel ----------------------------------------------------------------------------------
-__device__ __forceinline__ uint2 ld_dev64(const void* p) {
-    const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
-}
-__device__ __forceinline__ void st_dev64(void* p, float lo, float hi) {
-    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), (uint64_t)__float_as_uint(lo) | ((uint64_t)__float_as_uint(hi) << 32),
-                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
     f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
     f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
@@ -104,56 +115,121 @@ __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
     f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
 }
 
-template <int E>
+// How the visible positions [0, n) of one (row, head) are shared: `ns` workgroups (at most NS, each with at
+// least one sweep of KG positions), `per` positions each.  The same arithmetic runs in the main kernel and in
+// the combine kernel.
+__device__ __forceinline__ void split_of(int n, int NS, int KG, int& ns, int& per) {
+    int want = (n + KG - 1) / KG;
+    want = want < 1 ? 1 : (want > NS ? NS : want);
+    per = (n + want - 1) / want;
+    per = (per + KG - 1) / KG * KG;
+    if (per < KG) per = KG;
+    ns = (n + per - 1) / per;           // every share [sp * per, ...) with sp < ns starts below n
+    if (ns < 1) ns = 1;
+}
+
+__device__ __forceinline__ int visible_positions(const AttnArgs& a, int b, int s) {
+    const long long nn = (long long)a.pos[b] + s + 1;                 // causal
+    return (int)(nn < 0 ? 0 : (nn > a.S_max ? a.S_max : nn));
+}
+
+// FUSED (one new token per sequence): the workgroup rotates its head's query itself, and the workgroup whose
+// share ends at the new position rotates that key row in the cache; no prepare launch.  Otherwise the rotated,
+// pre-scaled queries come from the workspace and the cache is already rotated.
+template <int E, bool FUSED>
 __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
     constexpr int G = E / 8;            // lanes that share one cached position (16 bytes each)
     constexpr int KG = 256 / G;         // positions a workgroup takes per sweep = number of lane groups
-    constexpr int UNR = 4;              // positions in flight per group
+    constexpr int UNR = 4;              // positions per group and sweep; two sweeps are in flight
     __shared__ float s_m[KG], s_l[KG];
     __shared__ float s_acc[KG][E];
-    __shared__ uint32_t s_last;
+    __shared__ float s_q[E], s_knew[E];
     const int tid = threadIdx.x, grp = tid / G, gl = tid % G;
     const int sp = blockIdx.x % a.NS, rh = blockIdx.x / a.NS;
     const int h = rh % a.H, r = rh / a.H;
     const int b = r / a.T, s = r - b * a.T;
-    long long nn = (long long)a.pos[b] + s + 1;                 // visible positions (causal)
-    const int n = (int)(nn < 0 ? 0 : (nn > a.S_max ? a.S_max : nn));
-    int per = (n + a.NS - 1) / a.NS;
-    per = (per + KG - 1) / KG * KG;
+    const int n = visible_positions(a, b, s);
+    int ns, per;
+    split_of(n, a.NS, KG, ns, per);
+    if (sp >= ns) return;               // nothing for this workgroup (whole workgroup leaves)
     const int j0 = sp * per, j1 = (j0 + per < n) ? j0 + per : n;
 
+    const size_t row_stride = (size_t)a.H * E;
+    bf16_t* kbase = reinterpret_cast<bf16_t*>(a.k_cache) + ((size_t)b * a.S_max * a.H + h) * E;
+    const bf16_t* kb = kbase + gl * 8;
+    const bf16_t* vb = reinterpret_cast<const bf16_t*>(a.v_cache) + ((size_t)b * a.S_max * a.H + h) * E + gl * 8;
+    const bool rope = a.rope_base > 0.0;
+    const bool holds_new = FUSED && rope && j1 == n && n > 0;       // this share ends with the new token's key
+
+    // first sweep's loads go out before anything else
+    uint4 kk[UNR], vv[UNR];
+    int j = j0 + grp;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        const int jj = j + u * KG;
+        const int jc = jj < j1 ? jj : (j < j1 ? j : j0);             // positions past the end repeat a valid one; unused
+        kk[u] = *reinterpret_cast<const uint4*>(kb + (size_t)jc * row_stride);
+        vv[u] = *reinterpret_cast<const uint4*>(vb + (size_t)jc * row_stride);
+    }
+
     float qv[8];
-    {
+    if constexpr (FUSED) {
+        if (tid < E / 2) {
+            const bf16_t* q = reinterpret_cast<const bf16_t*>(a.q) + (size_t)r * a.H * E + (size_t)h * E;
+            double qlo = (double)bf16_to_f32(q[tid]), qhi = (double)bf16_to_f32(q[tid + E / 2]);
+            if (rope) {
+                double c, sn;
+                rope_cos_sin<float>((long long)n - 1, tid, E, a.rope_base, c, sn);
+                const double lo = qlo * c - qhi * sn, hi = qhi * c + qlo * sn;
+                qlo = lo; qhi = hi;
+                if (holds_new) {
+                    bf16_t* kn = kbase + (size_t)(n - 1) * row_stride;
+                    const double klo = (double)bf16_to_f32(kn[tid]), khi = (double)bf16_to_f32(kn[tid + E / 2]);
+                    const bf16_t rlo = f32_to_bf16((float)(klo * c - khi * sn)), rhi = f32_to_bf16((float)(khi * c + klo * sn));
+                    kn[tid] = rlo; kn[tid + E / 2] = rhi;             // the cache keeps the rotated key
+                    s_knew[tid] = bf16_to_f32(rlo); s_knew[tid + E / 2] = bf16_to_f32(rhi);
+                }
+            }
+            s_q[tid] = (float)(qlo * (double)a.qscale); s_q[tid + E / 2] = (float)(qhi * (double)a.qscale);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv[e] = s_q[gl * 8 + e];
+    } else {
         const float* q = reinterpret_cast<const float*>(a.q_rot) + (size_t)r * a.H * E + (size_t)h * E + gl * 8;
         const float4 q0 = *reinterpret_cast<const float4*>(q), q1 = *reinterpret_cast<const float4*>(q + 4);
         qv[0] = q0.x; qv[1] = q0.y; qv[2] = q0.z; qv[3] = q0.w; qv[4] = q1.x; qv[5] = q1.y; qv[6] = q1.z; qv[7] = q1.w;
     }
-    const size_t row_stride = (size_t)a.H * E;
-    const bf16_t* kb = reinterpret_cast<const bf16_t*>(a.k_cache) + ((size_t)b * a.S_max * a.H + h) * E + gl * 8;
-    const bf16_t* vb = reinterpret_cast<const bf16_t*>(a.v_cache) + ((size_t)b * a.S_max * a.H + h) * E + gl * 8;
 
     float m = -INFINITY, l = 0.f, acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int j = j0 + grp; j < j1; j += KG * UNR) {
-        uint4 kk[UNR], vv[UNR];
+    for (; j < j1; j += KG * UNR) {
+        // next sweep's loads fly while this one is used
+        uint4 kn[UNR], vn[UNR];
+        const int jn = j + KG * UNR;
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int jj = j + u * KG;
-            const int jc = jj < j1 ? jj : j;                    // positions past the end repeat a valid one; unused
-            kk[u] = *reinterpret_cast<const uint4*>(kb + (size_t)jc * row_stride);
-            vv[u] = *reinterpret_cast<const uint4*>(vb + (size_t)jc * row_stride);
+            const int jj = jn + u * KG;
+            const int jc = jj < j1 ? jj : j;
+            kn[u] = *reinterpret_cast<const uint4*>(kb + (size_t)jc * row_stride);
+            vn[u] = *reinterpret_cast<const uint4*>(vb + (size_t)jc * row_stride);
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
+            const int jj = j + u * KG;
             float kf[8], vf[8];
             unpack8(kk[u], kf);
+            if (holds_new && jj == n - 1) {                                  // the key this workgroup has just rotated
+#pragma unroll
+                for (int e = 0; e < 8; ++e) kf[e] = s_knew[gl * 8 + e];
+            }
             float sc = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) sc += qv[e] * kf[e];
 #pragma unroll
             for (int w = 1; w < G; w <<= 1) sc += __shfl_xor(sc, w, 64);    // the G lanes of a group are neighbours
-            if (j + u * KG < j1) {                                          // uniform inside a group
+            if (jj < j1) {                                                   // uniform inside a group
                 unpack8(vv[u], vf);
                 const float mn = fmaxf(m, sc);
                 const float corr = __builtin_amdgcn_exp2f(m - mn), pw = __builtin_amdgcn_exp2f(sc - mn);
@@ -163,55 +239,63 @@ __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
                 m = mn;
             }
         }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) { kk[u] = kn[u]; vv[u] = vn[u]; }
     }
     // groups -> workgroup
     if (gl == 0) { s_m[grp] = m; s_l[grp] = l; }
 #pragma unroll
     for (int e = 0; e < 8; ++e) s_acc[grp][gl * 8 + e] = acc[e];
     __syncthreads();
-    float Mw = -INFINITY, Lw = 0.f, ow = 0.f;
     if (tid < E) {
+        float Mw = -INFINITY, Lw = 0.f, ow = 0.f;
         for (int g = 0; g < KG; ++g) Mw = fmaxf(Mw, s_m[g]);
         for (int g = 0; g < KG; ++g) {
             const float wgt = s_m[g] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s_m[g] - Mw);
             Lw += s_l[g] * wgt;
             ow += s_acc[g][tid] * wgt;
         }
-    }
-    bf16_t* orow = reinterpret_cast<bf16_t*>(a.out) + (size_t)r * a.H * E + (size_t)h * E;
-    if (a.NS == 1) {
-        if (tid < E) orow[tid] = f32_to_bf16(Lw > 0.f ? ow / Lw : 0.f);
-        return;
-    }
-    // splits -> result: hand {max, sum, weighted V} to whoever arrives last
-    float* mine = a.part + ((size_t)rh * kAttnMaxSplit + sp) * (E + 2);
-    const float o1 = __shfl_down(ow, 1, 64);                        // every lane takes part; even lanes store a pair
-    if (tid < E && (tid & 1) == 0) st_dev64(mine + 2 + tid, ow, o1);
-    if (tid == 0) st_dev64(mine, Mw, Lw);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // this wave's stores have been performed
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t old = __hip_atomic_fetch_add(a.counter + rh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (old == (uint32_t)a.NS - 1u) ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    if (tid < E) {
-        const float* base = a.part + (size_t)rh * kAttnMaxSplit * (E + 2);
-        float Mt = -INFINITY;
-        for (int c = 0; c < a.NS; ++c) Mt = fmaxf(Mt, __uint_as_float(ld_dev64(base + (size_t)c * (E + 2)).x));
-        float Lt = 0.f, ot = 0.f;
-        for (int c = 0; c < a.NS; ++c) {
-            const uint2 ml = ld_dev64(base + (size_t)c * (E + 2));
-            const float mc = __uint_as_float(ml.x);
-            const float wgt = mc == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mc - Mt);
-            const uint2 ov = ld_dev64(base + (size_t)c * (E + 2) + 2 + (tid & ~1));
-            Lt += __uint_as_float(ml.y) * wgt;
-            ot += __uint_as_float((tid & 1) ? ov.y : ov.x) * wgt;
+        if (ns == 1) {
+            reinterpret_cast<bf16_t*>(a.out)[(size_t)r * a.H * E + (size_t)h * E + tid] = f32_to_bf16(Lw > 0.f ? ow / Lw : 0.f);
+        } else {
+            // {max, sum, weighted V} of this share; the combine launch folds the shares
+            float* mine = a.part + ((size_t)rh * kAttnMaxSplit + sp) * (E + 2);
+            mine[2 + tid] = ow;
+            if (tid == 0) { mine[0] = Mw; mine[1] = Lw; }
         }
-        orow[tid] = f32_to_bf16(Lt > 0.f ? ot / Lt : 0.f);
     }
-    if (tid == 0) __hip_atomic_store(a.counter + rh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int E>
+__global__ void __launch_bounds__(E) k_attn_combine(AttnArgs a) {
+    constexpr int KG = 256 / (E / 8);
+    const int tid = threadIdx.x, rh = blockIdx.x;
+    const int h = rh % a.H, r = rh / a.H;
+    const int b = r / a.T, s = r - b * a.T;
+    int ns, per;
+    split_of(visible_positions(a, b, s), a.NS, KG, ns, per);
+    if (ns == 1) return;                                             // the main kernel has written this row already
+    const float* base = a.part + (size_t)rh * kAttnMaxSplit * (E + 2);
+    // every load of this kernel is issued before the first one is used: two memory round trips in all
+    __shared__ float s_pm[kAttnMaxSplit], s_pl[kAttnMaxSplit];
+    float ov[kAttnMaxSplit];
+#pragma unroll
+    for (int c = 0; c < kAttnMaxSplit; ++c) ov[c] = base[(size_t)(c < ns ? c : ns - 1) * (E + 2) + 2 + tid];
+    if (tid < ns) { s_pm[tid] = base[(size_t)tid * (E + 2)]; s_pl[tid] = base[(size_t)tid * (E + 2) + 1]; }
+    __syncthreads();
+    float Mt = -INFINITY;
+    for (int c = 0; c < ns; ++c) Mt = fmaxf(Mt, s_pm[c]);
+    float Lt = 0.f, ot = 0.f;
+#pragma unroll
+    for (int c = 0; c < kAttnMaxSplit; ++c) {
+        if (c < ns) {
+            const float mc = s_pm[c];
+            const float wgt = mc == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mc - Mt);
+            Lt += s_pl[c] * wgt;
+            ot += ov[c] * wgt;
+        }
+    }
+    reinterpret_cast<bf16_t*>(a.out)[(size_t)r * a.H * E + (size_t)h * E + tid] = f32_to_bf16(Lt > 0.f ? ot / Lt : 0.f);
 }
 
 // ---- generic kernel: one workgroup per (row, head), positions in chunks through LDS ---------------
@@ -279,21 +363,30 @@ int attn_decode(const void* q, const lr_kv_target* kv, void* out, float scale, f
     const AttnLayout L = attn_layout(ws, M, d, H);
     AttnArgs a;
     a.q = q; a.q_rot = L.q_rot; a.k_cache = kv->k_cache; a.v_cache = kv->v_cache; a.pos = kv->pos; a.out = out;
-    a.part = L.part; a.counter = L.counter;
+    a.part = L.part;
     a.M = (int)M; a.T = (int)kv->tokens_per_seq; a.H = (int)H; a.E = (int)E; a.S_max = (int)kv->S_max;
     a.scale = scale; a.rope_base = (double)rope_base;
     const long long pairs = (long long)M * H * (E / 2);
     const unsigned pg = (unsigned)((pairs + 255) / 256 < 4096 ? (pairs + 255) / 256 : 4096);
     if (fast) {
-        // enough workgroups to cover the chip three times over, at most kAttnMaxSplit per (row, head)
-        int ns = (int)((768 + M * H - 1) / (M * H));
+        // about two workgroups per CU, at most kAttnMaxSplit per (row, head)
+        int ns = (int)((512 + M * H - 1) / (M * H));
+        { static const char* e = getenv("LOWRANK_ATTN_SPLITS"); if (e) ns = atoi(e); }
         a.NS = ns < 1 ? 1 : (ns > kAttnMaxSplit ? kAttnMaxSplit : ns);
         a.qscale = scale * 1.4426950408889634f;
-        hipLaunchKernelGGL((k_attn_prepare<bf16_t, float>), dim3(pg), dim3(256), 0, s, a);
-        const dim3 grid((unsigned)(M * H * a.NS));
-        if (E == 64) hipLaunchKernelGGL((k_attn_decode<64>), grid, dim3(256), 0, s, a);
-        else if (E == 128) hipLaunchKernelGGL((k_attn_decode<128>), grid, dim3(256), 0, s, a);
-        else hipLaunchKernelGGL((k_attn_decode<256>), grid, dim3(256), 0, s, a);
+        const bool fused = kv->tokens_per_seq == 1;
+        if (!fused) hipLaunchKernelGGL((k_attn_prepare<bf16_t, float>), dim3(pg), dim3(256), 0, s, a);
+        const dim3 grid((unsigned)(M * H * a.NS)), cgrid((unsigned)(M * H));
+#define LR_ATTN_LAUNCH(EE)                                                                                  \
+        do {                                                                                                \
+            if (fused) hipLaunchKernelGGL((k_attn_decode<EE, true>), grid, dim3(256), 0, s, a);             \
+            else hipLaunchKernelGGL((k_attn_decode<EE, false>), grid, dim3(256), 0, s, a);                  \
+            if (a.NS > 1) hipLaunchKernelGGL((k_attn_combine<EE>), cgrid, dim3(EE), 0, s, a);               \
+        } while (0)
+        if (E == 64) LR_ATTN_LAUNCH(64);
+        else if (E == 128) LR_ATTN_LAUNCH(128);
+        else LR_ATTN_LAUNCH(256);
+#undef LR_ATTN_LAUNCH
         return launch_status("decode attention");
     }
     a.NS = 1; a.qscale = 1.f;
