@@ -13,6 +13,7 @@ The same JSON line also carries
   roofline      the dominant kernel family (decode packed MLP) timed alone with HIP events,
   prefill       TFLOP/s of one layer (QKV + O + MLP, config 4) at S rows, algorithmic flops,
   decode_ops    per-entry-point GB/s for each batch size,
+  decode_attention  attention over the dense cache (with rotary embedding) at several cached lengths,
   cpu_baseline  the fp64 oracle timed on this machine's host cores on a bounded sample.
 """
 from __future__ import annotations
@@ -123,6 +124,31 @@ def run_prefill(torch, B, gen, ly, S):
     return {"workload": f"one layer, S={S}, ranks {R_ATTN}/{R_MLP}", "plan": plan, "ms": round(pms, 3),
             "TFLOPs": round(tf, 1), "frac_mfma_bf16_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
             "tokens_per_s": round(S / (pms * 1e-3), 1)}
+
+
+def run_decode_attention(torch, B, gen, cases=((1, 512), (1, 2048), (1, 8192), (32, 2048)), layers=8):
+    """Attention over the dense cache with rotary embedding, one new token per sequence: us per call and GB/s of
+    the K and V rows it has to read (plus q and out), rotated over `layers` distinct caches, HIP-graph replay."""
+    bf = torch.bfloat16
+    rows = {}
+    for Bn, n in cases:
+        kcs = [torch.randn((Bn, n, HEADS, HEAD_DIM), device="cuda", dtype=bf, generator=gen) for _ in range(layers)]
+        vcs = [torch.randn((Bn, n, HEADS, HEAD_DIM), device="cuda", dtype=bf, generator=gen) for _ in range(layers)]
+        q = torch.randn((Bn, D), device="cuda", dtype=bf, generator=gen)
+        out = torch.empty_like(q)
+        pos = torch.full((Bn,), n - 1, device="cuda", dtype=torch.int32)
+        ws = B.new_workspace(B.LR_OP_DECODE_ATTENTION, Bn, D, HEADS, 0, B.LR_BF16)
+
+        def sweep_attn():
+            for i in range(layers):
+                B.lowrank_decode_attention(q, kcs[i], vcs[i], pos, 1, out, HEAD_DIM ** -0.5, 10000.0, ws)
+
+        ms = time_region(torch, capture(torch, sweep_attn), 10, 2) / layers
+        by = 2 * Bn * n * D * 2 + 2 * Bn * D * 2
+        rows[f"B{Bn}_len{n}"] = {"us": round(ms * 1e3, 2), "GBps": round(by / (ms * 1e-3) / 1e9, 1),
+                                 "frac_hbm_peak": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del kcs, vcs
+    return rows
 
 
 def main():
@@ -276,6 +302,7 @@ def main():
         out["decode_ops"] = table
 
         out["prefill"] = run_prefill(torch, B, gen, layers[0], args.prefill_rows)
+        out["decode_attention"] = run_decode_attention(torch, B, gen)
 
         # ---- CPU baseline: the oracle as it stands, on this machine's host cores, bounded sample
         import numpy as np
@@ -293,7 +320,7 @@ def main():
             oracle.packed_mlp(tm["x"].f64, tm["U_gu"].f64, tm["V_g"].f64, tm["V_u"].f64, tm["U_d"].f64, tm["V_d"].f64)
             reps += 1
             el = time.perf_counter() - t_start
-            if el > 10.0 or reps >= 20:
+            if el > 12.0 or reps >= 2000:      # about 12 s of CPU work
                 break
         layer_bytes = sum(attn_bytes(Bs)) + mlp_bytes(Bs)
         out["cpu_baseline"] = {"value": round(reps * layer_bytes / el / 1e9, 3), "unit": "GB/s",
