@@ -162,6 +162,7 @@ def main():
     ap.add_argument("--eager", action="store_true", help="plain launches instead of HIP-graph replay")
     ap.add_argument("--quick", action="store_true", help="skip the per-batch table, prefill and the CPU baseline")
     ap.add_argument("--prefill-only", action="store_true", help="only the prefill layer (for profiling): one JSON line with its numbers")
+    ap.add_argument("--attention-only", action="store_true", help="only the decode-attention rows (for profiling)")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for rocprofv3 --pmc runs: a 256 MiB plain copy (known traffic) and 32 eager decode-MLP launches, nothing else")
     args = ap.parse_args()
@@ -179,6 +180,9 @@ def main():
     L, Bt = args.layers, args.batch
     if args.pmc_mode:
         L = min(L, 8)
+    if args.attention_only:
+        print(json.dumps({"attention_only": True, "decode_attention": run_decode_attention(torch, B, gen)}))
+        return
     if args.prefill_only:
         print(json.dumps({"prefill_only": True, "prefill": run_prefill(torch, B, gen, Layer(torch, gen=gen), args.prefill_rows)}))
         return
