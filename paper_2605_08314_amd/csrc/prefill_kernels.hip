@@ -112,23 +112,17 @@ __device__ __forceinline__ void dma_maybe_read_b(bf16x8_t (&bfn)[BN / 64], const
     constexpr int MI = BM / 64, NI = BN / 64;
     if constexpr (NIi < NI) {
         if constexpr ((NIi * MI) / NI == C) {
-#ifndef LR_ABLATE_READS_B
             bfn[NIi] = dma_read_b<BM, BN, NIi>(stage, f, kk);
-#endif
         }
     }
 }
 template <int BM, int BN, int C>
 __device__ __forceinline__ void dma_read_chunk(bf16x8_t (&afn)[BM / 64], bf16x8_t (&bfn)[BN / 64], const char* stage, const FragAddr<BM, BN>& f, int kk) {
-#ifndef LR_ABLATE_READS
-#ifndef LR_ABLATE_READS_A
     afn[C] = dma_read_a<BM, BN, C>(stage, f, kk);
-#endif
     dma_maybe_read_b<BM, BN, C, 0>(bfn, stage, f, kk);
     dma_maybe_read_b<BM, BN, C, 1>(bfn, stage, f, kk);
     dma_maybe_read_b<BM, BN, C, 2>(bfn, stage, f, kk);
     dma_maybe_read_b<BM, BN, C, 3>(bfn, stage, f, kk);
-#endif
 }
 
 // chunk C of a substep: its share of the next substep's fragment reads, then the MFMAs of row block C
@@ -143,14 +137,12 @@ template <int BM, int BN, int C, int NIi, bool ZERO, class IS>
 __device__ __forceinline__ void dma_mfma_one(f32x16_t (&acc)[BM / 64][BN / 64], const bf16x8_t (&afc)[BM / 64], const bf16x8_t (&bfc)[BN / 64], const IS& is) {
     constexpr int MI = BM / 64, NI = BN / 64, S = MI * NI, L = MI + NI;
     if constexpr (NIi < NI) {
-#ifndef LR_ABLATE_MFMA
         if constexpr (ZERO) {       // first product of a tile: the accumulator starts from the constant 0
             const f32x16_t z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             acc[C][NIi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[NIi], afc[C], z, 0, 0, 0);
         } else {
             acc[C][NIi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfc[NIi], afc[C], acc[C][NIi], 0, 0, 0);
         }
-#endif
         constexpr int slot = C * NI + NIi;
         constexpr int j = (slot * L + S - 1) / S;           // the request whose place floor(j * S / L) could be this slot
         if constexpr (j < L && (j * S) / L == slot) {
