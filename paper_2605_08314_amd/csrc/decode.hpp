@@ -16,6 +16,7 @@ struct DProb {
     bf16_t* Y;                                              // EPI_STORE / EPI_GATEUP: bf16 output [M, N] (nullable for STORE)
     const bf16_t* bias; const bf16_t* bias2;
     void* cache; const int32_t* pos; int S_max; int T;      // EPI_STORE: optional dense-cache scatter
+    float* part;      // EPI_ATOMIC with bf16 finalisation: fp32 partial tiles, one slot of 16*MB x NC floats per tile of the stage
     int ldy;          // EPI_ATOMIC with bf16 finalisation: row stride of Y (the bf16 copy of the accumulator)
     int ctile_begin;  // EPI_ATOMIC with bf16 finalisation: index of this product's first column-tile counter
     int tiles_n;      // column tiles (N / NC)
@@ -50,13 +51,17 @@ static_assert(sizeof(Ctrl) <= kHeaderBytes, "control block must fit the workspac
 constexpr size_t kSkFlagBytes = 4096;
 constexpr size_t kSkSlotBytes = (size_t)256 * 256 * 256 * 4;
 constexpr size_t kSkBytes = kSkFlagBytes + kSkSlotBytes;
-inline size_t sk_tail_bytes(int64_t M) { return M > 32 ? kSkBytes : 0; }
+// Tail of a decode workspace for 9..32 token rows: fp32 partial tiles of the split-K stages (one slot per
+// workgroup tile; the last K-slice of a column tile to arrive adds them up in slice order and writes bf16).
+constexpr size_t kDecPartBytes = (size_t)8 << 20;
+inline size_t sk_tail_bytes(int64_t M) { return M > 32 ? kSkBytes : (M > 8 ? kDecPartBytes : 0); }
 
 // Where the parts of a workspace of `ws_bytes` bytes for M token rows sit:
-// header | acc area 0 | acc area 1 | staging | shared-K tail (M > 32 only).
+// header | acc area 0 | acc area 1 | staging | tail (decode partial tiles for 8 < M <= 32, shared-K area for M > 32).
 struct WsLayout {
     Ctrl* ctrl; char* acc0; size_t acc_bytes; char* staging; size_t staging_bytes;
-    uint32_t* sk_flags; float* sk_slots;       // NULL without the tail
+    uint32_t* sk_flags; float* sk_slots;       // prefill tail (M > 32), else NULL
+    float* dec_part;                           // decode partial tiles (8 < M <= 32), else NULL
 };
 inline WsLayout ws_layout(void* ws, size_t ws_bytes, int64_t M) {
     WsLayout L;
@@ -68,8 +73,9 @@ inline WsLayout ws_layout(void* ws, size_t ws_bytes, int64_t M) {
     L.staging = L.acc0 + 2 * L.acc_bytes;
     L.staging_bytes = body - kHeaderBytes - 2 * L.acc_bytes;
     char* t = (char*)ws + (body & ~(size_t)255);
-    L.sk_flags = tail ? (uint32_t*)t : nullptr;
-    L.sk_slots = tail ? (float*)(t + kSkFlagBytes) : nullptr;
+    L.sk_flags = M > 32 ? (uint32_t*)t : nullptr;
+    L.sk_slots = M > 32 ? (float*)(t + kSkFlagBytes) : nullptr;
+    L.dec_part = (M > 8 && M <= 32) ? (float*)t : nullptr;
     return L;
 }
 

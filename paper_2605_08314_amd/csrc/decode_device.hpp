@@ -263,12 +263,20 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
             }
         if (m < M) {
             if constexpr (EPI == EPI_ATOMIC) {
+                if (tcnt) {
+                    // more than 8 token rows: the partial tile goes to its own slot (plain device-coherent stores, no
+                    // atomics: 2048 of them per workgroup were what bound these stages); see the finalisation below
+                    float* ps = P.part + (size_t)(P.tile_begin + lt) * (16 * MB * NC) + (size_t)m * NC + (n - n0);
+#pragma unroll
+                    for (int b = 0; b < CPL; b += 2) st_coherent_b64(ps + b, make_uint2(__float_as_uint(val[0][b]), __float_as_uint(val[0][b + 1])));
+                } else {
                 // RETURNING atomics: a non-returning one is acknowledged as soon as the L2 has accepted it,
                 // before it is performed where other XCDs can see it; its return value only exists once it
                 // has been performed, and consuming the values below orders them before the arrival signal.
                 float* c = (float*)((char*)P.C + acc_shift) + (size_t)m * P.ldc + n;
 #pragma unroll
                 for (int b = 0; b < CPL; ++b) atomic_returns += unsafeAtomicAdd(c + b, val[0][b]);
+                }
             } else if constexpr (EPI == EPI_STORE) {
                 if (P.bias) {
                     float bv[CPL];
@@ -302,9 +310,9 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
     }
     if constexpr (EPI == EPI_ATOMIC) asm volatile("" ::"v"(atomic_returns));   // every atomic above has returned
 
-    // bf16 finalisation of a split-K accumulator tile (more than 8 token rows): the workgroup that adds the
-    // last K-slice of this column tile converts the finished fp32 tile to bf16 once, so that the next stage's
-    // workgroups read half the bytes with plain cached loads instead of each converting the whole of t.
+    // bf16 finalisation of a split-K stage (more than 8 token rows): the workgroup whose K-slice of this column
+    // tile arrives last adds up all slices' partial tiles and writes the tile as bf16 once, so that the next
+    // stage's workgroups read half the bytes with plain cached loads instead of each converting the whole of t.
     if constexpr (EPI == EPI_ATOMIC) {
         if (tcnt) {
             __shared__ uint32_t s_last;
@@ -317,13 +325,28 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
             }
             __syncthreads();
             if (s_last) {
-                const float* src0 = (const float*)((const char*)P.C + acc_shift);
+                // add the K-slices of this column tile in slice order (deterministic), eight slots in flight per lane
+                const int slices = (P.K + P.KS - 1) / P.KS;
+                const size_t slot = (size_t)16 * MB * NC, step = (size_t)P.tiles_n * slot;
                 for (int it = tid; it < M * (NC / 4); it += 64 * NW) {
-                    const int m = it / (NC / 4), n = n0 + 4 * (it % (NC / 4));
-                    const float* src = src0 + (size_t)m * P.ldc + n;
-                    const uint2 a = ld_coherent_b64(src), b = ld_coherent_b64(src + 2);
-                    st_coherent_b64(P.Y + (size_t)m * P.ldy + n,
-                                    make_uint2(pack2(__uint_as_float(a.x), __uint_as_float(a.y)), pack2(__uint_as_float(b.x), __uint_as_float(b.y))));
+                    const int m = it / (NC / 4), c4 = 4 * (it % (NC / 4));
+                    const float* src = P.part + (size_t)(P.tile_begin + tn) * slot + (size_t)m * NC + c4;
+                    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+                    for (int sl0 = 0; sl0 < slices; sl0 += 8) {
+                        uint2 a[8], b[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int sl = sl0 + u < slices ? sl0 + u : slices - 1;
+                            a[u] = ld_coherent_b64(src + (size_t)sl * step); b[u] = ld_coherent_b64(src + (size_t)sl * step + 2);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (sl0 + u < slices) {
+                                s0 += __uint_as_float(a[u].x); s1 += __uint_as_float(a[u].y);
+                                s2 += __uint_as_float(b[u].x); s3 += __uint_as_float(b[u].y);
+                            }
+                    }
+                    st_coherent_b64(P.Y + (size_t)m * P.ldy + n0 + c4, make_uint2(pack2(s0, s1), pack2(s2, s3)));
                 }
             }
         }

@@ -48,7 +48,7 @@ static int pick_ks(int64_t K, int64_t tiles_n_total, int64_t M, int64_t want_til
 
 static void zero_prob(DProb& p) { memset(&p, 0, sizeof(p)); p.T = 1; }
 
-struct SplitK { const void* W; int64_t N; float* C; bf16_t* T16; };   // T16: bf16 copy of C made by the last K-slice (or NULL)
+struct SplitK { const void* W; int64_t N; float* C; bf16_t* T16; float* part; };   // T16: bf16 copy of C made by the last K-slice (or NULL)
 struct Final { const void* T; int64_t r; const void* V; int64_t N; const void* bias; void* Y; CacheDst cd; };   // T: fp32 or bf16 rank-space rows
 
 // t[M, ldc] += A[M, K] * W_i[K, N_i] for several weight matrices sharing A, split along K.
@@ -65,7 +65,7 @@ static void build_splitk(DStage& st, const void* A, int64_t lda, int64_t M, int6
         DProb& p = st.p[i]; zero_prob(p);
         p.W = (const bf16_t*)items[i].W; p.A = A; p.K = (int)K; p.lda = (int)lda; p.N = (int)items[i].N;
         p.C = items[i].C; p.ldc = (int)ldc; p.tiles_n = (int)(items[i].N / nc); p.KS = ks; p.tile_begin = tile;
-        p.Y = items[i].T16; p.ldy = (int)ldc; p.ctile_begin = *ctile_next; *ctile_next += p.tiles_n;
+        p.Y = items[i].T16; p.part = items[i].part; p.ldy = (int)ldc; p.ctile_begin = *ctile_next; *ctile_next += p.tiles_n;
         tile += p.tiles_n * tk;
     }
     st.total_tiles = tile;
@@ -122,25 +122,31 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
     bool all128 = true;
     for (int i = 0; i < nb; ++i) all128 = all128 && (sk_in[i].N % 128 == 0);
     const int c1 = pick_cpl(all128);
-    const bool t16 = fused && use_t16(M, R / (16 * c1));
+    // bf16 finalisation of t needs a slot of the workspace's partial-tile area for every tile of stage 1
+    const size_t slot1 = (size_t)(M > 16 ? 32 : 16) * 16 * c1 * 4;
+    bool t16 = fused && use_t16(M, R / (16 * c1)) && L.dec_part;
     float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* t16base = (bf16_t*)L.staging;                       // [M, R] bf16 (fused launches only)
     SplitK sk[kMaxProb]; Final fin[kMaxProb];
-    // the callers pass the column offset of each product inside t as the pointer value of C / T
-    for (int i = 0; i < nb; ++i) {
-        const size_t off = (size_t)(uintptr_t)sk_in[i].C;
-        sk[i] = sk_in[i]; sk[i].C = tbase + off; sk[i].T16 = t16 ? t16base + off : nullptr;
-    }
-    for (int i = 0; i < nf; ++i) {
-        const size_t off = (size_t)(uintptr_t)fin_in[i].T;
-        fin[i] = fin_in[i]; fin[i].T = t16 ? (const void*)(t16base + off) : (const void*)(tbase + off);
-    }
     DStage s1, s2;
-    int ctile = 0;
-    build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : env_int("LOWRANK_DECODE_TILES", 512), c1, &ctile);
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        // the callers pass the column offset of each product inside t as the pointer value of C / T
+        for (int i = 0; i < nb; ++i) {
+            const size_t off = (size_t)(uintptr_t)sk_in[i].C;
+            sk[i] = sk_in[i]; sk[i].C = tbase + off; sk[i].T16 = t16 ? t16base + off : nullptr; sk[i].part = t16 ? L.dec_part : nullptr;
+        }
+        for (int i = 0; i < nf; ++i) {
+            const size_t off = (size_t)(uintptr_t)fin_in[i].T;
+            fin[i] = fin_in[i]; fin[i].T = t16 ? (const void*)(t16base + off) : (const void*)(tbase + off);
+        }
+        int ctile = 0;
+        build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : env_int("LOWRANK_DECODE_TILES", 512), c1, &ctile);
+        if (!t16 || (size_t)s1.total_tiles * slot1 <= kDecPartBytes) break;
+        t16 = false;                                            // too many tiles for the area: accumulate with atomics instead
+    }
     const int c2 = build_final(s2, fin, nf, R, M);
     if (fused) {
-        FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, (uint32_t)(M * R), 0u, g_trace_buffer};
+        FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, t16 ? 0u : (uint32_t)(M * R), 0u, g_trace_buffer};   // t16: nothing is accumulated in place
         return decode_launch_fused2(fc, s1, s2, c1, c2, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, t16, s);
     }
     int st = fill_zero(tbase, (size_t)M * R * 4, s);
@@ -152,7 +158,7 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
 
 int decode_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
                   int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s) {
-    SplitK sk = {U, r, (float*)0, nullptr};
+    SplitK sk = {U, r, (float*)0, nullptr, nullptr};
     Final f = {(const void*)0, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
     return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, ws, ws_bytes, s);
 }
@@ -163,7 +169,7 @@ int decode_qkv(const void* x, const void* const* U, const void* const* V, const 
                void* ws, size_t ws_bytes, hipStream_t s) {
     SplitK sk[kMaxProb]; int nb = 0;
     for (int i = 0; i < n_proj; ++i)
-        if (base_of[i] == i) sk[nb++] = SplitK{U[i], r[i], (float*)(uintptr_t)t_off[i], nullptr};
+        if (base_of[i] == i) sk[nb++] = SplitK{U[i], r[i], (float*)(uintptr_t)t_off[i], nullptr, nullptr};
     Final f[kMaxProb];
     for (int i = 0; i < n_proj; ++i) {
         CacheDst cd = {nullptr, nullptr, 0, 1};
@@ -190,10 +196,19 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     const int64_t want = fused ? G : env_int("LOWRANK_DECODE_TILES", 512);
     DStage sa, sb, sc, sd;
     const int ca = pick_cpl(r_gu % 128 == 0 && r_d % 128 == 0), cc = ca;   // both split-K stages share one tile width
-    const bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca));
-    int ctile = 0;
-    SplitK a = {U_gu, r_gu, t, use16 ? t16 : nullptr};
-    build_splitk(sa, x, d, M, d, &a, 1, r_all, want, ca, &ctile);
+    const size_t slot = (size_t)(M > 16 ? 32 : 16) * 16 * ca * 4;      // bytes of one partial tile
+    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca)) && L.dec_part;
+    SplitK a, c;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        int ctile = 0;
+        a = SplitK{U_gu, r_gu, t, use16 ? t16 : nullptr, use16 ? L.dec_part : nullptr};
+        build_splitk(sa, x, d, M, d, &a, 1, r_all, want, ca, &ctile);
+        c = SplitK{U_d, r_d, t + r_gu, use16 ? t16 + r_gu : nullptr, use16 ? L.dec_part : nullptr};   // the two split-K stages take turns in the same slots
+        build_splitk(sc, h, ffn, M, ffn, &c, 1, r_all, want, cc, &ctile);
+        const int most = sa.total_tiles > sc.total_tiles ? sa.total_tiles : sc.total_tiles;
+        if (!use16 || (size_t)most * slot <= kDecPartBytes) break;
+        use16 = false;
+    }
     {   // gate/up: both products of a 64-column tile in one workgroup, full K
         sb.nprob = 1; sb.M = (int)M;
         DProb& p = sb.p[0]; zero_prob(p);
@@ -204,13 +219,11 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
         p.tiles_n = (int)(ffn / 64); p.KS = (int)r_g; p.tile_begin = 0;
         sb.total_tiles = p.tiles_n;
     }
-    SplitK c = {U_d, r_d, t + r_gu, use16 ? t16 + r_gu : nullptr};
-    build_splitk(sc, h, ffn, M, ffn, &c, 1, r_all, want, cc, &ctile);
     Final f = {use16 ? (const void*)(t16 + r_gu) : (const void*)(t + r_gu), r_d, V_d, d, b_d, out, {nullptr, nullptr, 0, 1}};
     const int cd = build_final(sd, &f, 1, r_all, M);
     if (fused) {
         FusedMlpArgs fa;
-        fa.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, (uint32_t)(M * r_all), 0u, g_trace_buffer};
+        fa.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, use16 ? 0u : (uint32_t)(M * r_all), 0u, g_trace_buffer};
         const DStage* src[4] = {&sa, &sb, &sc, &sd};
         DStageT<1>* dst[4] = {&fa.a, &fa.b, &fa.c, &fa.d};
         for (int i = 0; i < 4; ++i) { dst[i]->p[0] = src[i]->p[0]; dst[i]->nprob = 1; dst[i]->M = (int)M; dst[i]->total_tiles = src[i]->total_tiles; }
