@@ -54,6 +54,21 @@ __device__ __forceinline__ bf16x8_t frag_of(const uint4& v) {
 constexpr int DBK = 32;                 // k per stage
 constexpr int DSTAGES = 4;
 template <int BM, int BN> constexpr int dma_stage_bytes() { return BM * 64 + 32 * BN * 2; }
+
+// Where unit u (16 bytes = 8 columns) of row k of a B tile sits inside its LDS row of UR = BN/8 units, and the
+// inverse.  Power-of-two rows: XOR with 4 * (k & 3).  192-column tiles (24 units, 384 bytes = 1.5 times the
+// bank space, so rows k and k+2 would meet): rows with bit 1 of k set are rotated by 4 units.  Either way the
+// 4 rows x 2 column blocks that one half-wave of a transposing read touches fall into 8 different 32-byte bank groups.
+template <int BN> __device__ __forceinline__ int b_lds_pos(int k, int u) {
+    constexpr int UR = BN / 8;
+    if constexpr ((UR & (UR - 1)) == 0) return u ^ ((k & 3) << 2);
+    else { const int p = u + 4 * ((k >> 1) & 1); return p >= UR ? p - UR : p; }
+}
+template <int BN> __device__ __forceinline__ int b_unit_at(int k, int pos) {
+    constexpr int UR = BN / 8;
+    if constexpr ((UR & (UR - 1)) == 0) return pos ^ ((k & 3) << 2);
+    else { const int u = pos - 4 * ((k >> 1) & 1); return u < 0 ? u + UR : u; }
+}
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
@@ -88,7 +103,7 @@ __device__ __forceinline__ void frag_setup(FragAddr<BM, BN>& f) {
     for (int ni = 0; ni < NI; ++ni) {
         const int col = wn * (BN / 2) + ni * 32 + blk * 16 + 4 * (s & 3);
         const int u = col >> 3, half = (col >> 2) & 1;
-        f.b[ni] = (uint32_t)(BM * 64 + k * (BN * 2) + ((u ^ (q << 2)) * 16) + half * 8);
+        f.b[ni] = (uint32_t)(BM * 64 + k * (BN * 2) + b_lds_pos<BN>(k, u) * 16 + half * 8);   // k & 3 and bit 1 of k do not change with substep or half
     }
 }
 
@@ -219,8 +234,9 @@ __device__ __forceinline__ void stream_setup(Stream<BM, BN>& c, const bf16_t* A,
     }
 #pragma unroll
     for (int j = 0; j < NR; ++j) {
-        const int k = (wave * NR + j) * (64 / UR) + lane / UR, pos = lane % UR;
-        int col = (pos ^ ((k & 3) << 2)) * 8;
+        const int lin = (wave * NR + j) * 64 + lane;          // LDS unit of the tile this lane fills
+        const int k = lin / UR, pos = lin % UR;
+        int col = b_unit_at<BN>(k, pos) * 8;
         col = (n0 + col + 8 <= N) ? col : N - 8 - n0;     // columns past the end repeat the last unit; never stored
         c.vob[j] = (uint32_t)k * (uint32_t)N * 2u + (uint32_t)(col * 2);
     }
@@ -527,7 +543,8 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
     char* const wr = patch + li * 128 + lg * 8;                   // this lane's row of the patch when written
     const int wsw = (li >> 1) & 7;
 #pragma unroll
-    for (int pr = 0; pr < NI / 2; ++pr) {
+    for (int pr = 0; pr < (NI + 1) / 2; ++pr) {                   // pairs of 32-column blocks; the last one may be single
+        const int np2 = (2 * pr + 1 < NI) ? 2 : 1;                // column blocks in this pair
         uint2 bgp[2][4], bup[2][4];                               // bias of this lane's columns, bf16 pairs as loaded
 #pragma unroll
         for (int p2 = 0; p2 < 2; ++p2)
@@ -545,7 +562,7 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
                 }
         }
         const int gcol = n0 + wn * (BN / 2) + pr * 64 + runit * 8;   // first of the 8 columns this lane stores
-        const bool col_ok = gcol < N;
+        const bool col_ok = gcol < N && runit < 4 * np2;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const int r0 = m0 + wm * (BM / 2) + mi * 32;
@@ -566,7 +583,7 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
                     for (int cc = 0; cc < 3; ++cc) {
                         const int cs = c + cc < part1 ? c + cc : part1 - 1;      // a repeated slot is loaded but not added
 #pragma unroll
-                        for (int p2 = 0; p2 < 2; ++p2)
+                        for (int p2 = 0; p2 < np2; ++p2)
 #pragma unroll
                             for (int vg = 0; vg < 4; ++vg) {
                                 const float* src = parts + (size_t)cs * (BM * BN) + part_index<BM, BN>(wave, mi, pr * 2 + p2, vg, lane);
@@ -578,7 +595,7 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
                     for (int cc = 0; cc < 3; ++cc) {
                         const float w = c + cc < part1 ? 1.f : 0.f;
 #pragma unroll
-                        for (int p2 = 0; p2 < 2; ++p2)
+                        for (int p2 = 0; p2 < np2; ++p2)
 #pragma unroll
                             for (int vg = 0; vg < 4; ++vg) {
                                 psum[p2][vg][0] += w * __uint_as_float(raw[cc][p2][vg][0].x); psum[p2][vg][1] += w * __uint_as_float(raw[cc][p2][vg][0].y);
@@ -588,7 +605,7 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
                 }
             }
 #pragma unroll
-            for (int p2 = 0; p2 < 2; ++p2)
+            for (int p2 = 0; p2 < np2; ++p2)
 #pragma unroll
                 for (int vg = 0; vg < 4; ++vg) {
                     const int ni = pr * 2 + p2;
@@ -771,20 +788,24 @@ static int env_shape() { static int v = env_int("LOWRANK_PREFILL_SHAPE"); return
 static int env_gu() { static int v = env_int("LOWRANK_PREFILL_GU"); return v; }
 static int env_sk() { static int v = env_int("LOWRANK_PREFILL_SHAREK"); return v; }
 
-// Tile shape of a plain launch, from a two-line cost model fitted to measurements on this chip, in
-// units of "one 256 x 256 tile on one CU": the 256 x 256 kernel (one workgroup per CU) does one unit
-// per round; the 128 x 128 kernel needs 0.46 for its quarter-size tile when every tile has a CU to
-// itself, and 0.64 per round of two tiles per CU otherwise.  Big-N products with short K (the
-// reconstruction x V) go to 256 x 256, the rank-space products with few columns to 128 x 128.
-static bool want_256(const PArgs& a) {
-    long t256 = 0, t128 = 0;
+// Tile shape of a plain launch, from a small cost model fitted to measurements on this chip, in units of "one
+// 256 x 256 tile on one CU": the 256-row kernels (one workgroup per CU) take one unit per round for 256
+// columns and 0.75 for 192; the 128 x 128 kernel needs 0.46 for its quarter-size tile when every tile has a CU
+// to itself, and 0.64 per round of two tiles per CU otherwise.  Big-N products with short K (the
+// reconstruction x V) go to 256 x 256; the rank-space products (N = 384, 1536: multiples of 192 but poor
+// fits for 256) to 256 x 192, which wastes no matrix work on columns past N; small ones to 128 x 128.
+static int pick_tile(const PArgs& a) {
+    long t256 = 0, t192 = 0, t128 = 0;
     for (int i = 0; i < a.nprob; ++i) {
         t256 += (long)((a.M + 255) / 256) * ((a.p[i].N + 255) / 256);
+        t192 += (long)((a.M + 255) / 256) * ((a.p[i].N + 191) / 192);
         t128 += (long)((a.M + 127) / 128) * ((a.p[i].N + 127) / 128);
     }
     const double c256 = (double)((t256 + 255) / 256);
+    const double c192 = 0.75 * (double)((t192 + 255) / 256);
     const double c128 = t128 <= 256 ? 0.46 : 0.64 * (double)((t128 + 511) / 512);
-    return c256 <= c128;
+    if (c192 < c256 && c192 < c128) return 192;
+    return c256 <= c128 ? 256 : 128;
 }
 
 // A product with a very long K and so few 256 x 256 tiles that half the CUs would get none (h U_d of
@@ -812,11 +833,15 @@ int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
         case 1: return launch_persist<128, 128, PEPI_STORE, 2>(a, s, env_sk() == 1);
         case 2: return launch_persist<256, 128, PEPI_STORE, 1>(a, s);
         case 3: return launch_persist<128, 256, PEPI_STORE, 1>(a, s);
+        case 4: return launch_persist<256, 192, PEPI_STORE, 1>(a, s);
         default: break;
     }
     if (want_share_k(a)) return launch_persist<256, 256, PEPI_STORE, 1>(a, s, true);
-    if (want_256(a)) return launch_persist<256, 256, PEPI_STORE, 1>(a, s);
-    return launch_persist<128, 128, PEPI_STORE, 2>(a, s);
+    switch (pick_tile(a)) {
+        case 192: return launch_persist<256, 192, PEPI_STORE, 1>(a, s);
+        case 256: return launch_persist<256, 256, PEPI_STORE, 1>(a, s);
+        default: return launch_persist<128, 128, PEPI_STORE, 2>(a, s);
+    }
 }
 
 }  // namespace lr
