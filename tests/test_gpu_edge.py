@@ -336,3 +336,36 @@ def test_prefill_mlp_fast_path_with_bias(G, oracle, M):
     want = oracle.packed_mlp(t["x"].f64, t["U_gu"].f64, t["V_g"].f64, t["V_u"].f64, t["U_d"].f64, t["V_d"].f64,
                              t["b_g"].f64, t["b_u"].f64, t["b_d"].f64)
     assert max_rel_err(G.host64(out), want) <= TOL["bf16"]
+
+
+def _prefill_shapes():
+    """Seeded shapes for the MFMA prefill path: K in steps of 64, N in steps of 128, any M > 32; chosen so that
+    every tile kernel (128 x 128, 256 x 192, 256 x 256, ragged in both directions) and both k-step parities occur."""
+    rng = np.random.default_rng(2605)
+    shapes = [(33, 64, 128, 128), (257, 128, 256, 384), (1000, 192, 384, 1536), (2049, 64, 128, 4224),
+              (4100, 320, 256, 4096 + 128), (8192, 128, 128, 2048), (3000, 64, 128, 5248)]
+    for _ in range(9):
+        M = int(rng.integers(34, 2500))
+        d_in = 64 * int(rng.integers(1, 9))
+        r = 128 * int(rng.integers(1, 7))
+        d_out = 128 * int(rng.integers(1, 33))
+        shapes.append((M, d_in, r, d_out))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _prefill_shapes())
+def test_prefill_linear_shape_sweep(G, oracle, shape):
+    M, d_in, r, d_out = shape
+    rng = np.random.default_rng(M * 7 + d_out)
+    x = rand_t(rng, (M, d_in), "bf16")
+    U = rand_t(rng, (d_in, r), "bf16", d_in ** -0.5)
+    V = rand_t(rng, (r, d_out), "bf16", r ** -0.5)
+    b = rand_t(rng, (d_out,), "bf16")
+    assert G.B.lowrank_plan_name(G.B.LR_OP_LINEAR, M, d_in, r, d_out, G.B.LR_BF16, "prefill", 1) == "prefill_mfma"
+    y = G.run_linear(x, U, V, b, "prefill", "bf16")
+    rows = sorted(set([0, M // 2, M - 1] + [m for m in (127, 128, 255, 256, 511, 512, M - 129, M - 257) if 0 <= m < M] +
+                      list(rng.integers(0, M, size=40))))
+    want = oracle.linear(x.f64[rows], U.f64, V.f64, b.f64)
+    got = G.host64(y)
+    assert np.isfinite(got).all()                 # every element was written (the output starts as NaN)
+    assert max_rel_err(got[rows], want) <= TOL["bf16"]
