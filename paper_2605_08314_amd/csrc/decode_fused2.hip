@@ -1,4 +1,5 @@
 // Launcher of the fused two-stage decode kernel (lowrank_linear, lowrank_qkv).
+#include <stdlib.h>
 #include "decode_device.hpp"
 
 namespace lr {
@@ -41,6 +42,8 @@ int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& 
 int decode_resident_grid() {
     static int cached = 0;
     if (cached > 0) return cached;
+    const char* dry = getenv("LOWRANK_DECODE_DRYRUN");     // host-side tests of the plans: no device needed
+    if (dry && *dry && atoi(dry) != 0) return 256;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 0;

@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include "decode.hpp"
+#include "decode_ring.hpp"
 
 namespace lr {
 
@@ -111,6 +112,20 @@ static bool use_t16(int64_t M, int64_t col_tiles) {
     return M > 8 && col_tiles <= kTileCounters && env_int("LOWRANK_DECODE_T16", 1) != 0;
 }
 
+// Up to 16 token rows, at most four products per stage, 64-column tiles: the streaming kernel (factor bytes
+// through an LDS ring, requested across the stage barriers).  LOWRANK_DECODE_RING=0 keeps the older kernels.
+static bool ring_wanted(int64_t M, int cpl) {
+    return M <= 16 && cpl == 4 && env_int("LOWRANK_DECODE_RING", 0) != 0;
+}
+static int ring_rows(int64_t M) { int a = 1; while (a < M) a *= 2; return a; }
+static bool ring_stage(RStage& r, const DStage& st, int epi, int a_kind, bool finalise) {
+    if (st.nprob > kRingProbs) return false;
+    memset(&r, 0, sizeof(r));
+    for (int i = 0; i < st.nprob; ++i) r.p[i] = st.p[i];
+    r.nprob = st.nprob; r.total_tiles = st.total_tiles; r.epi = epi; r.a_kind = a_kind; r.finalise = finalise ? 1 : 0;
+    return true;
+}
+
 static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* sk_in, int nb, const Final* fin_in,
                          int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s) {
     const WsLayout L = ws_layout(ws, ws_bytes, M);
@@ -147,6 +162,14 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
     const int c2 = build_final(s2, fin, nf, R, M);
     if (fused) {
         FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, t16 ? 0u : (uint32_t)(M * R), 0u, g_trace_buffer};   // t16: nothing is accumulated in place
+        if (ring_wanted(M, c1) && c2 == 4) {
+            RingArgs ra;
+            ra.fc = fc; ra.nstages = 2; ra.M = (int)M; ra.a_rows = ring_rows(M);
+            const char* why = "";
+            if (ring_stage(ra.st[0], s1, EPI_ATOMIC, RA_BF16_PLAIN, t16) &&
+                ring_stage(ra.st[1], s2, EPI_STORE, t16 ? RA_BF16_PLAIN : RA_F32_COHERENT, false) && ring_args_ok(ra, G, &why))
+                return decode_launch_ring(ra, G, s);
+        }
         return decode_launch_fused2(fc, s1, s2, c1, c2, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, t16, s);
     }
     int st = fill_zero(tbase, (size_t)M * R * 4, s);
@@ -222,6 +245,17 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     Final f = {use16 ? (const void*)(t16 + r_gu) : (const void*)(t + r_gu), r_d, V_d, d, b_d, out, {nullptr, nullptr, 0, 1}};
     const int cd = build_final(sd, &f, 1, r_all, M);
     if (fused) {
+        if (ring_wanted(M, ca) && cd == 4) {
+            RingArgs ra;
+            ra.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, use16 ? 0u : (uint32_t)(M * r_all), 0u, g_trace_buffer};
+            ra.nstages = 4; ra.M = (int)M; ra.a_rows = ring_rows(M);
+            const int act = use16 ? RA_BF16_PLAIN : RA_F32_COHERENT;
+            const char* why = "";
+            if (ring_stage(ra.st[0], sa, EPI_ATOMIC, RA_BF16_PLAIN, use16) && ring_stage(ra.st[1], sb, EPI_GATEUP, act, false) &&
+                ring_stage(ra.st[2], sc, EPI_ATOMIC, RA_BF16_COHERENT, use16) && ring_stage(ra.st[3], sd, EPI_STORE, act, false) &&
+                ring_args_ok(ra, G, &why))
+                return decode_launch_ring(ra, G, s);
+        }
         FusedMlpArgs fa;
         fa.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, use16 ? 0u : (uint32_t)(M * r_all), 0u, g_trace_buffer};
         const DStage* src[4] = {&sa, &sb, &sc, &sd};

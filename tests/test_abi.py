@@ -71,3 +71,37 @@ def test_plan_names(B):
     assert B.lowrank_plan_name(B.LR_OP_QKV, 3, 37, 5, 19, B.LR_BF16, "decode") == "generic"
     assert B.lowrank_plan_name(B.LR_OP_LINEAR, 16, 512, 128, 512, B.LR_F32, "decode") == "generic"
     assert B.lowrank_plan_name(B.LR_OP_LINEAR, 16, 4096, 384, 4096, B.LR_BF16, "decode", aligned=False) == "generic"
+
+
+def _dry_lib(B):
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in ("lowrank_linear", "lowrank_qkv", "lowrank_packed_mlp", "lowrank_workspace_bytes"):
+        getattr(lib, n).argtypes = getattr(B._lib, n).argtypes
+        getattr(lib, n).restype = getattr(B._lib, n).restype
+    lib.lowrank_last_error.restype = ctypes.c_char_p
+    return lib
+
+
+@pytest.mark.parametrize("shape", [
+    # (M, d, ffn, r_g, r_u, r_d): the benchmark layer, a ragged K split, unequal ranks, 9..16 rows
+    (1, 4096, 11008, 768, 768, 768), (8, 4096, 11008, 768, 768, 768), (3, 1024, 2816, 192, 320, 128),
+    (16, 4096, 11008, 768, 768, 768), (11, 2048, 5632, 256, 384, 128), (5, 4096, 14336, 1024, 1024, 1024),
+])
+def test_decode_plan_walk_stays_inside_the_factors(B, monkeypatch, shape):
+    """Host side of the streaming decode kernel (LOWRANK_DECODE_RING=1): with LOWRANK_DECODE_DRYRUN the planner
+    builds the launch descriptors, walks every producer / consumer pair's sequence of factor blocks on the host
+    (LOWRANK_DECODE_CHECK: inside the matrices, each block of each tile exactly once, LDS layout fits) and launches
+    nothing.  No pointer is dereferenced."""
+    monkeypatch.setenv("LOWRANK_DECODE_RING", "1")        # the streaming kernel is opt-in
+    monkeypatch.setenv("LOWRANK_DECODE_DRYRUN", "1")
+    monkeypatch.setenv("LOWRANK_DECODE_CHECK", "1")
+    lib = _dry_lib(B)
+    M, d, ffn, r_g, r_u, r_d = shape
+    wsb = lib.lowrank_workspace_bytes(B.LR_OP_PACKED_MLP, M, d, r_g + r_u + r_d, ffn, B.LR_BF16, 0)
+    assert wsb > 0
+    fake = [0x10000000 * (i + 1) for i in range(10)]
+    rc = lib.lowrank_packed_mlp(fake[0], fake[1], fake[2], fake[3], fake[4], fake[5], None, None, None, fake[6],
+                                M, d, ffn, r_g, r_u, r_d, B.LR_BF16, 0, fake[7], wsb, None)
+    assert rc == 0, lib.lowrank_last_error()
+    rc = lib.lowrank_linear(fake[0], fake[1], fake[2], None, fake[6], M, d, r_g, ffn, B.LR_BF16, 0, fake[7], wsb, None)
+    assert rc == 0, lib.lowrank_last_error()

@@ -369,3 +369,26 @@ def test_prefill_linear_shape_sweep(G, oracle, shape):
     got = G.host64(y)
     assert np.isfinite(got).all()                 # every element was written (the output starts as NaN)
     assert max_rel_err(got[rows], want) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("M", [1, 3, 8, 11, 16])
+def test_streaming_decode_kernel_opt_in(G, oracle, monkeypatch, M):
+    """LOWRANK_DECODE_RING=1 routes decode calls of up to 16 rows through the streaming kernel (factor blocks through
+    LDS rings, requested across the stage barriers).  Same bar as the default kernels; run twice on one workspace
+    (epoch parity, counters), with the host-side walk check on."""
+    monkeypatch.setenv("LOWRANK_DECODE_RING", "1")
+    monkeypatch.setenv("LOWRANK_DECODE_CHECK", "1")
+    w = synth.mlp_layer(M, d=1024, ffn=2816, r_g=192, r_u=320, r_d=128, seed=4242 + M, dtype="bf16", with_bias=True)
+    t = w.t
+    want = oracle.packed_mlp(t["x"].f64, t["U_gu"].f64, t["V_g"].f64, t["V_u"].f64, t["U_d"].f64, t["V_d"].f64,
+                             t["b_g"].f64, t["b_u"].f64, t["b_d"].f64)
+    for _ in range(2):
+        out = G.run_mlp(w, "decode")
+        assert max_rel_err(G.host64(out), want) <= TOL["bf16"]
+    rng = np.random.default_rng(77 + M)
+    x = rand_t(rng, (M, 1024), "bf16")
+    U = rand_t(rng, (1024, 192), "bf16", 1024 ** -0.5)
+    V = rand_t(rng, (192, 2048), "bf16", 192 ** -0.5)
+    b = rand_t(rng, (2048,), "bf16")
+    y = G.run_linear(x, U, V, b, "decode", "bf16")
+    assert max_rel_err(G.host64(y), oracle.linear(x.f64, U.f64, V.f64, b.f64)) <= TOL["bf16"]
