@@ -151,6 +151,27 @@ def run_decode_attention(torch, B, gen, cases=((1, 512), (1, 2048), (1, 8192), (
     return rows
 
 
+def run_prefill_attention(torch, B, gen, S):
+    """Causal attention of S new tokens over the cache they were just written to (rotary embedding on q and k):
+    time and TFLOP/s; algorithmic flops = 4 * head_dim per visible (query, key) pair and head."""
+    bf = torch.bfloat16
+    q = torch.randn((S, D), device="cuda", dtype=bf, generator=gen)
+    kc = torch.randn((1, S, HEADS, HEAD_DIM), device="cuda", dtype=bf, generator=gen)
+    vc = torch.randn((1, S, HEADS, HEAD_DIM), device="cuda", dtype=bf, generator=gen)
+    out = torch.empty_like(q)
+    pos0 = torch.zeros((1,), device="cuda", dtype=torch.int32)
+
+    def call():
+        # every call rotates the new key rows again; the values drift but the work is the same
+        B.lowrank_prefill_attention(q, kc, vc, pos0, S, out, HEAD_DIM ** -0.5, 10000.0)
+
+    ms = time_region(torch, call, 5, 2)
+    fl = 4.0 * HEAD_DIM * HEADS * (S * (S + 1) / 2)
+    tf = fl / (ms * 1e-3) / 1e12
+    return {"workload": f"S={S} new tokens, {HEADS} heads x {HEAD_DIM}, causal, RoPE", "ms": round(ms, 3),
+            "TFLOPs": round(tf, 1), "frac_mfma_bf16_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,7 +205,8 @@ def main():
         print(json.dumps({"attention_only": True, "decode_attention": run_decode_attention(torch, B, gen)}))
         return
     if args.prefill_only:
-        print(json.dumps({"prefill_only": True, "prefill": run_prefill(torch, B, gen, Layer(torch, gen=gen), args.prefill_rows)}))
+        print(json.dumps({"prefill_only": True, "prefill": run_prefill(torch, B, gen, Layer(torch, gen=gen), args.prefill_rows),
+                          "prefill_attention": run_prefill_attention(torch, B, gen, args.prefill_rows)}))
         return
     layers = [Layer(torch, gen=gen) for _ in range(L)]
     S_max = 64
@@ -306,6 +328,7 @@ def main():
         out["decode_ops"] = table
 
         out["prefill"] = run_prefill(torch, B, gen, layers[0], args.prefill_rows)
+        out["prefill_attention"] = run_prefill_attention(torch, B, gen, args.prefill_rows)
         out["decode_attention"] = run_decode_attention(torch, B, gen)
 
         # ---- CPU baseline: the oracle as it stands, on this machine's host cores, bounded sample

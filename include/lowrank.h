@@ -154,6 +154,19 @@ int lowrank_decode_attention(const void *q, const lr_kv_target *kv, void *out, f
                              int dtype, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Prefill attention over the dense KV cache: the same operation as lowrank_decode_attention, steps 1 and 2
+ * word for word (causal attention of the new tokens' queries over cache positions [0, pos[b] + s], new key rows
+ * rotated in place when rope_base > 0), organised for the hundreds to thousands of new tokens per sequence of
+ * a prefill pass (Section 3.1, second paragraph; Section 4): tiles of 128 query rows x 64 keys on the bf16
+ * matrix cores with an online softmax, so that the work is bound by arithmetic, not by re-reading the cache per
+ * row.  Arguments as for lowrank_decode_attention; no workspace.  Supported: dtype LR_BF16, head_dim 128,
+ * 16-byte aligned q / out / caches; anything else returns LR_ERR_UNSUPPORTED (lowrank_decode_attention accepts
+ * every shape).  out must not alias q.
+ */
+int lowrank_prefill_attention(const void *q, const lr_kv_target *kv, void *out, float scale, float rope_base,
+                              int dtype, void *stream);
+
+/*
  * Offline prepack (Section 3.1, third paragraph; Figure 3): concatenate n (1..8) factors
  * U_list[i][d_in, r_list[i]] along the rank axis into U_packed[d_in, sum r_list].  U_list and
  * r_list are HOST arrays; the matrices are device memory.  Pure data movement: bit-exact.

@@ -46,6 +46,8 @@ _lib.lowrank_packed_mlp.argtypes = [_vp] * 10 + [_i64] * 6 + [_int, _int, _vp, _
 _lib.lowrank_packed_mlp.restype = _int
 _lib.lowrank_decode_attention.argtypes = [_vp, ctypes.POINTER(lr_kv_target), _vp, ctypes.c_float, ctypes.c_float, _int, _vp, _sz, _vp]
 _lib.lowrank_decode_attention.restype = _int
+_lib.lowrank_prefill_attention.argtypes = [_vp, ctypes.POINTER(lr_kv_target), _vp, ctypes.c_float, ctypes.c_float, _int, _vp]
+_lib.lowrank_prefill_attention.restype = _int
 _lib.lowrank_pack_concat.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_i64), _int, _i64, _int, _vp, _vp]
 _lib.lowrank_pack_concat.restype = _int
 _lib.lowrank_workspace_bytes.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int]
@@ -195,6 +197,16 @@ def lowrank_decode_attention(q, k_cache, v_cache, pos, tokens_per_seq: int, out,
     kvs = lr_kv_target(_ptr(k_cache), _ptr(v_cache), _ptr(pos), B, S_max, H, E, tokens_per_seq, 0, 0)
     _check(_lib.lowrank_decode_attention(_ptr(q), ctypes.byref(kvs), _ptr(out), scale, rope_base, _dtype_code(q),
                                          _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def lowrank_prefill_attention(q, k_cache, v_cache, pos, tokens_per_seq: int, out, scale: float, rope_base: float,
+                              stream=None) -> None:
+    """Same operation and shapes as ``lowrank_decode_attention``, on the matrix cores (bf16, head_dim 128); no workspace."""
+    B, S_max, H, E = k_cache.shape
+    assert v_cache.shape == k_cache.shape and pos.dtype == torch.int32
+    assert q.shape == (B * tokens_per_seq, H * E) and out.shape == q.shape
+    kvs = lr_kv_target(_ptr(k_cache), _ptr(v_cache), _ptr(pos), B, S_max, H, E, tokens_per_seq, 0, 0)
+    _check(_lib.lowrank_prefill_attention(_ptr(q), ctypes.byref(kvs), _ptr(out), scale, rope_base, _dtype_code(q), _stream(stream)))
 
 
 def lowrank_pack_concat(U_list: Sequence[torch.Tensor], U_packed: torch.Tensor, stream=None) -> None:

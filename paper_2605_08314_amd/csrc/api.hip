@@ -281,6 +281,24 @@ int lowrank_decode_attention(const void* q, const lr_kv_target* kv, void* out, f
     return attn_decode(q, kv, out, scale, rope_base, dtype, attn_fast_ok(dtype, E, al), workspace, (hipStream_t)stream);
 }
 
+int lowrank_prefill_attention(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base,
+                              int dtype, void* stream) {
+    if (dtype != LR_F32 && dtype != LR_BF16) { set_error("unknown dtype %d", dtype); return LR_ERR_DTYPE; }
+    if (!kv) { set_error("kv is NULL"); return LR_ERR_NULL; }
+    if (kv->B < 0 || kv->tokens_per_seq < 1 || kv->S_max < kv->tokens_per_seq || kv->n_heads < 1 || kv->head_dim < 1) {
+        set_error("kv: bad cache shape"); return LR_ERR_SHAPE; }
+    const int64_t M = kv->B * kv->tokens_per_seq, H = kv->n_heads, E = kv->head_dim;
+    if (M >= (1ll << 24) || H * E >= (1ll << 24) || kv->S_max >= (1ll << 30)) { set_error("size out of range"); return LR_ERR_SHAPE; }
+    if (M == 0) return LR_OK;
+    if (!q || !out || !kv->k_cache || !kv->v_cache || !kv->pos) { set_error("NULL operand"); return LR_ERR_NULL; }
+    const bool al = aligned16(q) && aligned16(out) && aligned16(kv->k_cache) && aligned16(kv->v_cache);
+    if (!attn_prefill_ok(dtype, E, al)) {
+        set_error("prefill attention: needs bf16, head_dim 128 and 16-byte aligned operands (use lowrank_decode_attention)");
+        return LR_ERR_UNSUPPORTED;
+    }
+    return attn_prefill(q, kv, out, scale, rope_base, (hipStream_t)stream);
+}
+
 int lowrank_pack_concat(const void* const* U_list, const int64_t* r_list, int n, int64_t d_in,
                         int dtype, void* U_packed, void* stream) {
     if (n < 1 || n > 8) { set_error("n must be 1..8"); return LR_ERR_SHAPE; }

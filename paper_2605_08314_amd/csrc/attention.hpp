@@ -20,4 +20,8 @@ bool attn_fast_ok(int dtype, int64_t E, bool aligned);
 int attn_decode(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base, int dtype,
                 bool fast, void* ws, hipStream_t s);
 
+// Prefill attention (attention_prefill.hip): bf16, head_dim 128, 16-byte aligned operands.
+bool attn_prefill_ok(int dtype, int64_t E, bool aligned);
+int attn_prefill(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base, hipStream_t s);
+
 }  // namespace lr

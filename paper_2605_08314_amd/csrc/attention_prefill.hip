@@ -1,0 +1,312 @@
+// Prefill attention over the dense KV cache (paper Section 3.1, attention paragraph: the present tokens' K/V go
+// to a standard dense cache [batch, position, head, head_dim]; Section 4: RoPE on q and k): causal softmax
+// attention of thousands of new tokens per sequence on the matrix cores, bf16, head_dim 128.
+// Same operation as the decode-attention kernels (token s of sequence b sees cache positions [0, pos[b] + s]),
+// organised for compute instead of for streaming:
+//
+//   k_rope_new_keys   rotates the new key rows in place in the cache (the projection call stores them raw).
+//   k_attn_prefill    one workgroup (4 waves) per (128 query rows, head, sequence); a wave owns 32 query rows and
+//                     walks the visible keys 64 at a time.  Everything is computed transposed, so that a lane owns
+//                     ONE query row throughout and every softmax statistic is a per-lane scalar:
+//                       S^T[key, row] = K Q^T      A = K rows from LDS (16-byte reads), B = the wave's rotated queries
+//                                                  (registers, loaded once), v_mfma_f32_32x32x16_bf16
+//                       online softmax             lane (row l % 32, half l / 32) holds 32 of the 64 scores of its row
+//                       O^T[e, row] += V^T P^T     A = V^T through the transposing LDS read ds_read_b64_tr_b16,
+//                                                  B = the probabilities straight from the score registers: the
+//                                                  accumulator layout hands a lane keys {8a + 4h .. +3}, so one
+//                                                  16-key MFMA step takes keys {16a' + 4h ..+3, 16a' + 8 + 4h ..+3}
+//                                                  and the V^T operand is read in the same order.
+//                     K and V tiles (64 x 128) are double-buffered in LDS, rows padded to 272 bytes.
+#include "attention.hpp"
+
+namespace lr {
+
+typedef __bf16 pbf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 pbf16x2_t __attribute__((ext_vector_type(2)));
+typedef float pf32x2_t __attribute__((ext_vector_type(2)));
+typedef float pf32x16_t __attribute__((ext_vector_type(16)));
+typedef short ps16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) ps16x4_t lds_ps16x4_t;
+
+struct PAttnArgs {
+    const bf16_t* q; bf16_t* k_cache; const bf16_t* v_cache; const int32_t* pos; bf16_t* out;
+    int B, T, H, S_max;
+    int ldq;                 // elements between query rows (H * 128)
+    float scale_log2e;       // softmax scale * log2(e)
+    double rope_base;        // <= 0: no rotation
+};
+
+constexpr int PA_E = 128, PA_BQ = 128, PA_BK = 64;
+constexpr int PA_ROW = 272;                              // bytes per K / V row in LDS (256 + 16: rows start in different banks)
+constexpr int PA_TILE = PA_BK * PA_ROW;                  // 17408
+
+__device__ __forceinline__ uint32_t pa_pack2(float lo, float hi) {
+    union { pbf16x2_t v; uint32_t u; } x;
+    x.v = __builtin_convertvector(pf32x2_t{lo, hi}, pbf16x2_t);
+    return x.u;
+}
+__device__ __forceinline__ pbf16x8_t pa_frag(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    union { uint32_t u[4]; pbf16x8_t v; } x;
+    x.u[0] = a; x.u[1] = b; x.u[2] = c; x.u[3] = d;
+    return x.v;
+}
+
+// cos / sin of position * base^(-2i/128): angle and range reduction in fp64, the functions in fp32 (the same
+// arithmetic as the decode path, so a key rotated here equals a key rotated there bit for bit)
+__device__ __forceinline__ void pa_cos_sin(long long p, double theta, float& c, float& sn) {
+    const double ang = (double)p * theta;
+    const double k = rint(ang * 0.15915494309189535);
+    const double red = fma(-k, 1.2246467991473532e-16 * 2.0, fma(-k, 6.283185307179586, ang));
+    sincosf((float)red, &sn, &c);
+}
+
+__global__ void __launch_bounds__(256) k_rope_new_keys(PAttnArgs a) {
+    const long long total = (long long)a.B * a.T * a.H * 64;
+    for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long long)gridDim.x * 256) {
+        const int i = (int)(idx & 63);
+        const int h = (int)((idx >> 6) % a.H);
+        const long long r = (idx >> 6) / a.H;
+        const int b = (int)(r / a.T), s = (int)(r - (long long)b * a.T);
+        const long long p = (long long)a.pos[b] + s;
+        if (p < 0 || p >= a.S_max) continue;
+        const double theta = exp2(-2.0 * (double)i / 128.0 * log2(a.rope_base));
+        float c, sn;
+        pa_cos_sin(p, theta, c, sn);
+        bf16_t* k = a.k_cache + (((size_t)b * a.S_max + (size_t)p) * a.H + h) * PA_E + i;
+        const double klo = (double)bf16_to_f32(k[0]), khi = (double)bf16_to_f32(k[64]);
+        k[0] = f32_to_bf16((float)(klo * (double)c - khi * (double)sn));
+        k[64] = f32_to_bf16((float)(khi * (double)c + klo * (double)sn));
+    }
+}
+
+__global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
+    __shared__ __attribute__((aligned(16))) char lds[4 * PA_TILE];       // K0 | V0 | K1 | V1
+    __shared__ double s_theta[64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, hh = lane >> 5;
+    const int nqb = (a.T + PA_BQ - 1) / PA_BQ;
+    // long blocks first: the last query block of a sequence sees the most keys
+    const int qb = nqb - 1 - (int)(blockIdx.x % nqb);
+    const int head = (int)((blockIdx.x / nqb) % a.H);
+    const int b = (int)(blockIdx.x / ((unsigned)nqb * a.H));
+    const int s0 = qb * PA_BQ;
+    const long long pos_b = a.pos[b];
+    // visible keys of the block: [0, n_keys)
+    long long nk = pos_b + (s0 + PA_BQ < a.T ? s0 + PA_BQ : a.T);
+    if (nk > a.S_max) nk = a.S_max;
+    if (nk < 0) nk = 0;
+    const int n_keys = (int)nk;
+    const int nkb = (n_keys + PA_BK - 1) / PA_BK;
+
+    if (tid < 64) s_theta[tid] = a.rope_base > 0.0 ? exp2(-2.0 * (double)tid / 128.0 * log2(a.rope_base)) : 0.0;
+    __syncthreads();
+
+    // ---- this lane's query row, rotated, as the B operand of S^T = K Q^T: step ks holds e = 16 ks + 8 hh .. + 7 ----
+    const int s_row = s0 + wave * 32 + li;                     // token index inside the sequence
+    const bool row_ok = s_row < a.T;
+    const long long p_row = pos_b + (row_ok ? s_row : a.T - 1);  // position of the row (rows past T repeat the last one; never stored)
+    pbf16x8_t qf[8];
+    {
+        const bf16_t* qrow = a.q + ((size_t)b * a.T + (size_t)(row_ok ? s_row : a.T - 1)) * a.ldq + (size_t)head * PA_E + 8 * hh;
+        uint4 raw[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) raw[ks] = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
+        if (a.rope_base > 0.0) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const uint32_t lo[4] = {raw[ks].x, raw[ks].y, raw[ks].z, raw[ks].w};
+                const uint32_t hi[4] = {raw[ks + 4].x, raw[ks + 4].y, raw[ks + 4].z, raw[ks + 4].w};
+                uint32_t olo[4], ohi[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    float rl[2], rh[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int i = 16 * ks + 8 * hh + 2 * w + t;        // pair (i, i + 64)
+                        const float ql = __uint_as_float(t ? (lo[w] & 0xffff0000u) : (lo[w] << 16));
+                        const float qh = __uint_as_float(t ? (hi[w] & 0xffff0000u) : (hi[w] << 16));
+                        float c, sn;
+                        pa_cos_sin(p_row, s_theta[i], c, sn);
+                        rl[t] = (float)((double)ql * (double)c - (double)qh * (double)sn);
+                        rh[t] = (float)((double)qh * (double)c + (double)ql * (double)sn);
+                    }
+                    olo[w] = pa_pack2(rl[0], rl[1]);
+                    ohi[w] = pa_pack2(rh[0], rh[1]);
+                }
+                qf[ks] = pa_frag(olo[0], olo[1], olo[2], olo[3]);
+                qf[ks + 4] = pa_frag(ohi[0], ohi[1], ohi[2], ohi[3]);
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) qf[ks] = pa_frag(raw[ks].x, raw[ks].y, raw[ks].z, raw[ks].w);
+        }
+    }
+
+    // ---- K / V tile loads: thread t moves 16 bytes of row t / 16 + 16 * pass, piece t % 16 ----
+    const size_t row_stride = (size_t)a.H * PA_E;                          // elements between cache positions
+    const bf16_t* kbase = a.k_cache + ((size_t)b * a.S_max * a.H + head) * PA_E + (size_t)(tid & 15) * 8;
+    const bf16_t* vbase = a.v_cache + ((size_t)b * a.S_max * a.H + head) * PA_E + (size_t)(tid & 15) * 8;
+    const int lrow = tid >> 4;
+    const uint32_t lds_off = (uint32_t)lrow * PA_ROW + (uint32_t)(tid & 15) * 16;
+    uint4 kreg[4], vreg[4];
+    auto load_tile = [&](int kb) {
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps) {
+            int key = kb * PA_BK + lrow + 16 * ps;
+            key = key < n_keys ? key : n_keys - 1;                         // clamped rows are masked below
+            kreg[ps] = *reinterpret_cast<const uint4*>(kbase + (size_t)key * row_stride);
+            vreg[ps] = *reinterpret_cast<const uint4*>(vbase + (size_t)key * row_stride);
+        }
+    };
+    auto store_tile = [&](int buf) {
+        char* kd = lds + buf * 2 * PA_TILE + lds_off;
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps) {
+            *reinterpret_cast<uint4*>(kd + ps * 16 * PA_ROW) = kreg[ps];
+            *reinterpret_cast<uint4*>(kd + PA_TILE + ps * 16 * PA_ROW) = vreg[ps];
+        }
+    };
+
+    pf32x16_t acc_o[4];
+#pragma unroll
+    for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc_o[eb][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    if (nkb > 0) { load_tile(0); store_tile(0); }
+    __syncthreads();
+
+    // this lane's fixed LDS offsets
+    const uint32_t k_off = (uint32_t)li * PA_ROW + (uint32_t)hh * 16;                        // + kbk * 32 * PA_ROW + ks * 32
+    // transposing read of V: inside a group of 16 lanes, source lane s hands in key row s / 4 and columns 4 (s % 4)..;
+    // the group (lane / 16) & 1 covers columns 16 .. 31 of the 32-column block, the half hh selects the keys
+    const uint32_t v_off = (uint32_t)(4 * hh + ((lane & 15) >> 2)) * PA_ROW + (uint32_t)(((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+
+    for (int kb = 0; kb < nkb; ++kb) {
+        const int buf = kb & 1;
+        if (kb + 1 < nkb) load_tile(kb + 1);
+        const char* kt = lds + buf * 2 * PA_TILE;
+        const char* vt = kt + PA_TILE;
+
+        // S^T = K Q^T for the 64 keys of the tile: two 32-key blocks
+        pf32x16_t acc_s[2];
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc_s[kbk][i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const uint4 kv4 = *reinterpret_cast<const uint4*>(kt + k_off + kbk * 32 * PA_ROW + ks * 32);
+                acc_s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_frag(kv4.x, kv4.y, kv4.z, kv4.w), qf[ks], acc_s[kbk], 0, 0, 0);
+            }
+        }
+
+        // scores of this lane: key = 64 kb + 32 kbk + 8 (i / 4) + 4 hh + i % 4
+        const int key0 = kb * PA_BK + 4 * hh;
+        const bool need_mask = (long long)(kb * PA_BK + PA_BK - 1) > pos_b + s0 + wave * 32 || kb * PA_BK + PA_BK > n_keys;
+        float m_blk = -INFINITY;
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float sv = acc_s[kbk][i] * a.scale_log2e;
+                if (need_mask) {
+                    const int key = key0 + 32 * kbk + 8 * (i >> 2) + (i & 3);
+                    if ((long long)key > p_row || key >= n_keys) sv = -INFINITY;
+                }
+                acc_s[kbk][i] = sv;
+                m_blk = fmaxf(m_blk, sv);
+            }
+        m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
+        const float m_new = fmaxf(m_run, m_blk);
+        // a row that has seen no key yet keeps m = -inf; exp2(-inf - (-inf)) would be NaN
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = exp2f(m_run - m_use);
+        float l_blk = 0.f;
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float pv = exp2f(acc_s[kbk][i] - m_use);
+                acc_s[kbk][i] = pv;
+                l_blk += pv;
+            }
+        l_run = l_run * alpha + l_blk;
+        m_run = m_new;
+        if (alpha != 1.f) {
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc_o[eb][i] *= alpha;
+        }
+
+        // O^T += V^T P^T, 16 keys per step: step a2 = 2 kbk + j takes score groups i / 4 = 2 j and 2 j + 1 of block kbk
+#pragma unroll
+        for (int a2 = 0; a2 < 4; ++a2) {
+            const int kbk = a2 >> 1, j = a2 & 1;
+            const pf32x16_t& sv = acc_s[kbk];
+            const pbf16x8_t pf = pa_frag(pa_pack2(sv[8 * j + 0], sv[8 * j + 1]), pa_pack2(sv[8 * j + 2], sv[8 * j + 3]),
+                                         pa_pack2(sv[8 * j + 4], sv[8 * j + 5]), pa_pack2(sv[8 * j + 6], sv[8 * j + 7]));
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb) {
+                union { struct { ps16x4_t lo, hi; } h; pbf16x8_t v; } x;
+                const char* vp = vt + v_off + (uint32_t)(16 * a2) * PA_ROW + eb * 64;
+                x.h.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp));
+                x.h.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp + 8 * PA_ROW));
+                acc_o[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, pf, acc_o[eb], 0, 0, 0);
+            }
+        }
+
+        if (kb + 1 < nkb) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- normalise, transpose through LDS (the tiles are no longer needed), store whole rows ----
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    char* stage = lds + wave * (32 * PA_ROW);                               // 32 rows x 272 bytes per wave
+#pragma unroll
+    for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const int e = eb * 32 + 8 * g4 + 4 * hh;
+            const uint2 o = make_uint2(pa_pack2(acc_o[eb][4 * g4 + 0] * inv, acc_o[eb][4 * g4 + 1] * inv),
+                                       pa_pack2(acc_o[eb][4 * g4 + 2] * inv, acc_o[eb][4 * g4 + 3] * inv));
+            *reinterpret_cast<uint2*>(stage + li * PA_ROW + e * 2) = o;
+        }
+    // LDS traffic of a wave completes in order; the rows below belong to this wave only
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int ps = 0; ps < 8; ++ps) {
+        const int r = 4 * ps + (lane >> 4), c16 = lane & 15;
+        const int s_out = s0 + wave * 32 + r;
+        const uint4 o = *reinterpret_cast<const uint4*>(stage + r * PA_ROW + c16 * 16);
+        if (s_out < a.T)
+            *reinterpret_cast<uint4*>(a.out + ((size_t)b * a.T + (size_t)s_out) * a.ldq + (size_t)head * PA_E + c16 * 8) = o;
+    }
+}
+
+bool attn_prefill_ok(int dtype, int64_t E, bool aligned) { return dtype == LR_BF16 && aligned && E == 128; }
+
+int attn_prefill(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base, hipStream_t s) {
+    PAttnArgs a;
+    a.q = (const bf16_t*)q; a.k_cache = (bf16_t*)kv->k_cache; a.v_cache = (const bf16_t*)kv->v_cache; a.pos = kv->pos;
+    a.out = (bf16_t*)out;
+    a.B = (int)kv->B; a.T = (int)kv->tokens_per_seq; a.H = (int)kv->n_heads; a.S_max = (int)kv->S_max;
+    a.ldq = a.H * PA_E;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.rope_base = (double)rope_base;
+    if (a.rope_base > 0.0) {
+        const long long pairs = (long long)a.B * a.T * a.H * 64;
+        const unsigned pg = (unsigned)((pairs + 255) / 256 < 8192 ? (pairs + 255) / 256 : 8192);
+        hipLaunchKernelGGL(k_rope_new_keys, dim3(pg), dim3(256), 0, s, a);
+    }
+    const long long nqb = (a.T + PA_BQ - 1) / PA_BQ;
+    const long long grid = nqb * a.H * a.B;
+    if (grid >= (1ll << 31)) { set_error("prefill attention: too many blocks"); return LR_ERR_SHAPE; }
+    hipLaunchKernelGGL(k_attn_prefill, dim3((unsigned)grid), dim3(256), 0, s, a);
+    return launch_status("prefill attention");
+}
+
+}  // namespace lr

@@ -135,3 +135,67 @@ def test_attention_error_codes(G):
     with pytest.raises(B.LowrankError):                                            # workspace too small
         B.lowrank_decode_attention(q, kc, kc.clone(), pos, 1, torch.empty_like(q), 1.0, 0.0, ws[:256])
     assert B.lowrank_workspace_bytes(B.LR_OP_DECODE_ATTENTION, 1, 8, 3, 0, B.LR_BF16, "decode") == 0   # 8 % 3 != 0
+
+
+PREFILL_CASES = [  # (B, T, H, S_max, positions): bf16, head_dim 128 -- the matrix-core prefill kernel
+    (1, 1, 2, 8, [0]),                       # a single token: sees only itself
+    (1, 65, 2, 80, [0]),                     # one partial query block, keys cross one tile border
+    (1, 128, 1, 128, [0]),                   # exactly one query block
+    (2, 200, 2, 300, [0, 37]),               # two query blocks, a ragged one; a history of 37 positions
+    (3, 130, 3, 400, [5, 0, 200]),           # histories longer than the new tokens
+    (1, 700, 2, 1000, [250]),                # many key tiles; unmasked tiles, then the diagonal
+]
+
+
+@pytest.mark.parametrize("base", [0.0, 10000.0])
+@pytest.mark.parametrize("case", PREFILL_CASES)
+def test_prefill_attention_matches_oracle(G, oracle, case, base):
+    B = G.B
+    Bn, T, H, S_max, pos = case
+    E = 128
+    rng = np.random.default_rng(500 + T + H)
+    q, kc, vc, pos = make_case(rng, Bn, T, H, E, S_max, pos, "bf16")
+    scale = E ** -0.5
+    qd, kd, vd = G.dev(q), G.dev(kc), G.dev(vc)
+    out = torch.full(qd.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.lowrank_prefill_attention(qd, kd, vd, G.dev(pos), T, out, scale, base)
+    torch.cuda.synchronize()
+    ok = kc.f64.copy()
+    want = oracle.decode_attention(q.f64, ok, vc.f64, pos, T, scale, rope_base=base)
+    got = G.host64(out)
+    assert np.isfinite(got).all()
+    assert max_rel_err(got, want) <= TOL["bf16"]
+    kb_in, kb_out, kh = kc.dev, G.bits(kd), G.host64(kd)
+    for b in range(Bn):
+        new = np.zeros(S_max, dtype=bool); new[pos[b]:pos[b] + T] = True
+        assert np.array_equal(kb_out[b][~new], kb_in[b][~new])
+        if base > 0:
+            assert max_rel_err(kh[b][new].reshape(T, -1), ok[b][new].reshape(T, -1)) <= 2.0 ** -8
+        else:
+            assert np.array_equal(kb_out[b][new], kb_in[b][new])
+
+
+def test_prefill_attention_equals_decode_attention_rotation(G):
+    """The two entry points rotate new key rows with the same arithmetic: bit-identical caches."""
+    B = G.B
+    rng = np.random.default_rng(91)
+    Bn, T, H, E, S_max = 2, 40, 2, 128, 64
+    q, kc, vc, pos = make_case(rng, Bn, T, H, E, S_max, [3, 20], "bf16")
+    qd, vd = G.dev(q), G.dev(vc)
+    k1, k2 = G.dev(kc), G.dev(kc)
+    o1 = torch.empty_like(qd); o2 = torch.empty_like(qd)
+    B.lowrank_prefill_attention(qd, k1, vd, G.dev(pos), T, o1, E ** -0.5, 10000.0)
+    ws = B.new_workspace(B.LR_OP_DECODE_ATTENTION, Bn * T, H * E, H, 0, B.LR_BF16)
+    B.lowrank_decode_attention(qd, k2, vd, G.dev(pos), T, o2, E ** -0.5, 10000.0, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.bits(k1), G.bits(k2))
+    assert max_rel_err(G.host64(o1), G.host64(o2)) <= TOL["bf16"]
+
+
+def test_prefill_attention_error_codes(G):
+    B = G.B
+    q = torch.zeros((4, 2 * 64), dtype=torch.bfloat16, device="cuda")
+    kc = torch.zeros((1, 8, 2, 64), dtype=torch.bfloat16, device="cuda")
+    pos = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.LowrankError):      # head_dim 64 is not covered by the matrix-core kernel
+        B.lowrank_prefill_attention(q, kc, kc.clone(), pos, 4, torch.empty_like(q), 1.0, 0.0)
