@@ -98,20 +98,32 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
     const int n_keys = (int)nk;
     const int nkb = (n_keys + PA_BK - 1) / PA_BK;
 
-    if (tid < 64) s_theta[tid] = a.rope_base > 0.0 ? exp2(-2.0 * (double)tid / 128.0 * log2(a.rope_base)) : 0.0;
-    __syncthreads();
-
     // ---- this lane's query row, rotated, as the B operand of S^T = K Q^T: step ks holds e = 16 ks + 8 hh .. + 7 ----
     const int s_row = s0 + wave * 32 + li;                     // token index inside the sequence
     const bool row_ok = s_row < a.T;
-    const long long p_row = pos_b + (row_ok ? s_row : a.T - 1);  // position of the row (rows past T repeat the last one; never stored)
+    const int s_clamped = row_ok ? s_row : a.T - 1;            // rows past T repeat the last one; never stored
+    const int p_row = (int)(pos_b + s_clamped);                // position of the row
     pbf16x8_t qf[8];
     {
-        const bf16_t* qrow = a.q + ((size_t)b * a.T + (size_t)(row_ok ? s_row : a.T - 1)) * a.ldq + (size_t)head * PA_E + 8 * hh;
+        const bf16_t* qrow = a.q + ((size_t)b * a.T + (size_t)s_clamped) * a.ldq + (size_t)head * PA_E + 8 * hh;
         uint4 raw[8];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) raw[ks] = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
         if (a.rope_base > 0.0) {
+            // cos / sin of the block's 128 positions x 64 frequencies, computed once by all threads into LDS (the tiles
+            // are not loaded yet): [row][i] as float2
+            if (tid < 64) s_theta[tid] = exp2(-2.0 * (double)tid / 128.0 * log2(a.rope_base));
+            __syncthreads();
+            float2* cs = reinterpret_cast<float2*>(lds);
+            for (int t = tid; t < PA_BQ * 64; t += 256) {
+                const int r = t >> 6, i = t & 63;
+                const int sr = s0 + r < a.T ? s0 + r : a.T - 1;
+                float c, sn;
+                pa_cos_sin(pos_b + sr, s_theta[i], c, sn);
+                cs[t] = make_float2(c, sn);
+            }
+            __syncthreads();
+            const float2* my = cs + (wave * 32 + li) * 64 + 8 * hh;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 const uint32_t lo[4] = {raw[ks].x, raw[ks].y, raw[ks].z, raw[ks].w};
@@ -122,13 +134,11 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
                     float rl[2], rh[2];
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        const int i = 16 * ks + 8 * hh + 2 * w + t;        // pair (i, i + 64)
+                        const float2 c_s = my[16 * ks + 2 * w + t];           // pair (i, i + 64), i = 16 ks + 8 hh + 2 w + t
                         const float ql = __uint_as_float(t ? (lo[w] & 0xffff0000u) : (lo[w] << 16));
                         const float qh = __uint_as_float(t ? (hi[w] & 0xffff0000u) : (hi[w] << 16));
-                        float c, sn;
-                        pa_cos_sin(p_row, s_theta[i], c, sn);
-                        rl[t] = (float)((double)ql * (double)c - (double)qh * (double)sn);
-                        rh[t] = (float)((double)qh * (double)c + (double)ql * (double)sn);
+                        rl[t] = (float)((double)ql * (double)c_s.x - (double)qh * (double)c_s.y);
+                        rh[t] = (float)((double)qh * (double)c_s.x + (double)ql * (double)c_s.y);
                     }
                     olo[w] = pa_pack2(rl[0], rl[1]);
                     ohi[w] = pa_pack2(rh[0], rh[1]);
@@ -136,6 +146,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
                 qf[ks] = pa_frag(olo[0], olo[1], olo[2], olo[3]);
                 qf[ks + 4] = pa_frag(ohi[0], ohi[1], ohi[2], ohi[3]);
             }
+            __syncthreads();                                    // the table has been read: the tiles may overwrite it
         } else {
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) qf[ks] = pa_frag(raw[ks].x, raw[ks].y, raw[ks].z, raw[ks].w);
@@ -148,24 +159,26 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
     const bf16_t* vbase = a.v_cache + ((size_t)b * a.S_max * a.H + head) * PA_E + (size_t)(tid & 15) * 8;
     const int lrow = tid >> 4;
     const uint32_t lds_off = (uint32_t)lrow * PA_ROW + (uint32_t)(tid & 15) * 16;
-    uint4 kreg[4], vreg[4];
-    auto load_tile = [&](int kb) {
-#pragma unroll
-        for (int ps = 0; ps < 4; ++ps) {
-            int key = kb * PA_BK + lrow + 16 * ps;
-            key = key < n_keys ? key : n_keys - 1;                         // clamped rows are masked below
-            kreg[ps] = *reinterpret_cast<const uint4*>(kbase + (size_t)key * row_stride);
-            vreg[ps] = *reinterpret_cast<const uint4*>(vbase + (size_t)key * row_stride);
-        }
-    };
-    auto store_tile = [&](int buf) {
-        char* kd = lds + buf * 2 * PA_TILE + lds_off;
-#pragma unroll
-        for (int ps = 0; ps < 4; ++ps) {
-            *reinterpret_cast<uint4*>(kd + ps * 16 * PA_ROW) = kreg[ps];
-            *reinterpret_cast<uint4*>(kd + PA_TILE + ps * 16 * PA_ROW) = vreg[ps];
-        }
-    };
+    uint4 k0r, k1r, k2r, k3r, v0r, v1r, v2r, v3r;           // the next tile on its way to LDS (named, not an array: they stay in registers)
+#define PA_LOAD_ROW(KB, PS, KR, VR)                                                                            \
+    do {                                                                                                       \
+        int key = (KB) * PA_BK + lrow + 16 * (PS);                                                             \
+        key = key < n_keys ? key : n_keys - 1;                 /* clamped rows are masked below */            \
+        KR = *reinterpret_cast<const uint4*>(kbase + (size_t)key * row_stride);                                \
+        VR = *reinterpret_cast<const uint4*>(vbase + (size_t)key * row_stride);                                \
+    } while (0)
+#define PA_LOAD_TILE(KB)                                                                                       \
+    do { PA_LOAD_ROW(KB, 0, k0r, v0r); PA_LOAD_ROW(KB, 1, k1r, v1r); PA_LOAD_ROW(KB, 2, k2r, v2r); PA_LOAD_ROW(KB, 3, k3r, v3r); } while (0)
+#define PA_STORE_ROW(KD, PS, KR, VR)                                                                           \
+    do {                                                                                                       \
+        *reinterpret_cast<uint4*>((KD) + (PS) * 16 * PA_ROW) = KR;                                             \
+        *reinterpret_cast<uint4*>((KD) + PA_TILE + (PS) * 16 * PA_ROW) = VR;                                   \
+    } while (0)
+#define PA_STORE_TILE(BUF)                                                                                     \
+    do {                                                                                                       \
+        char* kd = lds + (BUF) * 2 * PA_TILE + lds_off;                                                        \
+        PA_STORE_ROW(kd, 0, k0r, v0r); PA_STORE_ROW(kd, 1, k1r, v1r); PA_STORE_ROW(kd, 2, k2r, v2r); PA_STORE_ROW(kd, 3, k3r, v3r); \
+    } while (0)
 
     pf32x16_t acc_o[4];
 #pragma unroll
@@ -174,7 +187,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
         for (int i = 0; i < 16; ++i) acc_o[eb][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    if (nkb > 0) { load_tile(0); store_tile(0); }
+    if (nkb > 0) { PA_LOAD_TILE(0); PA_STORE_TILE(0); }
     __syncthreads();
 
     // this lane's fixed LDS offsets
@@ -185,7 +198,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
 
     for (int kb = 0; kb < nkb; ++kb) {
         const int buf = kb & 1;
-        if (kb + 1 < nkb) load_tile(kb + 1);
+        if (kb + 1 < nkb) PA_LOAD_TILE(kb + 1);
         const char* kt = lds + buf * 2 * PA_TILE;
         const char* vt = kt + PA_TILE;
 
@@ -204,17 +217,16 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
 
         // scores of this lane: key = 64 kb + 32 kbk + 8 (i / 4) + 4 hh + i % 4
         const int key0 = kb * PA_BK + 4 * hh;
+        // tiles entirely below the diagonal of this wave's rows need no mask: limit = "every key passes"
         const bool need_mask = (long long)(kb * PA_BK + PA_BK - 1) > pos_b + s0 + wave * 32 || kb * PA_BK + PA_BK > n_keys;
+        const int limit = need_mask ? (p_row < n_keys - 1 ? p_row : n_keys - 1) : 0x7fffffff;     // last visible key of this row
         float m_blk = -INFINITY;
 #pragma unroll
         for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                float sv = acc_s[kbk][i] * a.scale_log2e;
-                if (need_mask) {
-                    const int key = key0 + 32 * kbk + 8 * (i >> 2) + (i & 3);
-                    if ((long long)key > p_row || key >= n_keys) sv = -INFINITY;
-                }
+                const int key = key0 + 32 * kbk + 8 * (i >> 2) + (i & 3);
+                const float sv = key <= limit ? acc_s[kbk][i] * a.scale_log2e : -INFINITY;
                 acc_s[kbk][i] = sv;
                 m_blk = fmaxf(m_blk, sv);
             }
@@ -222,13 +234,13 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
         const float m_new = fmaxf(m_run, m_blk);
         // a row that has seen no key yet keeps m = -inf; exp2(-inf - (-inf)) would be NaN
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_use);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
         float l_blk = 0.f;
 #pragma unroll
         for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float pv = exp2f(acc_s[kbk][i] - m_use);
+                const float pv = __builtin_amdgcn_exp2f(acc_s[kbk][i] - m_use);
                 acc_s[kbk][i] = pv;
                 l_blk += pv;
             }
@@ -258,7 +270,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
             }
         }
 
-        if (kb + 1 < nkb) store_tile(buf ^ 1);
+        if (kb + 1 < nkb) PA_STORE_TILE(buf ^ 1);
         __syncthreads();
     }
 
