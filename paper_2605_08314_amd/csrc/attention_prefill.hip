@@ -60,22 +60,40 @@ __device__ __forceinline__ void pa_cos_sin(long long p, double theta, float& c, 
     sincosf((float)red, &sn, &c);
 }
 
+// One thread rotates 8 pairs (i .. i + 7, i + 64 .. i + 71) of one (token, head): two 16-byte loads and stores.
 __global__ void __launch_bounds__(256) k_rope_new_keys(PAttnArgs a) {
-    const long long total = (long long)a.B * a.T * a.H * 64;
+    __shared__ double s_theta[64];
+    if (threadIdx.x < 64) s_theta[threadIdx.x] = exp2(-2.0 * (double)threadIdx.x / 128.0 * log2(a.rope_base));
+    __syncthreads();
+    const long long total = (long long)a.B * a.T * a.H * 8;
     for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long long)gridDim.x * 256) {
-        const int i = (int)(idx & 63);
-        const int h = (int)((idx >> 6) % a.H);
-        const long long r = (idx >> 6) / a.H;
+        const int i0 = (int)(idx & 7) * 8;
+        const int h = (int)((idx >> 3) % a.H);
+        const long long r = (idx >> 3) / a.H;
         const int b = (int)(r / a.T), s = (int)(r - (long long)b * a.T);
         const long long p = (long long)a.pos[b] + s;
         if (p < 0 || p >= a.S_max) continue;
-        const double theta = exp2(-2.0 * (double)i / 128.0 * log2(a.rope_base));
-        float c, sn;
-        pa_cos_sin(p, theta, c, sn);
-        bf16_t* k = a.k_cache + (((size_t)b * a.S_max + (size_t)p) * a.H + h) * PA_E + i;
-        const double klo = (double)bf16_to_f32(k[0]), khi = (double)bf16_to_f32(k[64]);
-        k[0] = f32_to_bf16((float)(klo * (double)c - khi * (double)sn));
-        k[64] = f32_to_bf16((float)(khi * (double)c + klo * (double)sn));
+        bf16_t* k = a.k_cache + (((size_t)b * a.S_max + (size_t)p) * a.H + h) * PA_E + i0;
+        const uint4 lo4 = *reinterpret_cast<const uint4*>(k), hi4 = *reinterpret_cast<const uint4*>(k + 64);
+        const uint32_t lo[4] = {lo4.x, lo4.y, lo4.z, lo4.w}, hi[4] = {hi4.x, hi4.y, hi4.z, hi4.w};
+        uint32_t olo[4], ohi[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            bf16_t rl[2], rh[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                float c, sn;
+                pa_cos_sin(p, s_theta[i0 + 2 * w + t], c, sn);
+                const double klo = (double)__uint_as_float(t ? (lo[w] & 0xffff0000u) : (lo[w] << 16));
+                const double khi = (double)__uint_as_float(t ? (hi[w] & 0xffff0000u) : (hi[w] << 16));
+                rl[t] = f32_to_bf16((float)(klo * (double)c - khi * (double)sn));
+                rh[t] = f32_to_bf16((float)(khi * (double)c + klo * (double)sn));
+            }
+            olo[w] = (uint32_t)rl[0] | ((uint32_t)rl[1] << 16);
+            ohi[w] = (uint32_t)rh[0] | ((uint32_t)rh[1] << 16);
+        }
+        *reinterpret_cast<uint4*>(k) = make_uint4(olo[0], olo[1], olo[2], olo[3]);
+        *reinterpret_cast<uint4*>(k + 64) = make_uint4(ohi[0], ohi[1], ohi[2], ohi[3]);
     }
 }
 
@@ -137,8 +155,8 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
                         const float2 c_s = my[16 * ks + 2 * w + t];           // pair (i, i + 64), i = 16 ks + 8 hh + 2 w + t
                         const float ql = __uint_as_float(t ? (lo[w] & 0xffff0000u) : (lo[w] << 16));
                         const float qh = __uint_as_float(t ? (hi[w] & 0xffff0000u) : (hi[w] << 16));
-                        rl[t] = (float)((double)ql * (double)c_s.x - (double)qh * (double)c_s.y);
-                        rh[t] = (float)((double)qh * (double)c_s.x + (double)ql * (double)c_s.y);
+                        rl[t] = (float)((double)ql * (double)c_s.x - (double)qh * (double)c_s.y) * a.scale_log2e;
+                        rh[t] = (float)((double)qh * (double)c_s.x + (double)ql * (double)c_s.y) * a.scale_log2e;
                     }
                     olo[w] = pa_pack2(rl[0], rl[1]);
                     ohi[w] = pa_pack2(rh[0], rh[1]);
@@ -149,7 +167,14 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
             __syncthreads();                                    // the table has been read: the tiles may overwrite it
         } else {
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) qf[ks] = pa_frag(raw[ks].x, raw[ks].y, raw[ks].z, raw[ks].w);
+            for (int ks = 0; ks < 8; ++ks) {
+                const uint32_t rw[4] = {raw[ks].x, raw[ks].y, raw[ks].z, raw[ks].w};
+                uint32_t o[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    o[w] = pa_pack2(__uint_as_float(rw[w] << 16) * a.scale_log2e, __uint_as_float(rw[w] & 0xffff0000u) * a.scale_log2e);
+                qf[ks] = pa_frag(o[0], o[1], o[2], o[3]);
+            }
         }
     }
 
@@ -217,19 +242,27 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
 
         // scores of this lane: key = 64 kb + 32 kbk + 8 (i / 4) + 4 hh + i % 4
         const int key0 = kb * PA_BK + 4 * hh;
-        // tiles entirely below the diagonal of this wave's rows need no mask: limit = "every key passes"
+        // (the queries carry the softmax scale and log2 e, so the scores are exponents of 2 as they are)
+        // tiles entirely below the diagonal of this wave's rows need no mask
         const bool need_mask = (long long)(kb * PA_BK + PA_BK - 1) > pos_b + s0 + wave * 32 || kb * PA_BK + PA_BK > n_keys;
-        const int limit = need_mask ? (p_row < n_keys - 1 ? p_row : n_keys - 1) : 0x7fffffff;     // last visible key of this row
         float m_blk = -INFINITY;
+        if (need_mask) {
+            const int limit = p_row < n_keys - 1 ? p_row : n_keys - 1;        // last visible key of this row
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk)
+            for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = key0 + 32 * kbk + 8 * (i >> 2) + (i & 3);
-                const float sv = key <= limit ? acc_s[kbk][i] * a.scale_log2e : -INFINITY;
-                acc_s[kbk][i] = sv;
-                m_blk = fmaxf(m_blk, sv);
-            }
+                for (int i = 0; i < 16; ++i) {
+                    const int key = key0 + 32 * kbk + 8 * (i >> 2) + (i & 3);
+                    const float sv = key <= limit ? acc_s[kbk][i] : -INFINITY;
+                    acc_s[kbk][i] = sv;
+                    m_blk = fmaxf(m_blk, sv);
+                }
+        } else {
+#pragma unroll
+            for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) m_blk = fmaxf(m_blk, acc_s[kbk][i]);
+        }
         m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
         const float m_new = fmaxf(m_run, m_blk);
         // a row that has seen no key yet keeps m = -inf; exp2(-inf - (-inf)) would be NaN
@@ -246,7 +279,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
             }
         l_run = l_run * alpha + l_blk;
         m_run = m_new;
-        if (alpha != 1.f) {
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {       // no row of the wave raised its maximum: nothing to rescale
 #pragma unroll
             for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
@@ -310,7 +343,7 @@ int attn_prefill(const void* q, const lr_kv_target* kv, void* out, float scale, 
     a.scale_log2e = scale * 1.4426950408889634f;
     a.rope_base = (double)rope_base;
     if (a.rope_base > 0.0) {
-        const long long pairs = (long long)a.B * a.T * a.H * 64;
+        const long long pairs = (long long)a.B * a.T * a.H * 8;
         const unsigned pg = (unsigned)((pairs + 255) / 256 < 8192 ? (pairs + 255) / 256 : 8192);
         hipLaunchKernelGGL(k_rope_new_keys, dim3(pg), dim3(256), 0, s, a);
     }
