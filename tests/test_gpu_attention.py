@@ -199,3 +199,73 @@ def test_prefill_attention_error_codes(G):
     pos = torch.zeros(1, dtype=torch.int32, device="cuda")
     with pytest.raises(B.LowrankError):      # head_dim 64 is not covered by the matrix-core kernel
         B.lowrank_prefill_attention(q, kc, kc.clone(), pos, 4, torch.empty_like(q), 1.0, 0.0)
+
+
+def test_prefill_layer_chain_qkv_cache_rope_attention_o(G, oracle):
+    """The prefill attention half of a layer: lowrank_qkv writes raw k, v for 300 new tokens behind a history,
+    lowrank_prefill_attention rotates and attends, lowrank_linear projects."""
+    B = G.B
+    rng = np.random.default_rng(18)
+    Bn, T, H, E, S_max, r = 2, 300, 2, 128, 400, 128
+    d = H * E
+    pos = np.array([0, 90], dtype=np.int32)
+    bf = lambda a: synth.to_dtype(a, "bf16")
+    x = bf(rng.standard_normal((Bn * T, d)))
+    Us = [bf(rng.standard_normal((d, r)) * d ** -0.5) for _ in range(4)]
+    Vs = [bf(rng.standard_normal((r, d)) * r ** -0.5) for _ in range(4)]
+    kc = bf(rng.standard_normal((Bn, S_max, H, E))); vc = bf(rng.standard_normal((Bn, S_max, H, E)))
+    kd, vd, pd = G.dev(kc), G.dev(vc), G.dev(pos)
+    qd = torch.empty((Bn * T, d), dtype=torch.bfloat16, device="cuda")
+    ad = torch.empty_like(qd); yd = torch.empty_like(qd)
+    w1 = B.new_workspace(B.LR_OP_QKV, Bn * T, d, 3 * r, 3 * d, B.LR_BF16, "prefill")
+    w3 = B.new_workspace(B.LR_OP_LINEAR, Bn * T, d, r, d, B.LR_BF16, "prefill")
+    B.lowrank_qkv(G.dev(x), [G.dev(u) for u in Us[:3]], [G.dev(v) for v in Vs[:3]], None, [qd, None, None],
+                  dict(k_cache=kd, v_cache=vd, pos=pd, tokens_per_seq=T, k_index=1, v_index=2), "prefill", w1)
+    B.lowrank_prefill_attention(qd, kd, vd, pd, T, ad, E ** -0.5, 10000.0)
+    B.lowrank_linear(ad, G.dev(Us[3]), G.dev(Vs[3]), None, yd, "prefill", w3)
+    for w in (w1, w3):
+        B.lowrank_workspace_status(w)
+    okc, ovc = kc.f64.copy(), vc.f64.copy()
+    qkv = oracle.qkv(x.f64, [u.f64 for u in Us[:3]], [v.f64 for v in Vs[:3]],
+                     kv=dict(k_cache=okc, v_cache=ovc, pos=pos, T=T, k_index=1, v_index=2))
+    att = oracle.decode_attention(qkv[0], okc, ovc, pos, T, E ** -0.5, rope_base=10000.0)
+    want = oracle.linear(att, Us[3].f64, Vs[3].f64)
+    assert max_rel_err(G.host64(ad), att) <= TOL["bf16"]
+    assert max_rel_err(G.host64(yd), want) <= TOL["bf16"]
+
+
+def test_prefill_attention_full_size_sampled_rows(G, oracle):
+    """The benchmark's shape (8192 new tokens, 32 heads of 128, empty history): sampled rows of two heads against the
+    oracle.  The oracle sees a two-head slice of the caches whose key rows below the sampled token are rotated by the
+    oracle itself; the token's own key row is left raw for the oracle call to rotate, as the entry point does."""
+    B = G.B
+    T, H, E = 8192, 32, 128
+    gen = torch.Generator(device="cuda"); gen.manual_seed(99)
+    q = torch.randn((T, H * E), device="cuda", dtype=torch.bfloat16, generator=gen)
+    kc = torch.randn((1, T, H, E), device="cuda", dtype=torch.bfloat16, generator=gen)
+    vc = torch.randn((1, T, H, E), device="cuda", dtype=torch.bfloat16, generator=gen)
+    k_raw = kc.clone()
+    out = torch.full_like(q, float("nan"))
+    pos = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    B.lowrank_prefill_attention(q, kc, vc, pos, T, out, E ** -0.5, 10000.0)
+    torch.cuda.synchronize()
+    got = G.host64(out)
+    assert np.isfinite(got).all()
+    heads = [0, 21]
+    hs = np.array(heads)
+    k2 = G.host64(k_raw)[0][:, hs, :]                    # [T, 2, E] raw keys of two heads
+    v2 = G.host64(vc)[0][:, hs, :]
+    q2 = G.host64(q).reshape(T, H, E)[:, hs, :].reshape(T, 2 * E)
+    k_rot = oracle.rope(k2.reshape(T, 2 * E), np.arange(T), 2, E, 10000.0).reshape(T, 2, E)
+    rng = np.random.default_rng(5)
+    rows = sorted(set([0, 1, 63, 64, 127, 128, 129, 4095, 4096, 8063, 8064, 8191] + list(rng.integers(0, T, size=12))))
+    for srow in rows:
+        kcache = np.ascontiguousarray(k_rot[None, :srow + 1].copy())
+        kcache[0, srow] = k2[srow]                        # the new token's key: raw, rotated by the call
+        want = oracle.decode_attention(q2[srow:srow + 1], kcache, np.ascontiguousarray(v2[None, :srow + 1]),
+                                       np.array([srow], dtype=np.int32), 1, E ** -0.5, rope_base=10000.0)
+        sel = got[srow].reshape(H, E)[hs].reshape(1, 2 * E)
+        assert max_rel_err(sel, want) <= TOL["bf16"], srow
+    # the rotated cache rows of those heads, bf16-rounded
+    kh = G.host64(kc)[0][:, hs, :]
+    assert max_rel_err(kh.reshape(T, -1), k_rot.reshape(T, -1)) <= 2.0 ** -8
