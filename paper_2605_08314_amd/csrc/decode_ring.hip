@@ -31,11 +31,6 @@ __device__ __forceinline__ void ring_dma16(char* dst, const char* src) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                      (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
 }
-__device__ __forceinline__ const char* ring_uniform_ptr(const char* p) {
-    const uint64_t v = (uint64_t)(uintptr_t)p;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const char*>((uintptr_t)(((uint64_t)hi << 32) | lo));
-}
 __device__ __forceinline__ void ring_drain_vm() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void ring_drain_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
