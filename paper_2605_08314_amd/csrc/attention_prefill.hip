@@ -228,13 +228,16 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
         const char* vt = kt + PA_TILE;
 
         // S^T = K Q^T for the 64 keys of the tile: two 32-key blocks
+        // (the two blocks' accumulation chains alternate, so that consecutive MFMAs do not depend on each other)
         pf32x16_t acc_s[2];
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk) {
+        for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc_s[kbk][i] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+        for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+            for (int kbk = 0; kbk < 2; ++kbk) {
                 const uint4 kv4 = *reinterpret_cast<const uint4*>(kt + k_off + kbk * 32 * PA_ROW + ks * 32);
                 acc_s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_frag(kv4.x, kv4.y, kv4.z, kv4.w), qf[ks], acc_s[kbk], 0, 0, 0);
             }
