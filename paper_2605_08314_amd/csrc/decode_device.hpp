@@ -328,25 +328,47 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
                 // add the K-slices of this column tile in slice order (deterministic), eight slots in flight per lane
                 const int slices = (P.K + P.KS - 1) / P.KS;
                 const size_t slot = (size_t)16 * MB * NC, step = (size_t)P.tiles_n * slot;
-                for (int it = tid; it < M * (NC / 4); it += 64 * NW) {
-                    const int m = it / (NC / 4), c4 = 4 * (it % (NC / 4));
-                    const float* src = P.part + (size_t)(P.tile_begin + tn) * slot + (size_t)m * NC + c4;
-                    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-                    for (int sl0 = 0; sl0 < slices; sl0 += 8) {
-                        uint2 a[8], b[8];
+                // A thread takes IT outputs (4 columns of one row each) at a time and has the slices of all of them in
+                // flight together, SB slices per round trip: the sum is bound by those round trips, not by bytes.
+                constexpr int IT = NW == 4 ? 2 : 1, SB = NW == 4 ? 12 : 8;
+                const int items = M * (NC / 4);
+                for (int it0 = tid; it0 < items; it0 += 64 * NW * IT) {
+                    const float* src[IT];
+                    float acc4[IT][4];
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const int sl = sl0 + u < slices ? sl0 + u : slices - 1;
-                            a[u] = ld_coherent_b64(src + (size_t)sl * step); b[u] = ld_coherent_b64(src + (size_t)sl * step + 2);
-                        }
-#pragma unroll
-                        for (int u = 0; u < 8; ++u)
-                            if (sl0 + u < slices) {
-                                s0 += __uint_as_float(a[u].x); s1 += __uint_as_float(a[u].y);
-                                s2 += __uint_as_float(b[u].x); s3 += __uint_as_float(b[u].y);
-                            }
+                    for (int q = 0; q < IT; ++q) {
+                        int it = it0 + 64 * NW * q;
+                        it = it < items ? it : items - 1;
+                        const int m = it / (NC / 4), c4 = 4 * (it % (NC / 4));
+                        src[q] = P.part + (size_t)(P.tile_begin + tn) * slot + (size_t)m * NC + c4;
+                        acc4[q][0] = acc4[q][1] = acc4[q][2] = acc4[q][3] = 0.f;
                     }
-                    st_coherent_b64(P.Y + (size_t)m * P.ldy + n0 + c4, make_uint2(pack2(s0, s1), pack2(s2, s3)));
+                    for (int sl0 = 0; sl0 < slices; sl0 += SB) {
+                        uint2 a[IT][SB], b[IT][SB];
+#pragma unroll
+                        for (int q = 0; q < IT; ++q)
+#pragma unroll
+                            for (int u = 0; u < SB; ++u) {
+                                const int sl = sl0 + u < slices ? sl0 + u : slices - 1;
+                                a[q][u] = ld_coherent_b64(src[q] + (size_t)sl * step); b[q][u] = ld_coherent_b64(src[q] + (size_t)sl * step + 2);
+                            }
+#pragma unroll
+                        for (int q = 0; q < IT; ++q)
+#pragma unroll
+                            for (int u = 0; u < SB; ++u)
+                                if (sl0 + u < slices) {
+                                    acc4[q][0] += __uint_as_float(a[q][u].x); acc4[q][1] += __uint_as_float(a[q][u].y);
+                                    acc4[q][2] += __uint_as_float(b[q][u].x); acc4[q][3] += __uint_as_float(b[q][u].y);
+                                }
+                    }
+#pragma unroll
+                    for (int q = 0; q < IT; ++q) {
+                        const int it = it0 + 64 * NW * q;
+                        if (it < items) {
+                            const int m = it / (NC / 4), c4 = 4 * (it % (NC / 4));
+                            st_coherent_b64(P.Y + (size_t)m * P.ldy + n0 + c4, make_uint2(pack2(acc4[q][0], acc4[q][1]), pack2(acc4[q][2], acc4[q][3])));
+                        }
+                    }
                 }
             }
         }

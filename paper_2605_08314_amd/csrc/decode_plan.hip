@@ -261,7 +261,9 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
         const DStage* src[4] = {&sa, &sb, &sc, &sd};
         DStageT<1>* dst[4] = {&fa.a, &fa.b, &fa.c, &fa.d};
         for (int i = 0; i < 4; ++i) { dst[i]->p[0] = src[i]->p[0]; dst[i]->nprob = 1; dst[i]->M = (int)M; dst[i]->total_tiles = src[i]->total_tiles; }
-        return decode_launch_fused_mlp(fa, ca, cc, cd, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, use16, s);
+        // 17..32 rows: two 16-row MFMA blocks per wave; with 4 waves per workgroup the kernel has the registers for them
+        // (at 8 waves it spills), measured 45.6 against 47.8 us at 32 rows.  Up to 16 rows 8 waves are faster.
+        return decode_launch_fused_mlp(fa, ca, cc, cd, G, env_int("LOWRANK_DECODE_WAVES", M > 16 ? 4 : 8) == 4 ? 4 : 8, use16, s);
     }
     int st = fill_zero(t, (size_t)M * r_all * 4, s);
     if (st != LR_OK) return st;
