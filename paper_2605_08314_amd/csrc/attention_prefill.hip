@@ -37,8 +37,14 @@ struct PAttnArgs {
 };
 
 constexpr int PA_E = 128, PA_BQ = 128, PA_BK = 64;
-constexpr int PA_ROW = 272;                              // bytes per K / V row in LDS (256 + 16: rows start in different banks)
-constexpr int PA_TILE = PA_BK * PA_ROW;                  // 17408
+// Bytes per row of the K and V tiles in LDS.  K rows are read 16 bytes per lane by 16 lanes of 16 different rows:
+// 256 + 16 puts them 4 banks apart.  V rows are read by the transposing read, whose 32 lanes of a pass touch 4 rows
+// x 64 bytes: 256 + 64 puts those rows 16 banks apart (with 272 half of the LDS cycles were bank conflicts).
+constexpr int PA_ROW = 272;
+constexpr int PA_VROW = 320;
+constexpr int PA_KTILE = PA_BK * PA_ROW;                 // 17408
+constexpr int PA_VTILE = PA_BK * PA_VROW;                // 20480
+constexpr int PA_TILE = PA_KTILE + PA_VTILE;             // one buffer: K tile | V tile
 
 __device__ __forceinline__ uint32_t pa_pack2(float lo, float hi) {
     union { pbf16x2_t v; uint32_t u; } x;
@@ -98,7 +104,7 @@ __global__ void __launch_bounds__(256) k_rope_new_keys(PAttnArgs a) {
 }
 
 __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
-    __shared__ __attribute__((aligned(16))) char lds[4 * PA_TILE];       // K0 | V0 | K1 | V1
+    __shared__ __attribute__((aligned(16))) char lds[2 * PA_TILE];       // K0 | V0 | K1 | V1
     __shared__ double s_theta[64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, hh = lane >> 5;
@@ -184,6 +190,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
     const bf16_t* vbase = a.v_cache + ((size_t)b * a.S_max * a.H + head) * PA_E + (size_t)(tid & 15) * 8;
     const int lrow = tid >> 4;
     const uint32_t lds_off = (uint32_t)lrow * PA_ROW + (uint32_t)(tid & 15) * 16;
+    const uint32_t v_lds_off = (uint32_t)lrow * PA_VROW + (uint32_t)(tid & 15) * 16;
     uint4 k0r, k1r, k2r, k3r, v0r, v1r, v2r, v3r;           // the next tile on its way to LDS (named, not an array: they stay in registers)
 #define PA_LOAD_ROW(KB, PS, KR, VR)                                                                            \
     do {                                                                                                       \
@@ -196,12 +203,12 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
     do { PA_LOAD_ROW(KB, 0, k0r, v0r); PA_LOAD_ROW(KB, 1, k1r, v1r); PA_LOAD_ROW(KB, 2, k2r, v2r); PA_LOAD_ROW(KB, 3, k3r, v3r); } while (0)
 #define PA_STORE_ROW(KD, PS, KR, VR)                                                                           \
     do {                                                                                                       \
-        *reinterpret_cast<uint4*>((KD) + (PS) * 16 * PA_ROW) = KR;                                             \
-        *reinterpret_cast<uint4*>((KD) + PA_TILE + (PS) * 16 * PA_ROW) = VR;                                   \
+        *reinterpret_cast<uint4*>((KD) + lds_off + (PS) * 16 * PA_ROW) = KR;                                   \
+        *reinterpret_cast<uint4*>((KD) + PA_KTILE + v_lds_off + (PS) * 16 * PA_VROW) = VR;                     \
     } while (0)
 #define PA_STORE_TILE(BUF)                                                                                     \
     do {                                                                                                       \
-        char* kd = lds + (BUF) * 2 * PA_TILE + lds_off;                                                        \
+        char* kd = lds + (BUF) * PA_TILE;                                                                      \
         PA_STORE_ROW(kd, 0, k0r, v0r); PA_STORE_ROW(kd, 1, k1r, v1r); PA_STORE_ROW(kd, 2, k2r, v2r); PA_STORE_ROW(kd, 3, k3r, v3r); \
     } while (0)
 
@@ -219,13 +226,13 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
     const uint32_t k_off = (uint32_t)li * PA_ROW + (uint32_t)hh * 16;                        // + kbk * 32 * PA_ROW + ks * 32
     // transposing read of V: inside a group of 16 lanes, source lane s hands in key row s / 4 and columns 4 (s % 4)..;
     // the group (lane / 16) & 1 covers columns 16 .. 31 of the 32-column block, the half hh selects the keys
-    const uint32_t v_off = (uint32_t)(4 * hh + ((lane & 15) >> 2)) * PA_ROW + (uint32_t)(((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+    const uint32_t v_off = (uint32_t)(4 * hh + ((lane & 15) >> 2)) * PA_VROW + (uint32_t)(((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
 
     for (int kb = 0; kb < nkb; ++kb) {
         const int buf = kb & 1;
         if (kb + 1 < nkb) PA_LOAD_TILE(kb + 1);
-        const char* kt = lds + buf * 2 * PA_TILE;
-        const char* vt = kt + PA_TILE;
+        const char* kt = lds + buf * PA_TILE;
+        const char* vt = kt + PA_KTILE;
 
         // S^T = K Q^T for the 64 keys of the tile: two 32-key blocks
         // (the two blocks' accumulation chains alternate, so that consecutive MFMAs do not depend on each other)
@@ -299,9 +306,9 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
 #pragma unroll
             for (int eb = 0; eb < 4; ++eb) {
                 union { struct { ps16x4_t lo, hi; } h; pbf16x8_t v; } x;
-                const char* vp = vt + v_off + (uint32_t)(16 * a2) * PA_ROW + eb * 64;
+                const char* vp = vt + v_off + (uint32_t)(16 * a2) * PA_VROW + eb * 64;
                 x.h.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp));
-                x.h.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp + 8 * PA_ROW));
+                x.h.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp + 8 * PA_VROW));
                 acc_o[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, pf, acc_o[eb], 0, 0, 0);
             }
         }
