@@ -37,14 +37,32 @@ struct PAttnArgs {
 };
 
 constexpr int PA_E = 128, PA_BQ = 128, PA_BK = 64;
-// Bytes per row of the K and V tiles in LDS.  K rows are read 16 bytes per lane by 16 lanes of 16 different rows:
-// 256 + 16 puts them 4 banks apart.  V rows are read by the transposing read, whose 32 lanes of a pass touch 4 rows
-// x 64 bytes: 256 + 64 puts those rows 16 banks apart (with 272 half of the LDS cycles were bank conflicts).
-constexpr int PA_ROW = 272;
-constexpr int PA_VROW = 320;
-constexpr int PA_KTILE = PA_BK * PA_ROW;                 // 17408
-constexpr int PA_VTILE = PA_BK * PA_VROW;                // 20480
-constexpr int PA_TILE = PA_KTILE + PA_VTILE;             // one buffer: K tile | V tile
+// K and V tiles in LDS: 64 rows of 256 bytes each, unpadded (they arrive by direct-to-LDS loads, 1 KB = 4 rows per
+// request), with the sixteen 16-byte pieces of row r stored at position piece ^ f(r), f(r) = ((r & 3) << 2) | ((r >> 2) & 3):
+//   K is read 16 bytes per lane by 16 lanes of 16 consecutive rows, the same piece of each: f is a bijection on the 4
+//     row bits, so the 16 reads fall into 16 different bank groups;
+//   V is read by the transposing read, whose 32 lanes of a pass touch 4 consecutive rows x 64 bytes (4 pieces): the
+//     high two bits of f are r & 3, so the four rows use four different 64-byte quarters of the bank space.
+// The permutation costs nothing: a lane of the load writes LDS position (request base + lane) and simply fetches the
+// global piece that belongs there.
+constexpr int PA_TROW = 256;
+constexpr int PA_KTILE = PA_BK * PA_TROW;                // 16384
+constexpr int PA_TILE = 2 * PA_KTILE;                    // one buffer: K tile | V tile
+constexpr int PA_ROW = 272;                              // bytes per row of the output staging at the end (256 + 16)
+__host__ __device__ constexpr int pa_f(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+// 64 lanes x 16 bytes: global (sbase + voff[lane]) -> LDS (lds_byte + 16 * lane); counted by vmcnt.  (Inline assembly, so
+// that the compiler does not put a full vmcnt(0) in front of every LDS read that might alias the destination; the waits
+// are written out below.  voff registers are never rewritten while requests are in flight.)
+__device__ __forceinline__ void pa_dma16(uint32_t lds_byte, uint32_t voff, const void* sbase) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_byte), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ const char* pa_uniform_ptr(const char* p) {
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>((uintptr_t)(((uint64_t)hi << 32) | lo));
+}
 
 __device__ __forceinline__ uint32_t pa_pack2(float lo, float hi) {
     union { pbf16x2_t v; uint32_t u; } x;
@@ -104,7 +122,7 @@ __global__ void __launch_bounds__(256) k_rope_new_keys(PAttnArgs a) {
 }
 
 __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
-    __shared__ __attribute__((aligned(16))) char lds[2 * PA_TILE];       // K0 | V0 | K1 | V1
+    __shared__ __attribute__((aligned(1024))) char lds[2 * PA_TILE];     // K0 | V0 | K1 | V1
     __shared__ double s_theta[64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, hh = lane >> 5;
@@ -190,32 +208,38 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
         }
     }
 
-    // ---- K / V tile loads: thread t moves 16 bytes of row t / 16 + 16 * pass, piece t % 16 ----
-    const size_t row_stride = (size_t)a.H * PA_E;                          // elements between cache positions
-    const bf16_t* kbase = a.k_cache + ((size_t)b * a.S_max * a.H + head) * PA_E + (size_t)(tid & 15) * 8;
-    const bf16_t* vbase = a.v_cache + ((size_t)b * a.S_max * a.H + head) * PA_E + (size_t)(tid & 15) * 8;
-    const int lrow = tid >> 4;
-    const uint32_t lds_off = (uint32_t)lrow * PA_ROW + (uint32_t)(tid & 15) * 16;
-    const uint32_t v_lds_off = (uint32_t)lrow * PA_VROW + (uint32_t)(tid & 15) * 16;
-    uint4 k0r, k1r, k2r, k3r, v0r, v1r, v2r, v3r;           // the next tile on its way to LDS (named, not an array: they stay in registers)
-#define PA_LOAD_ROW(KB, PS, KR, VR)                                                                            \
+    // ---- K / V tile requests: wave w, request q covers rows 16 w + 4 q + lane / 16 of the tile, LDS piece lane % 16 ----
+    const size_t row_bytes = (size_t)a.H * PA_E * 2;                       // bytes between cache positions
+    const char* kbase = reinterpret_cast<const char*>(a.k_cache + ((size_t)b * a.S_max * a.H + head) * PA_E);
+    const char* vbase = reinterpret_cast<const char*>(a.v_cache + ((size_t)b * a.S_max * a.H + head) * PA_E);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
+    const int last_rows = n_keys - (nkb - 1) * PA_BK;                       // rows of the last tile that exist (1..64)
+    uint32_t voff[4], voff_last[4];                                         // loop-invariant: see pa_dma16
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = 16 * wave + 4 * q + (lane >> 4);
+        const int piece = (lane & 15) ^ pa_f(r & 15);
+        const int rl = r < last_rows ? r : last_rows - 1;                   // rows past the end repeat the last one (masked below)
+        voff[q] = (uint32_t)r * (uint32_t)row_bytes + (uint32_t)piece * 16u;
+        voff_last[q] = (uint32_t)rl * (uint32_t)row_bytes + (uint32_t)piece * 16u;
+    }
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+#define PA_REQUEST_TILE(KB, BUF)                                                                               \
     do {                                                                                                       \
-        int key = (KB) * PA_BK + lrow + 16 * (PS);                                                             \
-        key = key < n_keys ? key : n_keys - 1;                 /* clamped rows are masked below */            \
-        KR = *reinterpret_cast<const uint4*>(kbase + (size_t)key * row_stride);                                \
-        VR = *reinterpret_cast<const uint4*>(vbase + (size_t)key * row_stride);                                \
-    } while (0)
-#define PA_LOAD_TILE(KB)                                                                                       \
-    do { PA_LOAD_ROW(KB, 0, k0r, v0r); PA_LOAD_ROW(KB, 1, k1r, v1r); PA_LOAD_ROW(KB, 2, k2r, v2r); PA_LOAD_ROW(KB, 3, k3r, v3r); } while (0)
-#define PA_STORE_ROW(KD, PS, KR, VR)                                                                           \
-    do {                                                                                                       \
-        *reinterpret_cast<uint4*>((KD) + lds_off + (PS) * 16 * PA_ROW) = KR;                                   \
-        *reinterpret_cast<uint4*>((KD) + PA_KTILE + v_lds_off + (PS) * 16 * PA_VROW) = VR;                     \
-    } while (0)
-#define PA_STORE_TILE(BUF)                                                                                     \
-    do {                                                                                                       \
-        char* kd = lds + (BUF) * PA_TILE;                                                                      \
-        PA_STORE_ROW(kd, 0, k0r, v0r); PA_STORE_ROW(kd, 1, k1r, v1r); PA_STORE_ROW(kd, 2, k2r, v2r); PA_STORE_ROW(kd, 3, k3r, v3r); \
+        const char* ks_ = pa_uniform_ptr(kbase + (size_t)(KB) * PA_BK * row_bytes);                            \
+        const char* vs_ = pa_uniform_ptr(vbase + (size_t)(KB) * PA_BK * row_bytes);                            \
+        const uint32_t d_ = lds0 + (uint32_t)(BUF) * PA_TILE + (uint32_t)wave_u * 4096u;                       \
+        if ((KB) == nkb - 1) {                                                                                 \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                    \
+                pa_dma16(d_ + 1024u * q, voff_last[q], ks_);                                                   \
+                pa_dma16(d_ + PA_KTILE + 1024u * q, voff_last[q], vs_);                                        \
+            }                                                                                                  \
+        } else {                                                                                               \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                    \
+                pa_dma16(d_ + 1024u * q, voff[q], ks_);                                                        \
+                pa_dma16(d_ + PA_KTILE + 1024u * q, voff[q], vs_);                                             \
+            }                                                                                                  \
+        }                                                                                                      \
     } while (0)
 
     pf32x16_t acc_o[4];
@@ -225,18 +249,34 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
         for (int i = 0; i < 16; ++i) acc_o[eb][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    if (nkb > 0) { PA_LOAD_TILE(0); PA_STORE_TILE(0); }
+    if (nkb > 0) PA_REQUEST_TILE(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     // this lane's fixed LDS offsets
-    const uint32_t k_off = (uint32_t)li * PA_ROW + (uint32_t)hh * 16;                        // + kbk * 32 * PA_ROW + ks * 32
-    // transposing read of V: inside a group of 16 lanes, source lane s hands in key row s / 4 and columns 4 (s % 4)..;
-    // the group (lane / 16) & 1 covers columns 16 .. 31 of the 32-column block, the half hh selects the keys
-    const uint32_t v_off = (uint32_t)(4 * hh + ((lane & 15) >> 2)) * PA_VROW + (uint32_t)(((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+    // K operand: row 32 kbk + li, logical piece 2 ks + hh
+    uint32_t k_off[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) k_off[ks] = (uint32_t)li * PA_TROW + (uint32_t)(((2 * ks + hh) ^ pa_f(li & 15)) * 16);
+    // V operand through the transposing read: inside a group of 16 lanes, source lane s hands in key row s / 4 and columns
+    // 4 (s % 4)..; the group (lane / 16) & 1 covers columns 16 .. 31 of the 32-column block eb, the half hh selects the
+    // keys: rows 16 a2 + 4 hh + s / 4 (first four keys of the step) and + 8 (last four).  Logical piece of the 8 bytes:
+    // 4 eb + 2 g1 + (s % 4) / 2; its position: high bits eb ^ (row & 3), low bits ^ ((row >> 2) & 3).
+    uint32_t v_lo[4], v_hi[4];
+    {
+        const int sl = lane & 15, g1 = (lane >> 4) & 1;
+        const int rlo = 4 * hh + (sl >> 2), rhi = rlo + 8;
+        const int lowp = 2 * g1 + ((sl & 3) >> 1);
+#pragma unroll
+        for (int eb = 0; eb < 4; ++eb) {
+            v_lo[eb] = (uint32_t)rlo * PA_TROW + (uint32_t)((((4 * eb + lowp) ^ pa_f(rlo & 15)) * 16) + (sl & 1) * 8);
+            v_hi[eb] = (uint32_t)rhi * PA_TROW + (uint32_t)((((4 * eb + lowp) ^ pa_f(rhi & 15)) * 16) + (sl & 1) * 8);
+        }
+    }
 
     for (int kb = 0; kb < nkb; ++kb) {
         const int buf = kb & 1;
-        if (kb + 1 < nkb) PA_LOAD_TILE(kb + 1);
+        if (kb + 1 < nkb) PA_REQUEST_TILE(kb + 1, buf ^ 1);      // that buffer was last read before the previous barrier
         const char* kt = lds + buf * PA_TILE;
         const char* vt = kt + PA_KTILE;
 
@@ -251,7 +291,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
         for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
             for (int kbk = 0; kbk < 2; ++kbk) {
-                const uint4 kv4 = *reinterpret_cast<const uint4*>(kt + k_off + kbk * 32 * PA_ROW + ks * 32);
+                const uint4 kv4 = *reinterpret_cast<const uint4*>(kt + k_off[ks] + kbk * 32 * PA_TROW);
                 acc_s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_frag(kv4.x, kv4.y, kv4.z, kv4.w), qf[ks], acc_s[kbk], 0, 0, 0);
             }
         }
@@ -312,14 +352,14 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
 #pragma unroll
             for (int eb = 0; eb < 4; ++eb) {
                 union { struct { ps16x4_t lo, hi; } h; pbf16x8_t v; } x;
-                const char* vp = vt + v_off + (uint32_t)(16 * a2) * PA_VROW + eb * 64;
-                x.h.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp));
-                x.h.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp + 8 * PA_VROW));
+                const char* vp = vt + (uint32_t)(16 * a2) * PA_TROW;
+                x.h.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp + v_lo[eb]));
+                x.h.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp + v_hi[eb]));
                 acc_o[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, pf, acc_o[eb], 0, 0, 0);
             }
         }
 
-        if (kb + 1 < nkb) PA_STORE_TILE(buf ^ 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next tile has landed
         __syncthreads();
     }
 
