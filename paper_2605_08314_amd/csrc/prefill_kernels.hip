@@ -759,7 +759,7 @@ static int launch_persist(PArgs a, hipStream_t s, bool share_k = false) {
     a.trace = g_trace_buffer;
     a.sk = 0; a.sk_nk = 0;
     int grid;
-    if (share_k && EPI == PEPI_STORE && BM == 256 && BN == 256 && a.sk_slots && one_shape(a)) {
+    if (share_k && EPI == PEPI_STORE && BM == 256 && (BN == 256 || BN == 192) && a.sk_slots && one_shape(a)) {
         // shared-K walk: equal k-step ranges, at least 8 steps each, one workgroup per slot of the chip
         a.sk = 1; a.sk_nk = a.p[0].K / 32;
         const long long units = (long long)total * a.sk_nk;
@@ -767,13 +767,17 @@ static int launch_persist(PArgs a, hipStream_t s, bool share_k = false) {
         g &= ~7ll;
         if (g < 8) { a.sk = 0; }
         grid = (int)g;
+        // More rows than columns: the A operand is the big one.  Column tiles of one row block then follow each other in
+        // the walk, so that the workgroups that hold them (neighbours on one XCD) read the same rows of A at the same time
+        // and share them in that L2; otherwise row tiles of one column block do (they share B).
+        if (a.sk && a.M > a.p[0].N) a.group_m = 1;
     }
     if (!a.sk) {
         const int per_xcd = (total + 7) / 8;
         const int slots = per_xcd < 32 * MINB ? per_xcd : 32 * MINB;      // workgroups per XCD
         grid = 8 * slots;
     }
-    if constexpr (EPI == PEPI_STORE && BM == 256 && BN == 256) {
+    if constexpr (EPI == PEPI_STORE && BM == 256 && (BN == 256 || BN == 192)) {
         if (a.sk) {
             hipLaunchKernelGGL((k_prefill_persist<BM, BN, EPI, MINB, true>), dim3((unsigned)grid), dim3(256), 0, s, a);
             return launch_status("prefill gemm");
@@ -833,10 +837,15 @@ int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
         case 1: return launch_persist<128, 128, PEPI_STORE, 2>(a, s, env_sk() == 1);
         case 2: return launch_persist<256, 128, PEPI_STORE, 1>(a, s);
         case 3: return launch_persist<128, 256, PEPI_STORE, 1>(a, s);
-        case 4: return launch_persist<256, 192, PEPI_STORE, 1>(a, s);
+        case 4: return launch_persist<256, 192, PEPI_STORE, 1>(a, s, env_sk() == 1);
         default: break;
     }
-    if (want_share_k(a)) return launch_persist<256, 256, PEPI_STORE, 1>(a, s, true);
+    if (want_share_k(a)) {
+        // 192-wide tiles when they cover the columns exactly: more, aligned pieces of the K range per row block
+        // (N = 768: four column tiles x two halves of K = eight workgroups per row block, all on one XCD)
+        if (a.p[0].N % 192 == 0 && env_int("LOWRANK_PREFILL_SK192") != 0) return launch_persist<256, 192, PEPI_STORE, 1>(a, s, true);
+        return launch_persist<256, 256, PEPI_STORE, 1>(a, s, true);
+    }
     switch (pick_tile(a)) {
         case 192: return launch_persist<256, 192, PEPI_STORE, 1>(a, s);
         case 256: return launch_persist<256, 256, PEPI_STORE, 1>(a, s);
