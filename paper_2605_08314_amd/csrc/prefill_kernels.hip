@@ -758,7 +758,7 @@ static int launch_persist(PArgs a, hipStream_t s, bool share_k = false) {
     a.group_m = 8;
     a.trace = g_trace_buffer;
     a.sk = 0; a.sk_nk = 0;
-    int grid;
+    int grid = 0;
     if (share_k && EPI == PEPI_STORE && BM == 256 && (BN == 256 || BN == 192) && a.sk_slots && one_shape(a)) {
         // shared-K walk: equal k-step ranges, at least 8 steps each, one workgroup per slot of the chip
         a.sk = 1; a.sk_nk = a.p[0].K / 32;
