@@ -24,8 +24,7 @@ size_t attn_ws_bytes(int64_t M, int64_t d, int64_t H) {
            align256((size_t)M * (size_t)H * kAttnMaxSplit * (size_t)(E + 2) * 4);
 }
 
-AttnLayout attn_layout(void* ws, int64_t M, int64_t d, int64_t H) {
-    const int64_t E = H > 0 ? d / H : 0;
+AttnLayout attn_layout(void* ws, int64_t M, int64_t d, int64_t /*H*/) {
     AttnLayout L;
     char* p = (char*)ws + kHeaderBytes;
     L.q_rot = p; p += align256((size_t)M * (size_t)d * 8);
