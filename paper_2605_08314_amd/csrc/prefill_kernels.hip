@@ -491,25 +491,39 @@ __device__ __forceinline__ void sk_wait_flag(const uint32_t* flag, uint32_t* err
     }
 }
 
-// Dense-cache row index (batch * S_max + position) of the 4 rows this lane stores for one block of 32
-// tile rows starting at row r0 (uniform), or -1.  With at least 32 tokens per sequence the block
-// touches at most two sequences and their positions come through the scalar path.
+// Dense-cache rows.  A span of consecutive token rows that touches at most two sequences is described by
+// four wave-uniform numbers, found once (one division, two position loads through the scalar path); the
+// cache row of any token row m of the span then costs a compare and an add.
+struct CacheSpan {
+    int edge;          // first token row of the second sequence
+    int bi0;           // batch index of the first sequence
+    int p0, p1;        // position of the first new token of either sequence
+};
+__device__ __forceinline__ CacheSpan cache_span(const int32_t* pos, int T, int M, int r0) {
+    CacheSpan cs;
+    const int rc = r0 < M ? r0 : M - 1;
+    cs.bi0 = __builtin_amdgcn_readfirstlane(rc / T);
+    const int bl = (M - 1) / T;
+    const int bi1 = cs.bi0 + 1 < bl ? cs.bi0 + 1 : bl;
+    cs.p0 = pos[cs.bi0]; cs.p1 = pos[bi1];
+    cs.edge = (cs.bi0 + 1) * T;
+    return cs;
+}
+// batch * S_max + position of token row m (inside the span), or -1 when the row does not exist or falls outside the cache
+__device__ __forceinline__ int cache_row(const CacheSpan& cs, int T, int S_max, int M, int m) {
+    const bool second = m >= cs.edge;
+    const int bi = second ? cs.bi0 + 1 : cs.bi0;
+    const int64_t pp = (int64_t)(second ? cs.p1 : cs.p0) + (m - bi * T);
+    return (m < M && pp >= 0 && pp < S_max) ? bi * S_max + (int)pp : -1;
+}
+// The 4 rows this lane stores for one block of 32 tile rows starting at row r0 (uniform) when sequences are
+// shorter than a wave's strip of rows: a block of 32 rows still touches at most two sequences from 32 tokens
+// per sequence on; below that every lane looks its rows up by itself.
 __device__ __forceinline__ void cache_rows(int (&crow)[4], const int32_t* pos, int T, int S_max, int M, int r0, int rrow) {
     if (T >= 32) {
-        const int rc = r0 < M ? r0 : M - 1;
-        const int bi0 = __builtin_amdgcn_readfirstlane(rc / T);
-        const int bl = (M - 1) / T;
-        const int bi1 = bi0 + 1 < bl ? bi0 + 1 : bl;
-        const int p0 = pos[bi0], p1 = pos[bi1];
-        const int edge = (bi0 + 1) * T;
+        const CacheSpan cs = cache_span(pos, T, M, r0);
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int m = r0 + it * 8 + rrow;
-            const bool second = m >= edge;
-            const int bi = second ? bi0 + 1 : bi0;
-            const int64_t pp = (int64_t)(second ? p1 : p0) + (m - bi * T);
-            crow[it] = (m < M && pp >= 0 && pp < S_max) ? bi * S_max + (int)pp : -1;
-        }
+        for (int it = 0; it < 4; ++it) crow[it] = cache_row(cs, T, S_max, M, r0 + it * 8 + rrow);
     } else {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
@@ -542,6 +556,10 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
     const int32_t* const pos = P.pos; const int S_max = P.S_max, T = P.T;
     char* const wr = patch + li * 128 + lg * 8;                   // this lane's row of the patch when written
     const int wsw = (li >> 1) & 7;
+    // cache rows of the wave's strip of BM / 2 tile rows: one look-up per tile when the strip touches at most two sequences
+    const bool strip_span = EPI == PEPI_STORE && cache != nullptr && T >= BM / 2;
+    CacheSpan span = {0, 0, 0, 0};
+    if constexpr (EPI == PEPI_STORE) { if (strip_span) span = cache_span(pos, T, M, m0 + wm * (BM / 2)); }
 #pragma unroll
     for (int pr = 0; pr < (NI + 1) / 2; ++pr) {                   // pairs of 32-column blocks; the last one may be single
         const int np2 = (2 * pr + 1 < NI) ? 2 : 1;                // column blocks in this pair
@@ -567,7 +585,14 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
         for (int mi = 0; mi < MI; ++mi) {
             const int r0 = m0 + wm * (BM / 2) + mi * 32;
             int crow[4] = {-1, -1, -1, -1};
-            if constexpr (EPI == PEPI_STORE) { if (cache) cache_rows(crow, pos, T, S_max, M, r0, rrow); }
+            if constexpr (EPI == PEPI_STORE) {
+                if (strip_span) {
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) crow[it] = cache_row(span, T, S_max, M, r0 + it * 8 + rrow);
+                } else if (cache) {
+                    cache_rows(crow, pos, T, S_max, M, r0, rrow);
+                }
+            }
             // shared-K holder: the other workgroups' partial sums of this block, three slots per round trip
             float psum[2][4][4];
 #pragma unroll
