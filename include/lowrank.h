@@ -86,7 +86,8 @@ int lowrank_linear(const void *x, const void *U, const void *V, const void *bias
  * likewise v_index -> v_cache.  d_out of both projections must equal n_heads * head_dim.
  * pos is a DEVICE array of B int32; the caller guarantees 0 <= pos[b] and
  * pos[b] + tokens_per_seq <= S_max (rows that would fall outside are skipped, never written
- * out of bounds).  This struct itself lives in HOST memory.
+ * out of bounds).  B * S_max must be below 2^31 (LR_ERR_SHAPE otherwise).  This struct itself
+ * lives in HOST memory.
  */
 typedef struct {
     void *k_cache;             /* device, [B, S_max, n_heads, head_dim], element type = dtype */

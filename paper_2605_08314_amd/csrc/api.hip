@@ -181,6 +181,8 @@ int lowrank_qkv(const void* x, const void* const* U, const void* const* V, const
             set_error("kv: B * tokens_per_seq must equal M"); return LR_ERR_SHAPE; }
         if (kv->S_max < kv->tokens_per_seq || kv->n_heads < 1 || kv->head_dim < 1) {
             set_error("kv: bad cache shape"); return LR_ERR_SHAPE; }
+        if (kv->S_max >= (1ll << 30) || kv->B >= (1ll << 30) || kv->B * kv->S_max >= (1ll << 31)) {   // cache rows are indexed with 32-bit integers
+            set_error("kv: B * S_max must be below 2^31"); return LR_ERR_SHAPE; }
         const int64_t w = kv->n_heads * kv->head_dim;
         if (d_out[kv->k_index] != w || d_out[kv->v_index] != w) {
             set_error("kv: d_out of K and V must equal n_heads * head_dim"); return LR_ERR_SHAPE; }

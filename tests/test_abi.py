@@ -105,3 +105,26 @@ def test_decode_plan_walk_stays_inside_the_factors(B, monkeypatch, shape):
     assert rc == 0, lib.lowrank_last_error()
     rc = lib.lowrank_linear(fake[0], fake[1], fake[2], None, fake[6], M, d, r_g, ffn, B.LR_BF16, 0, fake[7], wsb, None)
     assert rc == 0, lib.lowrank_last_error()
+
+
+def test_qkv_cache_argument_validation_without_launch(B):
+    """lowrank_qkv rejects inconsistent cache descriptions before anything is launched."""
+    lib = _dry_lib(B)
+    fake = 0x10000
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+
+    def call(M=4, Bn=2, T=2, S_max=16, H=2, E=4, k_index=1, v_index=2, d_out=(8, 8, 8), cache=fake):
+        U = (vp * 3)(fake, fake, fake); V = (vp * 3)(fake, fake, fake); out = (vp * 3)(fake, fake, fake)
+        r = (i64 * 3)(4, 4, 4); n = (i64 * 3)(*d_out)
+        kv = B.lr_kv_target(cache, cache, fake, Bn, S_max, H, E, T, k_index, v_index)
+        return lib.lowrank_qkv(fake, U, V, None, out, r, n, 3, M, 16, ctypes.pointer(kv), B.LR_BF16, 0,
+                               fake, 1 << 44, None)      # workspace size only compared, never touched
+
+    assert call(k_index=3) == -2                      # index outside the projections
+    assert call(Bn=3) == -2                           # B * tokens_per_seq != M
+    assert call(S_max=1) == -2                        # cache shorter than one call's tokens
+    assert call(d_out=(8, 8, 16)) == -2               # V width != n_heads * head_dim
+    assert call(S_max=1 << 30) == -2                  # cache rows are 32-bit indices
+    assert call(M=1 << 21, Bn=1 << 20, S_max=1 << 12) == -2 and b"2^31" in lib.lowrank_last_error()
+    assert call(cache=None) == -1                     # NULL cache
+    assert call(M=0, Bn=0, cache=None) == 0           # empty batch: no-op
