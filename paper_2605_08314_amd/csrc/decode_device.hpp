@@ -176,6 +176,60 @@ __device__ __forceinline__ void mma_range(f32x4_t (&acc)[MB][CPL], const bf16_t*
     }
 }
 
+// Gate/up tiles: the blocks of both products as ONE sequence (nb1 blocks of W, then nb2 blocks of W2; this wave takes
+// entries wave, wave + NW, ...), so that the prefetch runs across the border between the two products.  Two ranges one
+// after the other let the requests drain at the end of the first: a memory latency per tile with nothing in flight.
+template <int MB, int CPL, bool AF32, int PF, int NW, class Sync>
+__device__ __forceinline__ void mma_range2(f32x4_t (&acc1)[MB][CPL], f32x4_t (&acc2)[MB][CPL],
+                                           const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2, int N,
+                                           const void* A, const void* A2, int lda, int lda2, int M, int col, int nb1, int nb2,
+                                           int wave, int j, int g, const Sync& sync) {
+    WFrag<CPL> wf[PF];
+    AFrag<AF32> af[PF][MB];
+    const int nv = nb1 + nb2;
+    int blk = wave;
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+        const int v = blk + NW * p;
+        if (v < nv) {
+            if (v < nb1) load_w<CPL>(wf[p], W, N, 32 * v + 8 * g, col);
+            else         load_w<CPL>(wf[p], W2, N, 32 * (v - nb1) + 8 * g, col);
+        }
+    }
+    sync();
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+        const int v = blk + NW * p;
+        if (v < nv) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                if (v < nb1) load_a<AF32, Sync::kCoherent>(af[p][mb], A, lda, 16 * mb + j, M, 32 * v + 8 * g);
+                else         load_a<AF32, Sync::kCoherent>(af[p][mb], A2, lda2, 16 * mb + j, M, 32 * (v - nb1) + 8 * g);
+            }
+        }
+    }
+    for (; blk < nv; blk += NW * PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int v = blk + NW * p;
+            if (v < nv) {
+                if (v < nb1) mma_block<MB, CPL, AF32>(acc1, wf[p], af[p]);
+                else         mma_block<MB, CPL, AF32>(acc2, wf[p], af[p]);
+                const int nx = v + NW * PF;
+                if (nx < nv) {
+                    if (nx < nb1) load_w<CPL>(wf[p], W, N, 32 * nx + 8 * g, col);
+                    else          load_w<CPL>(wf[p], W2, N, 32 * (nx - nb1) + 8 * g, col);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        if (nx < nb1) load_a<AF32, Sync::kCoherent>(af[p][mb], A, lda, 16 * mb + j, M, 32 * nx + 8 * g);
+                        else          load_a<AF32, Sync::kCoherent>(af[p][mb], A2, lda2, 16 * mb + j, M, 32 * (nx - nb1) + 8 * g);
+                    }
+                }
+            }
+        }
+    }
+}
+
 template <int CPL>
 __device__ __forceinline__ void store_bf16_row(bf16_t* dst, const float (&v)[CPL]) {
     if constexpr (CPL == 8) {
@@ -213,18 +267,25 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
 #pragma unroll
             for (int b = 0; b < CPL; ++b) acc[mt][mb][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    {
+    if constexpr (NMAT == 1) {
         const int kb0 = tk * (P.KS >> 5);
         int kb1 = kb0 + (P.KS >> 5);
         if (kb1 > (P.K >> 5)) kb1 = P.K >> 5;
         const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
         mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, kb0, kb1, wave, j, g, sync);
-    }
-    if constexpr (NMAT == 2) {
+    } else if constexpr (MB == 1) {
+        const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
         const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
-        if constexpr (Sync::kCoherent) mma_range<MB, CPL, AF32, PF, NW>(acc[1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncCoherent());
-        else if constexpr (Sync::kFused) mma_range<MB, CPL, AF32, PF, NW>(acc[1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncPlain());
-        else mma_range<MB, CPL, AF32, PF, NW>(acc[1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSync());
+        mma_range2<MB, CPL, AF32, PF, NW>(acc[0], acc[NMAT - 1], P.W, P.W2, P.N, A, A2, P.lda, P.lda2, M, col, P.K >> 5, P.K2 >> 5,
+                                          wave, j, g, sync);
+    } else {
+        // two 16-row blocks per wave: one product after the other (measured: the joint sequence is 1.2 us slower at 32 rows)
+        const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
+        const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
+        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, 0, P.K >> 5, wave, j, g, sync);
+        if constexpr (Sync::kCoherent) mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncCoherent());
+        else if constexpr (Sync::kFused) mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncPlain());
+        else mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSync());
     }
 
     // cross-wave reduction through LDS: red[wave][slot = (mat*MB + mb)*4 + v][q][lane]
