@@ -325,7 +325,7 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
         if (m < M) {
             if constexpr (EPI == EPI_ATOMIC) {
                 if (tcnt) {
-                    // more than 8 token rows: the partial tile goes to its own slot (plain device-coherent stores, no
+                    // larger row counts: the partial tile goes to its own slot (plain device-coherent stores, no
                     // atomics: 2048 of them per workgroup were what bound these stages); see the finalisation below
                     float* ps = P.part + (size_t)(P.tile_begin + lt) * (16 * MB * NC) + (size_t)m * NC + (n - n0);
 #pragma unroll
@@ -371,7 +371,7 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
     }
     if constexpr (EPI == EPI_ATOMIC) asm volatile("" ::"v"(atomic_returns));   // every atomic above has returned
 
-    // bf16 finalisation of a split-K stage (more than 8 token rows): the workgroup whose K-slice of this column
+    // bf16 finalisation of a split-K stage (larger row counts, chosen by the host planner): the workgroup whose K-slice of this column
     // tile arrives last adds up all slices' partial tiles and writes the tile as bf16 once, so that the next
     // stage's workgroups read half the bytes with plain cached loads instead of each converting the whole of t.
     if constexpr (EPI == EPI_ATOMIC) {

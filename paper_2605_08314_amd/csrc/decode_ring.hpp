@@ -37,7 +37,7 @@ struct RStage {
     int nprob, total_tiles;
     int epi;          // EPI_*
     int a_kind;       // RA_*
-    int finalise;     // EPI_ATOMIC: partial tiles to slots + bf16 finalisation by the last K-slice (more than 8 rows)
+    int finalise;     // EPI_ATOMIC: partial tiles to slots + bf16 finalisation by the last K-slice (larger row counts)
 };
 
 struct RingArgs {
