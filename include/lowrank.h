@@ -181,7 +181,7 @@ int lowrank_pack_concat(const void *const *U_list, const int64_t *r_list, int n,
  *   LR_OP_QKV         d_in, r_total = sum of r[i],       d_out = sum of d_out[i]
  *   LR_OP_PACKED_MLP  d_in = d, r_total = r_g + r_u + r_d, d_out = ffn
  *   LR_OP_DECODE_ATTENTION  d_in = n_heads * head_dim, r_total = n_heads, d_out unused
- * Returns 0 for invalid arguments.  The value covers both phases whatever `phase` says.  For 7..32
+ * Returns 0 for invalid arguments.  The value covers both phases whatever `phase` says.  For 9..32
  * token rows it includes 8 MiB for the partial tiles of the decode split-K stages, for more than 32
  * rows a fixed area of 64 MiB + 4 KiB in which the workgroups of a prefill product that share one
  * tile's K range hand their partial sums to each other.

@@ -51,20 +51,20 @@ static_assert(sizeof(Ctrl) <= kHeaderBytes, "control block must fit the workspac
 constexpr size_t kSkFlagBytes = 4096;
 constexpr size_t kSkSlotBytes = (size_t)256 * 256 * 256 * 4;
 constexpr size_t kSkBytes = kSkFlagBytes + kSkSlotBytes;
-// Tail of a decode workspace for 7..32 token rows: fp32 partial tiles of the split-K stages (one slot per
+// Tail of a decode workspace for 9..32 token rows: fp32 partial tiles of the split-K stages (one slot per
 // workgroup tile; the last K-slice of a column tile to arrive adds them up in slice order and writes bf16).
 constexpr size_t kDecPartBytes = (size_t)8 << 20;
 // More token rows than this may use split-K partial tiles in slots + bf16 finalisation instead of atomics (the packed MLP
-// does from 7 rows on, the two-stage calls from 9: measured cross-over points), so the workspace has the tail for them.
-constexpr int kT16Rows = 6;
+// does from 9 rows on, the two-stage calls from 25: measured cross-over points), so the workspace has the tail for them.
+constexpr int kT16Rows = 8;
 inline size_t sk_tail_bytes(int64_t M) { return M > 32 ? kSkBytes : (M > kT16Rows ? kDecPartBytes : 0); }
 
 // Where the parts of a workspace of `ws_bytes` bytes for M token rows sit:
-// header | acc area 0 | acc area 1 | staging | tail (decode partial tiles for 6 < M <= 32, shared-K area for M > 32).
+// header | acc area 0 | acc area 1 | staging | tail (decode partial tiles for 8 < M <= 32, shared-K area for M > 32).
 struct WsLayout {
     Ctrl* ctrl; char* acc0; size_t acc_bytes; char* staging; size_t staging_bytes;
     uint32_t* sk_flags; float* sk_slots;       // prefill tail (M > 32), else NULL
-    float* dec_part;                           // decode partial tiles (6 < M <= 32), else NULL
+    float* dec_part;                           // decode partial tiles (8 < M <= 32), else NULL
 };
 inline WsLayout ws_layout(void* ws, size_t ws_bytes, int64_t M) {
     WsLayout L;

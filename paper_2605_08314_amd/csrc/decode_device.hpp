@@ -131,8 +131,9 @@ __device__ __forceinline__ void mma_block(f32x4_t (&acc)[MB][CPL], const WFrag<C
 struct NoSync { static constexpr bool kCoherent = false, kFused = false; __device__ __forceinline__ void operator()() const {} };
 // Same, for later tiles of a stage whose input other workgroups of this launch produced.
 struct NoSyncCoherent { static constexpr bool kCoherent = true, kFused = true; __device__ __forceinline__ void operator()() const {} };
-// Later tiles of a stage whose input is a finalised bf16 copy that no workgroup on this XCD has read yet in
-// this launch: plain cached loads are safe (first touch misses L2) and let the other workgroups hit in L2.
+// Later tiles of a stage whose input (accumulators added with device-scope atomics, hidden rows or a finalised bf16
+// copy written with device-coherent stores) no workgroup on this XCD has read before the stage's barrier in this
+// launch: plain cached loads are safe (first touch misses L2) and let the other workgroups hit in L2.
 struct NoSyncPlain { static constexpr bool kCoherent = false, kFused = true; __device__ __forceinline__ void operator()() const {} };
 
 // This wave's share of rows [32*kb0, 32*kb1) of W: blocks kb0 + wave, kb0 + wave + NW, ...
@@ -519,7 +520,7 @@ struct GridWait {
     }
 };
 
-// The same wait in front of a stage that reads a finalised bf16 copy with plain loads.
+// The same wait in front of a stage that reads its input with plain cached loads (see NoSyncPlain).
 struct GridWaitPlain : GridWait {
     static constexpr bool kCoherent = false, kFused = true;
     __device__ __forceinline__ GridWaitPlain(const GridWait& g) : GridWait(g) {}
@@ -600,8 +601,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
             if (!waited) decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift);
             else         decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift);
         } else {
-            if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, gw, shift);
-            else         decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncCoherent(), shift);
+            if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift);
+            else         decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift);
         }
         if (!waited) fused_publish(fa.fc, cs);
         waited = true;
@@ -640,8 +641,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
                 if (!waited) decode_tile<MB, 4, false, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, GridWaitPlain(gw), shift);
                 else         decode_tile<MB, 4, false, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncPlain(), shift);
             } else {
-                if (!waited) decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, gw, shift);
-                else         decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncCoherent(), shift);
+                if (!waited) decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, GridWaitPlain(gw), shift);
+                else         decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncPlain(), shift);
             }
             if (!waited) fused_publish(fa.fc, cs);
             waited = true;
@@ -658,8 +659,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.c.total_tiles; tile += G) {
             uint32_t* tc = T16 ? fa.fc.ctrl->tcnt[p] : nullptr;
-            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, gw, shift, tc);
-            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncCoherent(), shift, tc);
+            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, GridWaitPlain(gw), shift, tc);
+            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncPlain(), shift, tc);
             waited = true;
             __syncthreads();
         }
@@ -676,8 +677,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
                 if (!waited) decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift);
                 else         decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift);
             } else {
-                if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, gw, shift);
-                else         decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncCoherent(), shift);
+                if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift);
+                else         decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift);
             }
             waited = true;
             __syncthreads();

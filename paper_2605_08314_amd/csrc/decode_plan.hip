@@ -107,8 +107,9 @@ static int fused_grid(size_t factor_bytes) {
 }
 
 // More than `min_rows` token rows: split-K accumulators are finalised to bf16 once (see decode_tile) instead of
-// every consumer workgroup converting all of t.  Measured cross-over (atomics / finalisation, us): packed MLP 29.7 / 30.5
-// at 5 rows, 30.2 / 30.6 at 6, 33.4 / 30.9 at 8; QKV 10.5 / 12.4 at 5, 11.6 / 12.7 at 8, 13.4 with finalisation at 16.
+// every consumer workgroup converting all of t.  Measured (atomics / finalisation, us): packed MLP 30.7 / 30.7 at 8 rows,
+// 32.7 / 31.7 at 12, 36.0 / 32.6 at 16, 52.8 / 44.7 at 32; QKV 11.7 / 13.2 at 12, 12.9 / 13.5 at 16, 15.1 / 15.0 at 24,
+// 16.2 / 15.9 at 32; O projection 9.4 / 10.0 at 12, 11.2 / 11.7 at 24, 12.1 / 12.6 at 32.
 static bool use_t16(int64_t M, int64_t col_tiles, int min_rows) {
     const int rows = env_int("LOWRANK_DECODE_T16_ROWS", min_rows);
     return M > rows && M > kT16Rows && col_tiles <= kTileCounters && env_int("LOWRANK_DECODE_T16", 1) != 0;
@@ -141,7 +142,7 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
     const int c1 = pick_cpl(all128);
     // bf16 finalisation of t needs a slot of the workspace's partial-tile area for every tile of stage 1
     const size_t slot1 = (size_t)(M > 16 ? 32 : 16) * 16 * c1 * 4;
-    bool t16 = fused && use_t16(M, R / (16 * c1), 8) && L.dec_part;
+    bool t16 = fused && use_t16(M, R / (16 * c1), 24) && L.dec_part;
     float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* t16base = (bf16_t*)L.staging;                       // [M, R] bf16 (fused launches only)
     SplitK sk[kMaxProb]; Final fin[kMaxProb];
@@ -222,7 +223,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     DStage sa, sb, sc, sd;
     const int ca = pick_cpl(r_gu % 128 == 0 && r_d % 128 == 0), cc = ca;   // both split-K stages share one tile width
     const size_t slot = (size_t)(M > 16 ? 32 : 16) * 16 * ca * 4;      // bytes of one partial tile
-    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca), 6) && L.dec_part;
+    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca), 8) && L.dec_part;
     SplitK a, c;
     for (int attempt = 0; attempt < 2; ++attempt) {
         int ctile = 0;
