@@ -36,6 +36,7 @@ struct PAttnArgs {
     double rope_base;        // <= 0: no rotation
 };
 
+constexpr float kLazyExp = 8.f;      // a row's reference maximum is moved when a score exceeds it by more than this (log2 units)
 constexpr int PA_E = 128, PA_BQ = 128, PA_BK = 64;
 // K and V tiles in LDS: 64 rows of 256 bytes each, unpadded (they arrive by direct-to-LDS loads, 1 KB = 4 rows per
 // request), with the sixteen 16-byte pieces of row r stored at position piece ^ f(r), f(r) = ((r & 3) << 2) | ((r >> 2) & 3):
@@ -247,7 +248,10 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
     for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc_o[eb][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float l_run = 0.f;
+    pf32x16_t negm;                       // minus the reference maximum of this lane's query row, in every element
+#pragma unroll
+    for (int i = 0; i < 16; ++i) negm[i] = 0.f;
 
     if (nkb > 0) PA_REQUEST_TILE(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -282,17 +286,16 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
 
         // S^T = K Q^T for the 64 keys of the tile: two 32-key blocks
         // (the two blocks' accumulation chains alternate, so that consecutive MFMAs do not depend on each other)
+        // The accumulation starts from -m_ref of the lane's query row (negm, sixteen copies: the C operand of the first
+        // MFMA), so the scores come out relative to the row's reference maximum and need no subtraction before exp2.
         pf32x16_t acc_s[2];
-#pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc_s[kbk][i] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
             for (int kbk = 0; kbk < 2; ++kbk) {
                 const uint4 kv4 = *reinterpret_cast<const uint4*>(kt + k_off[ks] + kbk * 32 * PA_TROW);
-                acc_s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_frag(kv4.x, kv4.y, kv4.z, kv4.w), qf[ks], acc_s[kbk], 0, 0, 0);
+                if (ks == 0) acc_s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_frag(kv4.x, kv4.y, kv4.z, kv4.w), qf[ks], negm, 0, 0, 0);
+                else         acc_s[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_frag(kv4.x, kv4.y, kv4.z, kv4.w), qf[ks], acc_s[kbk], 0, 0, 0);
             }
         }
 
@@ -320,27 +323,37 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
                 for (int i = 0; i < 16; ++i) m_blk = fmaxf(m_blk, acc_s[kbk][i]);
         }
         m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
-        const float m_new = fmaxf(m_run, m_blk);
-        // a row that has seen no key yet keeps m = -inf; exp2(-inf - (-inf)) would be NaN
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        float l_blk = 0.f;
+        // The reference maximum of a row moves only when the tile's relative maximum exceeds 2^kLazyExp (the weights stay
+        // below that bound in the meantime; numerator and denominator carry the same reference, so the result does not
+        // depend on it) and on the first tile, where every row sees key 0 and takes that tile's maximum.  A wave in which
+        // no row moves -- nearly all tiles -- skips the subtraction, the rescaling of O and the update of negm.
+        const bool move = kb == 0 || m_blk > kLazyExp;
+        if (__builtin_amdgcn_ballot_w64(move) != 0ull) {
+            const float delta = (move && m_blk != -INFINITY) ? m_blk : 0.f;
+            const float alpha = __builtin_amdgcn_exp2f(-delta);
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk)
+            for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float pv = __builtin_amdgcn_exp2f(acc_s[kbk][i] - m_use);
-                acc_s[kbk][i] = pv;
-                l_blk += pv;
-            }
-        l_run = l_run * alpha + l_blk;
-        m_run = m_new;
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {       // no row of the wave raised its maximum: nothing to rescale
+                for (int i = 0; i < 16; ++i) acc_s[kbk][i] -= delta;
+            const float nm = negm[0] - delta;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) negm[i] = nm;
+            l_run *= alpha;
 #pragma unroll
             for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc_o[eb][i] *= alpha;
         }
+        float l_blk = 0.f;
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float pv = __builtin_amdgcn_exp2f(acc_s[kbk][i]);
+                acc_s[kbk][i] = pv;
+                l_blk += pv;
+            }
+        l_run += l_blk;
 
         // O^T += V^T P^T, 16 keys per step: step a2 = 2 kbk + j takes score groups i / 4 = 2 j and 2 j + 1 of block kbk
 #pragma unroll

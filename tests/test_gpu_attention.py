@@ -175,6 +175,38 @@ def test_prefill_attention_matches_oracle(G, oracle, case, base):
             assert np.array_equal(kb_out[b][new], kb_in[b][new])
 
 
+@pytest.mark.parametrize("profile", ["rising", "falling", "jumps"])
+def test_prefill_attention_scores_far_from_the_first_tile(G, oracle, profile):
+    """Score profiles along the keys that make a row's running maximum move by many powers of two in later tiles
+    (rising), never again after the first (falling), or now and then (jumps): the kernel keeps its exponentials
+    relative to a reference that it moves only when needed, so every one of those paths has to give the plain softmax."""
+    B = G.B
+    rng = np.random.default_rng(777)
+    Bn, T, H, E, S_max = 1, 300, 2, 128, 512
+    pos = np.asarray([130], dtype=np.int32)                   # 130 keys of history, 300 new rows: 7 key tiles
+    u = rng.standard_normal(E); u /= np.linalg.norm(u)
+    j = np.arange(S_max, dtype=np.float64)
+    if profile == "rising":
+        amp = 0.35 * j                                        # about +22 per 64-key tile in log2 units after scaling
+    elif profile == "falling":
+        amp = 60.0 - 0.35 * j
+    else:
+        amp = 40.0 * ((j // 97) % 2) + 25.0 * (j % 131 == 0)
+    k = 0.3 * rng.standard_normal((Bn, S_max, H, E)) + amp[None, :, None, None] * u[None, None, None, :]
+    qv = 0.3 * rng.standard_normal((Bn * T, H, E)) + 3.0 * u[None, None, :]
+    q = synth.to_dtype(qv.reshape(Bn * T, H * E), "bf16")
+    kc = synth.to_dtype(k, "bf16")
+    vc = synth.to_dtype(rng.standard_normal((Bn, S_max, H, E)), "bf16")
+    scale = E ** -0.5
+    out = torch.full((Bn * T, H * E), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.lowrank_prefill_attention(G.dev(q), G.dev(kc), G.dev(vc), G.dev(pos), T, out, scale, 0.0)
+    torch.cuda.synchronize()
+    want = oracle.decode_attention(q.f64, kc.f64.copy(), vc.f64, pos, T, scale, rope_base=0.0)
+    got = G.host64(out)
+    assert np.isfinite(got).all()
+    assert max_rel_err(got, want) <= TOL["bf16"]
+
+
 def test_prefill_attention_equals_decode_attention_rotation(G):
     """The two entry points rotate new key rows with the same arithmetic: bit-identical caches."""
     B = G.B
