@@ -70,6 +70,12 @@ __device__ __forceinline__ uint32_t pa_pack2(float lo, float hi) {
     x.v = __builtin_convertvector(pf32x2_t{lo, hi}, pbf16x2_t);
     return x.u;
 }
+// acc + lo + hi of a packed bf16 pair (v_dot2_f32_bf16 with a pair of ones)
+__device__ __forceinline__ float pa_sum2(uint32_t pair, float acc) {
+    union { uint32_t u; pbf16x2_t v; } x, one;
+    x.u = pair; one.u = 0x3f803f80u;
+    return __builtin_amdgcn_fdot2_f32_bf16(x.v, one.v, acc, false);
+}
 __device__ __forceinline__ pbf16x8_t pa_frag(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     union { uint32_t u[4]; pbf16x8_t v; } x;
     x.u[0] = a; x.u[1] = b; x.u[2] = c; x.u[3] = d;
@@ -344,24 +350,25 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc_o[eb][i] *= alpha;
         }
-        float l_blk = 0.f;
+        // weights, rounded to bf16 pairs as the MFMA will see them; their sum by v_dot2_f32_bf16 against (1, 1): one
+        // instruction per pair, and the denominator adds up exactly the values that enter the numerator
+        uint32_t pp[2][8];
+        float l_a = 0.f, l_b = 0.f;
 #pragma unroll
         for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float pv = __builtin_amdgcn_exp2f(acc_s[kbk][i]);
-                acc_s[kbk][i] = pv;
-                l_blk += pv;
+            for (int g2 = 0; g2 < 8; ++g2) {
+                const uint32_t w = pa_pack2(__builtin_amdgcn_exp2f(acc_s[kbk][2 * g2]), __builtin_amdgcn_exp2f(acc_s[kbk][2 * g2 + 1]));
+                pp[kbk][g2] = w;
+                if (g2 & 1) l_b = pa_sum2(w, l_b); else l_a = pa_sum2(w, l_a);
             }
-        l_run += l_blk;
+        l_run += l_a + l_b;
 
         // O^T += V^T P^T, 16 keys per step: step a2 = 2 kbk + j takes score groups i / 4 = 2 j and 2 j + 1 of block kbk
 #pragma unroll
         for (int a2 = 0; a2 < 4; ++a2) {
             const int kbk = a2 >> 1, j = a2 & 1;
-            const pf32x16_t& sv = acc_s[kbk];
-            const pbf16x8_t pf = pa_frag(pa_pack2(sv[8 * j + 0], sv[8 * j + 1]), pa_pack2(sv[8 * j + 2], sv[8 * j + 3]),
-                                         pa_pack2(sv[8 * j + 4], sv[8 * j + 5]), pa_pack2(sv[8 * j + 6], sv[8 * j + 7]));
+            const pbf16x8_t pf = pa_frag(pp[kbk][4 * j + 0], pp[kbk][4 * j + 1], pp[kbk][4 * j + 2], pp[kbk][4 * j + 3]);
 #pragma unroll
             for (int eb = 0; eb < 4; ++eb) {
                 union { struct { ps16x4_t lo, hi; } h; pbf16x8_t v; } x;
