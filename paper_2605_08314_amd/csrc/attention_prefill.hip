@@ -16,7 +16,7 @@
 //                                                  accumulator layout hands a lane keys {8a + 4h .. +3}, so one
 //                                                  16-key MFMA step takes keys {16a' + 4h ..+3, 16a' + 8 + 4h ..+3}
 //                                                  and the V^T operand is read in the same order.
-//                     K and V tiles (64 x 128) are double-buffered in LDS, rows padded to 272 bytes.
+//                     K and V tiles (64 x 128) are double-buffered in LDS (direct-to-LDS loads, swizzled 16-byte pieces).
 #include "attention.hpp"
 
 namespace lr {
