@@ -13,6 +13,8 @@ The same JSON line also carries
   roofline      the dominant kernel family (decode packed MLP) timed alone with HIP events,
   prefill       TFLOP/s of one layer (QKV + O + MLP, config 4) at S rows, algorithmic flops,
   decode_ops    per-entry-point GB/s for each batch size,
+  prefill_ranks the four layers of the mixed-rank stack (ranks 384/768, 256, 512, 1024) at S = 512, 2048, 8192,
+  shared_basis  the shared-basis layer pair of the 13B shape: decode B = 16 and prefill S = 4096,
   decode_attention  attention over the dense cache (with rotary embedding) at several cached lengths,
   cpu_baseline  the fp64 oracle timed on this machine's host cores on a bounded sample.
 """
@@ -32,6 +34,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per decode-MLP launch at B=1 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
 # same counters read for the 256 MiB copy of --pmc-mode (profiles/decode_mlp_pmc_traffic.txt).
 MLP_TRAFFIC_BYTES = 71024442
+TRAFFIC_SOURCE = "profiles/decode_mlp_pmc_traffic.txt (rocprofv3 --pmc run of `bench.py --pmc-mode`; not measured in this run)"
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -95,7 +98,7 @@ def time_region(torch, fn, iters, warmup):
     return e0.elapsed_time(e1) / iters
 
 
-def run_prefill(torch, B, gen, ly, S):
+def run_prefill(torch, B, gen, ly, S, R_ATTN=R_ATTN, R_MLP=R_MLP, iters=10):
     """One layer at S rows (QKV with cache write, O, packed MLP): time and TFLOP/s (algorithmic flops)."""
     bf = torch.bfloat16
     xs = torch.randn((S, D), device="cuda", generator=gen).to(bf)
@@ -115,15 +118,79 @@ def run_prefill(torch, B, gen, ly, S):
         B.lowrank_packed_mlp(xs, ly.U_gu, ly.V_g, ly.V_u, ly.U_d, ly.V_d, None, None, None, ms_, "prefill", wm)
 
     plan = B.lowrank_plan_name(B.LR_OP_PACKED_MLP, S, D, 3 * R_MLP, FFN, B.LR_BF16, "prefill")
-    iters = 10 if plan != "generic" else 1
-    pms = time_region(torch, prefill_layer, iters, 2)
+    iters = iters if plan != "generic" else 1
+    # replayed as a HIP graph like the decode step: at a few hundred rows the eight launches of a layer are
+    # otherwise bound by the host's launch rate, not by the GPU
+    pms = time_region(torch, capture(torch, prefill_layer) if plan != "generic" else prefill_layer, iters, 2)
     for w in (wq, wo, wm):
         B.lowrank_workspace_status(w)
-    pfl = attn_flops(S) + mlp_flops(S)
+    pfl = attn_flops(S, R_ATTN) + mlp_flops(S, R_MLP)
     tf = pfl / (pms * 1e-3) / 1e12
     return {"workload": f"one layer, S={S}, ranks {R_ATTN}/{R_MLP}", "plan": plan, "ms": round(pms, 3),
             "TFLOPs": round(tf, 1), "frac_mfma_bf16_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
             "tokens_per_s": round(S / (pms * 1e-3), 1)}
+
+
+def run_prefill_ranks(torch, B, gen, S_list=(512, 2048, 8192), ranks=((384, 768), (256, 256), (512, 512), (1024, 1024))):
+    """The four layers of the mixed-rank stack (attention rank, MLP rank), each at S rows: time, TFLOP/s of the
+    algorithmic flops (156,160 * rho * S when all seven pairs have rank rho) and the tiles the dispatcher picked."""
+    rows = {}
+    for ra, rm in ranks:
+        ly = Layer(torch, r_attn=ra, r_mlp=rm, gen=gen)
+        for S in S_list:
+            r = run_prefill(torch, B, gen, ly, S, ra, rm, iters=6 if S >= 8192 else 10)
+            tiles = {"x*U_qkv": B.lowrank_prefill_tile(S, D, ra, 3), "t*V_qkv": B.lowrank_prefill_tile(S, ra, D, 3),
+                     "x*U_gu": B.lowrank_prefill_tile(S, D, 2 * rm, 1), "h*U_d": B.lowrank_prefill_tile(S, FFN, rm, 1),
+                     "t*V_d": B.lowrank_prefill_tile(S, rm, D, 1)}
+            r["tiles"] = {k: f"{v[0]}x{v[1]}" + ("+shareK" if v[2] else "") for k, v in tiles.items()}
+            rows[f"r{ra}-{rm}_S{S}"] = r
+        del ly
+    return rows
+
+
+def run_shared_basis(torch, B, gen, groups=20, d=5120, r=512):
+    """Shared-basis layer pair (13B shape): one basis U_sh[d, r] used by two layers with their own V_i[r, d], through
+    lowrank_qkv with the same U pointer twice (x * U_sh is formed once).  Decode at B = 16 rotating over `groups`
+    distinct groups (15.7 MB each, far more than the last-level cache in total); prefill at S = 4096."""
+    bf = torch.bfloat16
+    def w(rows, cols, fan):
+        return (torch.randn((rows, cols), device="cuda", dtype=torch.float32, generator=gen) * fan ** -0.5).to(bf)
+    sets = [(w(d, r, d), w(r, d, r), w(r, d, r)) for _ in range(groups)]
+    out = {}
+    Bn = 16
+    x = torch.randn((Bn, d), device="cuda", generator=gen).to(bf)
+    y0, y1 = torch.empty((Bn, d), device="cuda", dtype=bf), torch.empty((Bn, d), device="cuda", dtype=bf)
+    ws = B.new_workspace(B.LR_OP_QKV, Bn, d, 2 * r, 2 * d, B.LR_BF16, "decode")
+
+    def sweep_dec():
+        for U, V0, V1 in sets:
+            B.lowrank_qkv(x, [U, U], [V0, V1], None, [y0, y1], None, "decode", ws)
+
+    ms = time_region(torch, capture(torch, sweep_dec), 10, 2) / groups
+    B.lowrank_workspace_status(ws)
+    nbytes = 3 * d * r * 2 + Bn * d * 2 * 3                       # U_sh once, V_1, V_2; x read, two outputs written
+    out["decode_B16"] = {"plan": B.lowrank_plan_name(B.LR_OP_QKV, Bn, d, 2 * r, 2 * d, B.LR_BF16, "decode"),
+                         "us": round(ms * 1e3, 2), "bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                         "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                         "unshared_bytes": 4 * d * r * 2 + Bn * d * 2 * 3}
+    S = 4096
+    xs = torch.randn((S, d), device="cuda", generator=gen).to(bf)
+    z0, z1 = torch.empty((S, d), device="cuda", dtype=bf), torch.empty((S, d), device="cuda", dtype=bf)
+    wp = B.new_workspace(B.LR_OP_QKV, S, d, 2 * r, 2 * d, B.LR_BF16, "prefill")
+    U, V0, V1 = sets[0]
+
+    def pre():
+        B.lowrank_qkv(xs, [U, U], [V0, V1], None, [z0, z1], None, "prefill", wp)
+
+    ms = time_region(torch, pre, 10, 2)
+    B.lowrank_workspace_status(wp)
+    fl = 2.0 * S * (d * r + 2 * r * d)
+    t1, t2 = B.lowrank_prefill_tile(S, d, r, 1), B.lowrank_prefill_tile(S, r, d, 2)
+    out["prefill_S4096"] = {"plan": B.lowrank_plan_name(B.LR_OP_QKV, S, d, 2 * r, 2 * d, B.LR_BF16, "prefill"),
+                            "tiles": {"x*U_sh": f"{t1[0]}x{t1[1]}", "t*V_i": f"{t2[0]}x{t2[1]}"},
+                            "ms": round(ms, 4), "GFLOP": round(fl / 1e9, 1), "TFLOPs": round(fl / (ms * 1e-3) / 1e12, 1),
+                            "frac_mfma_bf16_peak": round(fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    return out
 
 
 def run_decode_attention(torch, B, gen, cases=((1, 512), (1, 2048), (1, 8192), (32, 2048)), layers=8):
@@ -274,7 +341,8 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     ms_per_step = e0.elapsed_time(e1) / args.steps
-    B.lowrank_workspace_status(buf["ws_mlp"])
+    for k in ("ws_qkv", "ws_o", "ws_mlp"):
+        B.lowrank_workspace_status(buf[k])
     qkv_b, o_b = attn_bytes(Bt)
     step_bytes = L * (qkv_b + o_b + mlp_bytes(Bt))
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
@@ -296,6 +364,7 @@ def main():
     roofline = {"bound": "hbm", "kernel": "lowrank_packed_mlp decode (k_decode_fused_mlp, all four stages of one call)",
                 "achieved": round(mlp_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(mlp_gbs / HBM_PEAK_GBS, 4), "traffic": MLP_TRAFFIC_BYTES if Bt == 1 else None,
+                "traffic_source": TRAFFIC_SOURCE if Bt == 1 else None,
                 "bytes_per_launch": mlp_bytes(Bt), "us_per_launch": round(mlp_ms * 1e3, 2),
                 "stream_read_same_size_GBps": round(per / (read_ms * 1e-3) / 1e9, 1)}
 
@@ -322,12 +391,16 @@ def main():
                 fn = (lambda: sweep(b2, (op,))) if args.eager else capture(torch, lambda: sweep(b2, (op,)))
                 ms = time_region(torch, fn, 10, 2) / L
                 row[name] = {"us": round(ms * 1e3, 2), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+            for k in ("ws_qkv", "ws_o", "ws_mlp"):
+                B.lowrank_workspace_status(b2[k])
             table[f"B{Bn}"] = row
             if b2 is not buf:
                 del b2
         out["decode_ops"] = table
 
         out["prefill"] = run_prefill(torch, B, gen, layers[0], args.prefill_rows)
+        out["prefill_ranks"] = run_prefill_ranks(torch, B, gen)
+        out["shared_basis"] = run_shared_basis(torch, B, gen)
         out["prefill_attention"] = run_prefill_attention(torch, B, gen, args.prefill_rows)
         out["decode_attention"] = run_decode_attention(torch, B, gen)
 
@@ -349,11 +422,26 @@ def main():
             el = time.perf_counter() - t_start
             if el > 12.0 or reps >= 2000:      # about 12 s of CPU work
                 break
+        # the same layer at B = 1 (the batch of the timed step): one row, hence one thread
+        x1, a1, m1 = ta["x"].f64[:1], ta["a"].f64[:1], tm["x"].f64[:1]
+        t1 = time.perf_counter()
+        reps1 = 0
+        while True:
+            oracle.qkv(x1, [ta["U_" + n].f64 for n in "qkv"], [ta["V_" + n].f64 for n in "qkv"])
+            oracle.linear(a1, ta["U_o"].f64, ta["V_o"].f64)
+            oracle.packed_mlp(m1, tm["U_gu"].f64, tm["V_g"].f64, tm["V_u"].f64, tm["U_d"].f64, tm["V_d"].f64)
+            reps1 += 1
+            el1 = time.perf_counter() - t1
+            if el1 > 4.0 or reps1 >= 200:
+                break
         layer_bytes = sum(attn_bytes(Bs)) + mlp_bytes(Bs)
         out["cpu_baseline"] = {"value": round(reps * layer_bytes / el / 1e9, 3), "unit": "GB/s",
                                "cores": min(Bs, oracle.num_threads()), "kind": "oracle",
                                "sample": f"{reps} layer(s) of the same stack at B={Bs} (fp64 oracle, rows parallel over OpenMP threads)",
-                               "tokens_per_s": round(reps * Bs / el / L, 3)}
+                               "tokens_per_s": round(reps * Bs / el / L, 3),
+                               "B1": {"ms_per_layer": round(el1 / reps1 * 1e3, 2), "cores": 1,
+                                      "GBps": round(reps1 * (sum(attn_bytes(1)) + mlp_bytes(1)) / el1 / 1e9, 3),
+                                      "tokens_per_s": round(reps1 / el1 / L, 3)}}
 
     print(json.dumps(out))
 

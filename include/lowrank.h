@@ -210,6 +210,18 @@ const char *lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, 
                               int dtype, int phase, int aligned);
 
 /*
+ * Tile selection of the prefill phase (Section 3: phase-specific kernels; heterogeneous ranks multiply the GEMM
+ * shapes a layer runs): for n_products (1..8) dense products C[M, N] = A[M, K] * B[K, N] of one launch -- the
+ * rank-space products x U_i of one call, or its reconstruction products t_i V_i -- the workgroup tile
+ * tile_m x tile_n (256x256, 256x192 or 128x128) and whether the K range of a tile is shared between workgroups
+ * (long K, few tiles: the h U_d product of the MLP).  gate_up != 0 asks for the fused gate/up kernel (always
+ * 128x128, two accumulator sets).  Pure host function, deterministic, no GPU needed.  LR_ERR_UNSUPPORTED when
+ * the shape is outside the matrix-core rule (K % 64 == 0, N % 128 == 0).
+ */
+int lowrank_prefill_tile(int64_t M, int64_t K, int64_t N, int n_products, int gate_up,
+                         int *tile_m, int *tile_n, int *share_k);
+
+/*
  * Measurement helpers (no part of the method): a kernel that only streams `bytes` (multiple of 16,
  * 16-byte aligned) from src, and a plain copy.  bench.py times the first to report the streaming
  * ceiling of the box at the size of a decode call; the second is the kernel of known traffic used

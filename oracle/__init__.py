@@ -202,3 +202,52 @@ def decode_attention(q, k_cache: np.ndarray, v_cache: np.ndarray, pos, T: int, s
         raise ValueError("cache position out of range")
     assert rc == 0, rc
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Diagnostic-only "rounding-faithful" mode.  The definitions above round nothing; a bf16 kernel
+# rounds the rank-space rows t, the hidden rows h and the outputs to bfloat16 (nearest-even).
+# The functions below take the same steps in the same order with those three roundings put in, in
+# float64 otherwise, so that a kernel result can be compared with something that differs from it by
+# accumulation order only.  They gate nothing: tests report the distance to them next to the
+# distance to the exact definition, to tell rounding from a systematic error inside the tolerance.
+# ---------------------------------------------------------------------------------------------
+def round_bf16(a) -> np.ndarray:
+    """Nearest bfloat16 (8 significant bits, ties to even) of float64 values, returned as float64.
+    Written on the float64 value itself: scale to an integer significand, round half to even, scale back."""
+    a = _f64(a)
+    out = np.zeros_like(a)
+    nz = np.isfinite(a) & (a != 0.0)
+    m, e = np.frexp(a[nz])                 # a = m * 2**e, 0.5 <= |m| < 1
+    q = np.rint(m * 256.0)                 # 8 significant bits; numpy rounds half to even
+    out[nz] = np.ldexp(q, e - 8)
+    out[~np.isfinite(a)] = a[~np.isfinite(a)]
+    return out
+
+
+def diag_linear(x, U, V, bias=None, rnd=round_bf16) -> np.ndarray:
+    """linear() with t and y rounded by ``rnd`` (identity ``rnd`` gives linear() again)."""
+    return rnd(stage2(rnd(stage1(x, U)), V, bias))
+
+
+def diag_qkv(x, Us: Sequence, Vs: Sequence, biases: Optional[Sequence] = None, rnd=round_bf16):
+    """qkv() without the cache scatter, with t and the outputs rounded by ``rnd``."""
+    t_by_basis = {}
+    outs = []
+    for i in range(len(Us)):
+        key = id(Us[i])
+        if key not in t_by_basis:
+            t_by_basis[key] = rnd(stage1(x, Us[i]))
+        outs.append(rnd(stage2(t_by_basis[key], Vs[i], None if biases is None else biases[i])))
+    return outs
+
+
+def diag_packed_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g=None, b_u=None, b_d=None, rnd=round_bf16) -> np.ndarray:
+    """packed_mlp() step by step (Section 3.1, packed gate/up) with t_gu, h, t_d and out rounded by ``rnd``."""
+    V_g, V_u = _f64(V_g), _f64(V_u)
+    r_g = V_g.shape[0]
+    t = rnd(stage1(x, U_gu))
+    g = stage2(np.ascontiguousarray(t[:, :r_g]), V_g, b_g)
+    u = stage2(np.ascontiguousarray(t[:, r_g:]), V_u, b_u)
+    h = rnd(g / (1.0 + np.exp(-g)) * u)
+    return rnd(stage2(rnd(stage1(h, U_d)), V_d, b_d))

@@ -62,6 +62,8 @@ _lib.lowrank_probe_copy.argtypes = [_vp, _vp, _sz, _vp]
 _lib.lowrank_probe_copy.restype = _int
 _lib.lowrank_plan_name.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int, _int]
 _lib.lowrank_plan_name.restype = ctypes.c_char_p
+_lib.lowrank_prefill_tile.argtypes = [_i64, _i64, _i64, _int, _int] + [ctypes.POINTER(_int)] * 3
+_lib.lowrank_prefill_tile.restype = _int
 _lib.lowrank_last_error.restype = ctypes.c_char_p
 _lib.lowrank_version.restype = ctypes.c_char_p
 
@@ -108,6 +110,13 @@ def lowrank_last_error() -> str:
 
 def lowrank_version() -> str:
     return _lib.lowrank_version().decode()
+
+
+def lowrank_prefill_tile(M: int, K: int, N: int, n_products: int = 1, gate_up: bool = False):
+    """(tile_m, tile_n, share_k) the prefill dispatcher picks for n_products products [M, K] x [K, N]."""
+    bm, bn, sk = _int(0), _int(0), _int(0)
+    _check(_lib.lowrank_prefill_tile(M, K, N, n_products, int(gate_up), ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(sk)))
+    return bm.value, bn.value, bool(sk.value)
 
 
 def lowrank_workspace_bytes(op: int, M: int, d_in: int, r_total: int, d_out: int, dtype: int, phase) -> int:

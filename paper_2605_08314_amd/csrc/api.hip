@@ -128,6 +128,15 @@ const char* lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, 
     return kPlanNames[pick_plan(dtype, phase, M, dec, pre, aligned != 0)];
 }
 
+int lowrank_prefill_tile(int64_t M, int64_t K, int64_t N, int n_products, int gate_up,
+                         int* tile_m, int* tile_n, int* share_k) {
+    if (!tile_m || !tile_n || !share_k) { set_error("NULL result pointer"); return LR_ERR_NULL; }
+    if (n_products < 1 || n_products > 8) { set_error("n_products must be 1..8"); return LR_ERR_SHAPE; }
+    if (!prefill_shape_ok(M, K, N)) { set_error("shape outside the matrix-core prefill rule (K %% 64, N %% 128)"); return LR_ERR_UNSUPPORTED; }
+    prefill_plan_query(M, K, N, n_products, gate_up != 0, tile_m, tile_n, share_k);
+    return LR_OK;
+}
+
 int lowrank_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
                    int64_t M, int64_t d_in, int64_t r, int64_t d_out, int dtype, int phase,
                    void* workspace, size_t workspace_bytes, void* stream) {

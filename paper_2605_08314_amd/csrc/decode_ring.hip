@@ -92,7 +92,7 @@ __device__ __forceinline__ void pflag_store(uint32_t lds_addr, uint32_t v) {
     asm volatile("ds_write_b32 %0, %1" :: "v"(lds_addr), "v"(v) : "memory");
 }
 struct ProducerState {
-    uint32_t issued, landed, freed, slot, window, depth, spins;
+    uint32_t issued, landed, freed, slot, window, wmax, depth, spins;
     uint32_t freed_addr, ready_addr;
     uint32_t* err;
 };
@@ -102,7 +102,7 @@ __device__ __forceinline__ void producer_retire(ProducerState& ps) {
     ring_wait_blocks(ps.issued - ps.landed - 1);
     ++ps.landed;
     pflag_store(ps.ready_addr, ps.landed);
-    if (ps.window < ps.depth) ++ps.window;
+    if (ps.window < ps.wmax) ++ps.window;
     ps.spins = 0;
 }
 
@@ -129,7 +129,8 @@ __device__ __forceinline__ void producer_run(const RingArgs& ra, int p, int lane
     ps.depth = (uint32_t)ra.depth;
     // Blocks in flight are limited by a window that starts at half the ring and grows by one per landed block, so
     // that the first requests of all workgroups at kernel start are the blocks that are needed first.
-    ps.window = (uint32_t)ra.window0 < ps.depth ? (uint32_t)ra.window0 : ps.depth;
+    ps.wmax = (uint32_t)ra.wmax < ps.depth ? (uint32_t)ra.wmax : ps.depth;
+    ps.window = (uint32_t)ra.window0 < ps.wmax ? (uint32_t)ra.window0 : ps.wmax;
     ps.err = &ra.fc.ctrl->error;
     char* ring0 = ring_lds + (size_t)p * ps.depth * kRingChunkBytes;
     const uint32_t flags_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint32_t*)flags);
@@ -538,6 +539,8 @@ bool ring_args_ok(RingArgs& ra, int grid, const char** why) {
                 if (e && *e && atoi(e) >= kRingMinDepth && atoi(e) < ra.depth) ra.depth = atoi(e);
                 e = getenv("LOWRANK_RING_WINDOW");
                 ra.window0 = (e && *e && atoi(e) >= 1) ? atoi(e) : 4;
+                e = getenv("LOWRANK_RING_WMAX");
+                ra.wmax = (e && *e && atoi(e) >= 1) ? atoi(e) : 64;
             }
             ra.a_bytes = (int)a_bytes;
             ra.red_bufs = bufs;

@@ -44,6 +44,7 @@ struct RingArgs {
     FusedCommon fc;
     int nstages, M;
     int depth;        // blocks each pair's LDS ring holds (kRingMinDepth..kRingMaxDepth)
+    int wmax;         // cap of that window
     int window0;      // blocks a producer may have in flight at kernel start (grows by one per landed block up to depth)
     int a_bytes;      // bytes of one consumer wave's activation region (behind the rings)
     int red_bufs;     // 2: the reduction scratch alternates between tiles; 1: one scratch, one more consumer sync per tile

@@ -33,6 +33,7 @@ struct PArgs {
 
 bool prefill_shape_ok(int64_t M, int64_t K, int64_t N);
 int prefill_launch(const PArgs& a, int epi, hipStream_t s);
+void prefill_plan_query(int64_t M, int64_t K, int64_t N, int n, bool gateup, int* bm, int* bn, int* share_k);
 
 int prefill_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
                    int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s);

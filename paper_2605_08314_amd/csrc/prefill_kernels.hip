@@ -12,6 +12,8 @@
 // per-wave LDS patch; from there rows leave as 16-byte stores covering whole 128-byte lines (to C
 // and/or scattered to the dense KV cache).  Epilogues: + bias, or the gate/up pair ->
 // SiLU(g + b_g) * (u + b_u).
+#include <string.h>
+#include <stdlib.h>
 #include "prefill.hpp"
 #include "decode.hpp"
 
@@ -852,6 +854,21 @@ static bool want_share_k(const PArgs& a) {
     const long t256 = (long)a.nprob * ((a.M + 255) / 256) * ((a.p[0].N + 255) / 256);
     const long nk = a.p[0].K / 32;
     return t256 <= 128 && t256 * nk / 256 >= 96;
+}
+
+// The tile the dispatcher would pick for `n` products C[M, N] = A[M, K] * B[K, N] launched together (plain
+// epilogue), and whether they would share K between workgroups.  Pure host logic (no device needed).
+void prefill_plan_query(int64_t M, int64_t K, int64_t N, int n, bool gateup, int* bm, int* bn, int* share_k) {
+    PArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = (int)M; a.nprob = n < 1 ? 1 : (n > kMaxPProb ? kMaxPProb : n);
+    for (int i = 0; i < a.nprob; ++i) { a.p[i].K = (int)K; a.p[i].N = (int)N; }
+    a.sk_slots = reinterpret_cast<float*>(sizeof(float));      // "a shared-K area exists"; never dereferenced here
+    *share_k = 0;
+    if (gateup) { *bm = 128; *bn = 128; return; }
+    if (want_share_k(a)) { *share_k = 1; *bm = 256; *bn = (N % 192 == 0) ? 192 : 256; return; }
+    const int t = pick_tile(a);
+    *bm = t == 128 ? 128 : 256; *bn = t;
 }
 
 int prefill_launch(const PArgs& a, int epi, hipStream_t s) {

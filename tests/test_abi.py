@@ -128,3 +128,37 @@ def test_qkv_cache_argument_validation_without_launch(B):
     assert call(M=1 << 21, Bn=1 << 20, S_max=1 << 12) == -2 and b"2^31" in lib.lowrank_last_error()
     assert call(cache=None) == -1                     # NULL cache
     assert call(M=0, Bn=0, cache=None) == 0           # empty batch: no-op
+
+
+def test_prefill_tile_selection_over_the_benchmark_shapes(B):
+    """Host-side tile choice of the prefill phase (pure integer logic): every product of the mixed-rank layers
+    (ranks 384/768, 256, 512, 1024 at S = 512, 2048, 8192) and of the shared-basis layer (13B shape, S = 4096)
+    gets one of the three tile kernels, tall tiles only when there are rows for them, shared K only for the long-K
+    product with few tiles, and the choices the measurements settled on at S = 8192 are the ones made."""
+    shapes = []
+    for S in (512, 2048, 8192):
+        for ra, rm in ((384, 768), (256, 256), (512, 512), (1024, 1024)):
+            shapes += [(S, 4096, ra, 3), (S, ra, 4096, 3), (S, 4096, ra, 1), (S, ra, 4096, 1),
+                       (S, 4096, 2 * rm, 1), (S, 11008, rm, 1), (S, rm, 4096, 1)]
+    shapes += [(4096, 5120, 512, 1), (4096, 512, 5120, 2), (4096, 13824, 512, 1)]
+    for M, K, N, n in shapes:
+        bm, bn, sk = B.lowrank_prefill_tile(M, K, N, n)
+        assert (bm, bn) in {(256, 256), (256, 192), (128, 128)}, (M, K, N, n)
+        assert not sk or (bm == 256 and K >= 4096 and n * ((M + 255) // 256) * ((N + 255) // 256) <= 128), (M, K, N, n)
+        if bn == 192:
+            assert N % 192 == 0 or ((N + 191) // 192) * 192 - N < ((N + 255) // 256) * 256 - N      # 192-wide only where it wastes fewer columns
+        assert B.lowrank_prefill_tile(M, K, N, n) == (bm, bn, sk)                                       # deterministic
+    # S = 8192, ranks 384/768 (the benchmark's layer): reconstruction products on 256x256, the rank-space products
+    # of width 1152 / 1536 on 256x192, h U_d (K = 11008, 96 tiles for 256 CUs) shares K on 256x192
+    assert B.lowrank_prefill_tile(8192, 384, 4096, 3) == (256, 256, False)
+    assert B.lowrank_prefill_tile(8192, 4096, 384, 3) == (256, 192, False)
+    assert B.lowrank_prefill_tile(8192, 4096, 1536, 1) == (256, 192, False)
+    assert B.lowrank_prefill_tile(8192, 11008, 768, 1) == (256, 192, True)
+    assert B.lowrank_prefill_tile(8192, 768, 4096, 1) == (256, 256, False)
+    # few rows: every product fits the chip as 128x128 tiles in one round
+    assert B.lowrank_prefill_tile(512, 4096, 384, 3) == (128, 128, False)
+    assert B.lowrank_prefill_tile(512, 11008, 768, 1) == (128, 128, False)
+    # the fused gate/up kernel has one shape; shapes outside the matrix-core rule are refused
+    assert B.lowrank_prefill_tile(8192, 768, 11008, 1, gate_up=True) == (128, 128, False)
+    with pytest.raises(B.LowrankError):
+        B.lowrank_prefill_tile(8192, 100, 4096, 1)

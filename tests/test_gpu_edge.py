@@ -120,7 +120,7 @@ def test_qkv_multi_token_cache_bias_and_null_out(G, oracle, phase, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_pack_concat_bit_exact_and_packed_equals_separate(G, oracle, dtype):
+def test_pack_concat_bit_exact(G, oracle, dtype):
     B = G.B
     rng = np.random.default_rng(8)
     d_in = 192
@@ -132,6 +132,42 @@ def test_pack_concat_bit_exact_and_packed_equals_separate(G, oracle, dtype):
     want = oracle.pack_concat([u.dev for u in Us])
     want_bits = want.view(np.uint32) if want.dtype == np.float32 else want
     assert np.array_equal(G.bits(packed), want_bits)
+
+
+@pytest.mark.parametrize("M,phase", [(1, "decode"), (8, "decode"), (20, "decode"), (300, "prefill")])
+def test_pack_concat_output_feeds_packed_mlp_and_qkv(G, oracle, M, phase):
+    """The offline prepack in use: U_gu = lowrank_pack_concat(U_gate, U_up) goes into lowrank_packed_mlp, and a
+    rank-concatenated factor [U_a | U_b] (with V_a stacked on V_b) goes into lowrank_qkv as one projection next to
+    an ordinary one.  Expected values come from the oracle on the separate factors."""
+    B = G.B
+    w = synth.mlp_layer(M, d=1024, ffn=2816, r_g=192, r_u=320, r_d=128, seed=515 + M, dtype="bf16", with_bias=True)
+    t = w.t
+    U_gu = torch.full((1024, 512), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.lowrank_pack_concat([G.dev(t["U_g"]), G.dev(t["U_u"])], U_gu)
+    out = torch.full((M, 1024), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = B.new_workspace(B.LR_OP_PACKED_MLP, M, 1024, 192 + 320 + 128, 2816, B.LR_BF16, phase)
+    B.lowrank_packed_mlp(G.dev(t["x"]), U_gu, G.dev(t["V_g"]), G.dev(t["V_u"]), G.dev(t["U_d"]), G.dev(t["V_d"]),
+                         G.dev(t["b_g"]), G.dev(t["b_u"]), G.dev(t["b_d"]), out, phase, ws)
+    B.lowrank_workspace_status(ws)
+    want = oracle.packed_mlp(t["x"].f64, oracle.pack_concat([t["U_g"].f64, t["U_u"].f64]), t["V_g"].f64, t["V_u"].f64,
+                             t["U_d"].f64, t["V_d"].f64, t["b_g"].f64, t["b_u"].f64, t["b_d"].f64)
+    assert max_rel_err(G.host64(out), want) <= TOL["bf16"]
+    # qkv: projection 0 uses the packed pair, projection 1 an ordinary factor pair
+    rng = np.random.default_rng(616 + M)
+    d_in, d_out = 512, 1024
+    Ua, Ub, Uc = (rand_t(rng, (d_in, r), "bf16", d_in ** -0.5) for r in (64, 128, 192))
+    Va, Vb, Vc = (rand_t(rng, (r, d_out), "bf16", r ** -0.5) for r in (64, 128, 192))
+    x = rand_t(rng, (M, d_in), "bf16")
+    Uab = torch.full((d_in, 192), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.lowrank_pack_concat([G.dev(Ua), G.dev(Ub)], Uab)
+    Vab = torch.cat([G.dev(Va), G.dev(Vb)], dim=0).contiguous()
+    outs = [torch.full((M, d_out), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    ws = B.new_workspace(B.LR_OP_QKV, M, d_in, 384, 2 * d_out, B.LR_BF16, phase)
+    B.lowrank_qkv(G.dev(x), [Uab, G.dev(Uc)], [Vab, G.dev(Vc)], None, outs, None, phase, ws)
+    B.lowrank_workspace_status(ws)
+    want0 = oracle.linear(x.f64, Ua.f64, Va.f64) + oracle.linear(x.f64, Ub.f64, Vb.f64)     # separate factors, summed
+    assert max_rel_err(G.host64(outs[0]), want0) <= TOL["bf16"]
+    assert max_rel_err(G.host64(outs[1]), oracle.linear(x.f64, Uc.f64, Vc.f64)) <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("M", [1, 5, 32, 40, 300])

@@ -414,3 +414,47 @@ def test_attention_with_rope_rotates_new_keys_in_place_and_queries(oracle):
     want = oracle.decode_attention(oracle.rope(q, rows_pos, H, E), kc.copy(), vc, pos, T, E ** -0.5, rope_base=0.0)
     assert np.allclose(out, want, rtol=1e-13, atol=1e-15)
     assert not np.allclose(out, oracle.decode_attention(q, k_in.copy(), vc, pos, T, E ** -0.5), atol=1e-3)
+
+
+# ------------------------------------------------------------------ diagnostic rounding-faithful mode
+def test_round_bf16_known_values_and_grid():
+    import oracle as o
+    # ties to even at 8 significant bits: 1 + 2^-8 is half-way between 1 and 1 + 2^-7
+    assert o.round_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert o.round_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    assert o.round_bf16(np.array([1.0 + 2.0 ** -8 + 2.0 ** -20]))[0] == 1.0 + 2.0 ** -7
+    assert o.round_bf16(np.array([-3.0, 0.0, 0.15625, 255.0, 256.5]))[::1].tolist() == [-3.0, 0.0, 0.15625, 255.0, 256.0]
+    rng = np.random.default_rng(11)
+    a = rng.standard_normal(4096) * np.exp(rng.uniform(-20, 20, 4096))
+    r = o.round_bf16(a)
+    assert np.array_equal(o.round_bf16(r), r)                                  # idempotent: results are on the grid
+    assert np.max(np.abs(r - a) / np.abs(a)) <= 2.0 ** -8                      # half a unit in the 8th significant bit
+    # independent statement of the same rounding: through the float32 bit pattern (inputs exactly float32 here)
+    f = a.astype(np.float32)
+    assert np.array_equal(o.round_bf16(f.astype(np.float64)), synth.bf16_bits_to_f64(synth.f64_to_bf16_bits(f)))
+
+
+def test_diag_mode_is_the_exact_definition_when_nothing_rounds(oracle):
+    rng = np.random.default_rng(12)
+    ident = lambda a: a
+    x = rng.standard_normal((5, 24)); U = rng.standard_normal((24, 6)); V = rng.standard_normal((6, 10)); b = rng.standard_normal(10)
+    assert np.array_equal(oracle.diag_linear(x, U, V, b, rnd=ident), oracle.linear(x, U, V, b))
+    ya = oracle.diag_qkv(x, [U, U], [V, 2 * V], [b, None], rnd=ident)
+    yb = oracle.qkv(x, [U, U], [V, 2 * V], [b, None])
+    assert all(np.array_equal(p, q) for p, q in zip(ya, yb))
+    w = synth.mlp_layer(3, d=32, ffn=40, r_g=4, r_u=6, r_d=5, seed=5, dtype="f32", with_bias=True).t
+    args = [w[n].f64 for n in ("x", "U_gu", "V_g", "V_u", "U_d", "V_d", "b_g", "b_u", "b_d")]
+    assert max_rel_err(oracle.diag_packed_mlp(*args, rnd=ident), oracle.packed_mlp(*args)) <= 1e-13
+    # integer-valued eighths: every intermediate of the linear layer is exactly representable, so rounding changes nothing
+    xi = rng.integers(-4, 5, (4, 8)) / 8.0; Ui = rng.integers(-2, 3, (8, 3)).astype(float); Vi = rng.integers(-2, 3, (3, 5)).astype(float)
+    assert np.array_equal(oracle.diag_linear(xi, Ui, Vi), oracle.linear(xi, Ui, Vi))
+
+
+def test_diag_mode_differs_from_exact_by_rounding_only(oracle):
+    w = synth.mlp_layer(4, d=256, ffn=448, r_g=64, r_u=64, r_d=64, seed=6, dtype="bf16", with_bias=True).t
+    args = [w[n].f64 for n in ("x", "U_gu", "V_g", "V_u", "U_d", "V_d", "b_g", "b_u", "b_d")]
+    e = max_rel_err(oracle.diag_packed_mlp(*args), oracle.packed_mlp(*args))
+    assert 0.0 < e <= 4 * 2.0 ** -8                                             # four roundings of at most 2^-8 each
+    wa = synth.attention_layer(4, d=256, r=32, n_heads=2, S_max=8, seed=7).t
+    e = max_rel_err(oracle.diag_linear(wa["x"].f64, wa["U_q"].f64, wa["V_q"].f64), oracle.linear(wa["x"].f64, wa["U_q"].f64, wa["V_q"].f64))
+    assert 0.0 < e <= 2 * 2.0 ** -8
