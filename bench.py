@@ -260,6 +260,7 @@ def main():
 
     import torch
     from paper_2605_08314_amd import binding as B
+    from paper_2605_08314_amd import bench_probe as probe
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
@@ -315,7 +316,7 @@ def main():
         dst = torch.empty_like(src)
         buf = decode_buffers(Bt)
         for _ in range(4):
-            B.lowrank_probe_copy(dst, src)
+            probe.copy(dst, src)
         for _ in range(4):
             sweep(buf, (op_mlp,))
         torch.cuda.synchronize()
@@ -358,7 +359,7 @@ def main():
     slices = [big[i * per:(i + 1) * per] for i in range(L)]
     def read_sweep():
         for sl in slices:
-            B.lowrank_probe_read(sl, sink)
+            probe.read(sl, sink)
     read_ms = time_region(torch, read_sweep if args.eager else capture(torch, read_sweep), max(3, args.steps // 2), 2) / L
     del big, slices
     roofline = {"bound": "hbm", "kernel": "lowrank_packed_mlp decode (k_decode_fused_mlp, all four stages of one call)",

@@ -26,18 +26,33 @@
  *              no device memory, never synchronises the stream and never changes the current
  *              device.  All work is enqueued on `stream` (a hipStream_t, NULL = default stream).
  *   Workspace  Caller-provided device scratch of at least lowrank_workspace_bytes(...) bytes,
- *              256-byte aligned.  It must be prepared ONCE after allocation with
- *              lowrank_workspace_init (or by zero-filling it) and is left prepared by every
- *              successful call.  A workspace is always passed with the same workspace_bytes.
- *              Two calls that share a workspace must be ordered on one stream; calls overlapping
- *              in time on one workspace race.
+ *              256-byte aligned.  Its contents on entry may be anything: the first call that finds no
+ *              valid control block at its start prepares the workspace itself, on `stream`, without
+ *              host synchronisation (lowrank_workspace_init does the same ahead of time and is
+ *              optional).  Between calls the library keeps state in the first 16 MiB + 20 KiB; the
+ *              rest is scratch whose contents are undefined after a call.  One workspace may serve
+ *              calls of any entry point, phase, shape and row count for which it is large enough.
+ *              Two calls that share a workspace must be ordered on one stream; calls overlapping in
+ *              time on one workspace race.
+ *   Residency  Decode calls (up to 32 rows) normally run as ONE launch whose workgroups (one per
+ *              compute unit) hand intermediates to each other through device-wide counters, and the
+ *              prefill product with the longest K shares tiles between workgroups the same way.  Both
+ *              need every workgroup of the launch resident at the same time, which holds when nothing
+ *              else occupies compute units while the call runs: no kernel of another stream, process
+ *              or graph branch.  A caller that cannot guarantee this says so once with
+ *              lowrank_configure(LR_CFG_DEVICE_SHARED, 1); calls then use one launch per stage and no
+ *              cross-workgroup waits.  If the guarantee is broken anyway, the waits are bounded: a
+ *              workgroup that gives up writes NaN as its part of the result and raises the error word
+ *              of the workspace, every later call on that workspace returns NaN results until it is
+ *              prepared again (lowrank_workspace_init), and lowrank_workspace_status reports it.
  *   Errors     Return value is an lr_status: 0 on success, negative on error.  On a validation
  *              error nothing is launched.  lowrank_last_error() gives a thread-local message.
  *              No C++ exception crosses this boundary.
  *   Sizes      Any M, d_in, r, d_out >= 0 is legal.  M == 0 is a no-op.  r == 0 gives
- *              y = bias (or zeros).  The fast kernels need bf16, 16-byte aligned pointers and
- *              dimensions that are multiples of 64; anything else takes a slower generic kernel
- *              with the same results to rounding.
+ *              y = bias (or zeros).  The fast kernels need bf16 and 16-byte aligned pointers;
+ *              decode (up to 32 rows): every d_in and r a multiple of 32, every r and d_out a multiple
+ *              of 64; prefill: every d_in and r a multiple of 64, every r and d_out a multiple of 128.
+ *              Anything else takes a slower generic kernel with the same results to rounding.
  */
 #ifndef LOWRANK_H
 #define LOWRANK_H
@@ -148,7 +163,7 @@ int lowrank_packed_mlp(const void *x, const void *U_gu, const void *V_g, const v
  * q and out are [M, n_heads * head_dim], element type = dtype; out must not alias q.  head_dim must be
  * even and at most 1024.  The caller guarantees 0 <= pos[b] and pos[b] + tokens_per_seq <= S_max
  * (positions outside are clamped for memory safety, results for such rows are meaningless).
- * Workspace: lowrank_workspace_bytes(LR_OP_DECODE_ATTENTION, ...), prepared like every workspace.
+ * Workspace: lowrank_workspace_bytes(LR_OP_DECODE_ATTENTION, ...); pure scratch, no preparation needed.
  * Bound by streaming the visible K and V rows once; meant for the 1..32 rows of a decode step.
  */
 int lowrank_decode_attention(const void *q, const lr_kv_target *kv, void *out, float scale, float rope_base,
@@ -181,25 +196,38 @@ int lowrank_pack_concat(const void *const *U_list, const int64_t *r_list, int n,
  *   LR_OP_QKV         d_in, r_total = sum of r[i],       d_out = sum of d_out[i]
  *   LR_OP_PACKED_MLP  d_in = d, r_total = r_g + r_u + r_d, d_out = ffn
  *   LR_OP_DECODE_ATTENTION  d_in = n_heads * head_dim, r_total = n_heads, d_out unused
- * Returns 0 for invalid arguments.  The value covers both phases whatever `phase` says.  For 9..32
- * token rows it includes 8 MiB for the partial tiles of the decode split-K stages, for more than 32
- * rows a fixed area of 64 MiB + 4 KiB in which the workgroups of a prefill product that share one
- * tile's K range hand their partial sums to each other.
+ * Returns 0 for invalid arguments.  The value covers both phases whatever `phase` says and grows with M: a
+ * workspace sized for M rows serves every call of the same kind with fewer rows.  Every workspace of the three
+ * linear entry points starts with a fixed part of 16 MiB + 20 KiB (control block, flags, partial-tile area, two
+ * accumulator areas) followed by scratch for the rank-space and hidden rows; for more than 32 rows another 64 MiB
+ * hold the partial sums that workgroups of a prefill product sharing one tile's K range hand to each other.
  */
 size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,
                                int dtype, int phase);
 
-/* Prepare a freshly allocated workspace (enqueues a fill on `stream`).  Equivalent to zero-filling it. */
+/*
+ * Optional: prepare a workspace ahead of its first use, or again after lowrank_workspace_status reported a
+ * failure (enqueues three small launches on `stream`; no synchronisation).  The decode-attention workspace keeps
+ * no state between calls and needs no preparation.
+ */
 int lowrank_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Diagnostic, the only function here that SYNCHRONISES `stream`: reads the workspace's control
- * block back and returns LR_OK, or LR_ERR_LAUNCH if a bounded device-side wait gave up -- between
- * the stages of a fused decode call, or for the partial sums of a prefill product whose K range is
- * shared between workgroups (then that call's results are invalid and the workspace must be
- * prepared again).
+ * block back and returns LR_OK, or LR_ERR_LAUNCH if a bounded device-side wait gave up (see "Residency"
+ * above; that call's results are NaN where they could not be completed).
  */
 int lowrank_workspace_status(const void *workspace, void *stream);
+
+/*
+ * Process-wide settings (host only; not thread-safe against concurrent calls of the entry points).
+ *   LR_CFG_DEVICE_SHARED  value != 0: other work may occupy compute units while calls run, so no launch may
+ *                         depend on all of its workgroups being resident (see "Residency").  Default 0.
+ *   LR_CFG_WAIT_LIMIT     number of polls after which a device-side wait gives up (default 2^20, about half a
+ *                         second).  A robustness knob for callers that prefer an early NaN to a long stall.
+ */
+typedef enum { LR_CFG_DEVICE_SHARED = 0, LR_CFG_WAIT_LIMIT = 1 } lr_config;
+int lowrank_configure(int option, int64_t value);
 
 /*
  * Name of the kernel family the dispatcher picks for a call of this shape, e.g.
@@ -220,16 +248,6 @@ const char *lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, 
  */
 int lowrank_prefill_tile(int64_t M, int64_t K, int64_t N, int n_products, int gate_up,
                          int *tile_m, int *tile_n, int *share_k);
-
-/*
- * Measurement helpers (no part of the method): a kernel that only streams `bytes` (multiple of 16,
- * 16-byte aligned) from src, and a plain copy.  bench.py times the first to report the streaming
- * ceiling of the box at the size of a decode call; the second is the kernel of known traffic used
- * to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters.  `sink` is a device word that is
- * (practically) never written.
- */
-int lowrank_probe_read(const void *src, size_t bytes, void *sink, void *stream);
-int lowrank_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 const char *lowrank_last_error(void);   /* thread-local, static storage, never NULL */
 const char *lowrank_version(void);

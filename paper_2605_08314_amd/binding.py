@@ -56,10 +56,8 @@ _lib.lowrank_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.lowrank_workspace_init.restype = _int
 _lib.lowrank_workspace_status.argtypes = [_vp, _vp]
 _lib.lowrank_workspace_status.restype = _int
-_lib.lowrank_probe_read.argtypes = [_vp, _sz, _vp, _vp]
-_lib.lowrank_probe_read.restype = _int
-_lib.lowrank_probe_copy.argtypes = [_vp, _vp, _sz, _vp]
-_lib.lowrank_probe_copy.restype = _int
+_lib.lowrank_configure.argtypes = [_int, _i64]
+_lib.lowrank_configure.restype = _int
 _lib.lowrank_plan_name.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int, _int]
 _lib.lowrank_plan_name.restype = ctypes.c_char_p
 _lib.lowrank_prefill_tile.argtypes = [_i64, _i64, _i64, _int, _int] + [ctypes.POINTER(_int)] * 3
@@ -136,20 +134,24 @@ def lowrank_workspace_status(workspace: torch.Tensor, stream=None) -> None:
     _check(_lib.lowrank_workspace_status(_ptr(workspace), _stream(stream)))
 
 
-def lowrank_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
-    _check(_lib.lowrank_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
+LR_CFG_DEVICE_SHARED, LR_CFG_WAIT_LIMIT = 0, 1
 
 
-def lowrank_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
-    _check(_lib.lowrank_probe_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)))
+def lowrank_configure(option: int, value: int) -> None:
+    _check(_lib.lowrank_configure(option, value))
 
 
 def new_workspace(op: int, M: int, d_in: int, r_total: int, d_out: int, dtype: int, phase="auto",
-                  device="cuda") -> torch.Tensor:
-    """Allocate (with torch) and prepare a workspace big enough for the given call."""
+                  device="cuda", prepare: bool = False) -> torch.Tensor:
+    """Allocate (with torch) a workspace big enough for the given call.  The library prepares a workspace
+    itself on first use, so nothing else is needed; ``prepare=True`` also calls lowrank_workspace_init.
+    The part in which the library keeps state is filled with random bytes first, so that no caller (or
+    test) can come to depend on fresh memory happening to be zero."""
     n = max(lowrank_workspace_bytes(op, M, d_in, r_total, d_out, dtype, phase), 4096)
     ws = torch.empty(n, dtype=torch.uint8, device=device)
-    lowrank_workspace_init(ws)
+    ws[: min(n, 17 << 20)].random_(0, 256)
+    if prepare:
+        lowrank_workspace_init(ws)
     return ws
 
 

@@ -46,6 +46,12 @@ def build_lib(verbose: bool = True) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    # the benchmark's measurement kernels: a library of their own, not part of liblowrank.so
+    probe_src = os.path.join(HERE, "bench_probe", "probe_kernels.hip")
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+                           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                           probe_src, "-o", os.path.join(HERE, "bench_probe", "libbenchprobe.so")],
+                          stderr=subprocess.DEVNULL)
     return LIB
 
 

@@ -60,13 +60,12 @@ static Plan pick_plan(int dtype, int phase, int64_t M, bool decode_ok, bool pref
 }
 
 static size_t ws_bytes_for(int op, int64_t M, int64_t r_total, int64_t d_out) {
-    // header | accumulator area 0 | accumulator area 1 | staging (two quarters) | shared-K tail, see ws_layout().
-    // A quarter holds the fp32 rank-space rows [M, r_total]; for the MLP also fp32 [M, ffn], so
-    // that the staging half fits rank-space rows plus hidden rows in any kernel family.
-    size_t q = align256((size_t)M * (size_t)r_total * 4);
-    if (op == LR_OP_PACKED_MLP) { const size_t hq = align256((size_t)M * (size_t)d_out * 4); if (hq > q) q = hq; }
-    if (q < 256) q = 256;
-    return kHeaderBytes + 4 * q + sk_tail_bytes(M);
+    // fixed front (control block, flags, partial-tile area, two accumulator areas: see ws_layout) | staging | shared-K tail.
+    // Staging holds the rank-space rows [M, r_total] and, for the MLP, the hidden rows [M, ffn], as fp32 (the widest
+    // any kernel family keeps them).
+    size_t staging = align256((size_t)M * (size_t)r_total * 4) + 256;
+    if (op == LR_OP_PACKED_MLP) staging += align256((size_t)M * (size_t)d_out * 4) + 256;
+    return kFrontBytes + staging + sk_tail_bytes(M);
 }
 
 }  // namespace lr
@@ -95,20 +94,37 @@ size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total,
 int lowrank_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
     if (!workspace) { set_error("workspace is NULL"); return LR_ERR_NULL; }
     if (((uintptr_t)workspace) & 255u) { set_error("workspace must be 256-byte aligned"); return LR_ERR_ALIGN; }
-    return fill_zero(workspace, workspace_bytes & ~(size_t)3, (hipStream_t)stream);
+    if (workspace_bytes < kFrontBytes) { set_error("workspace too small: %zu bytes given, every workspace has at least %zu", workspace_bytes, (size_t)kFrontBytes); return LR_ERR_WORKSPACE; }
+    // zero-fill the part that carries state (the ready word included), then let the preparation launches mark it ready
+    int st = fill_zero(workspace, kHeaderBytes + kSkFlagBytes, (hipStream_t)stream);
+    if (st != LR_OK) return st;
+    return ws_prepare(workspace, (hipStream_t)stream);
 }
 
 int lowrank_workspace_status(const void* workspace, void* stream) {
     if (!workspace) { set_error("workspace is NULL"); return LR_ERR_NULL; }
     Ctrl c;
     hipStream_t s = (hipStream_t)stream;
-    if (hipMemcpyAsync(&c, workspace, sizeof(Ctrl), hipMemcpyDeviceToHost, s) != hipSuccess ||
+    if (hipMemcpyAsync(&c, workspace, 128, hipMemcpyDeviceToHost, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) {
         set_error("workspace status: copy failed: %s", hipGetErrorString(hipGetLastError()));
         return LR_ERR_LAUNCH;
     }
-    if (c.error != 0) { set_error("a device-side wait between stages gave up; results of that call are invalid, re-initialise the workspace"); return LR_ERR_LAUNCH; }
+    if (c.magic == kCtrlReady && c.error != 0) {
+        set_error("a device-side wait between stages gave up; the results of that call are NaN and the workspace must be prepared again (lowrank_workspace_init)");
+        return LR_ERR_LAUNCH;
+    }
     return LR_OK;
+}
+
+int lowrank_configure(int option, int64_t value) {
+    switch (option) {
+        case LR_CFG_DEVICE_SHARED: g_device_shared = value != 0; return LR_OK;
+        case LR_CFG_WAIT_LIMIT:
+            if (value < 0 || value > (int64_t)0x7fffffff) { set_error("wait limit out of range"); return LR_ERR_SHAPE; }
+            g_wait_limit = (uint32_t)value; return LR_OK;
+        default: set_error("unknown option %d", option); return LR_ERR_UNSUPPORTED;
+    }
 }
 
 const char* lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,

@@ -370,7 +370,6 @@ int attn_decode(const void* q, const lr_kv_target* kv, void* out, float scale, f
     if (fast) {
         // about two workgroups per CU, at most kAttnMaxSplit per (row, head)
         int ns = (int)((512 + M * H - 1) / (M * H));
-        { static const char* e = getenv("LOWRANK_ATTN_SPLITS"); if (e) ns = atoi(e); }
         a.NS = ns < 1 ? 1 : (ns > kAttnMaxSplit ? kAttnMaxSplit : ns);
         a.qscale = scale * 1.4426950408889634f;
         const bool fused = kv->tokens_per_seq == 1;

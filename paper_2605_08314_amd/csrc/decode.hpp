@@ -27,58 +27,68 @@ struct DProb {
 template <int NP> struct DStageT { DProb p[NP]; int nprob, M, total_tiles; };
 typedef DStageT<kMaxProb> DStage;
 
-// Control block at the start of every workspace (zero when prepared).  A stage barrier is kSlots
-// counters on separate 128-byte lines: workgroup w adds 1 to slot w % kSlots, a waiting wave reads
-// all slots with one load instruction.  One hot counter for 256 workgroups costs several
-// microseconds per barrier on this chip; sixteen cool ones cost about one.
+// Control block at the start of every workspace.  A stage barrier is kSlots counters on separate 128-byte lines:
+// workgroup w adds 1 to slot w % kSlots, a waiting wave reads all slots with one load instruction.  One hot counter
+// for 256 workgroups costs several microseconds per barrier on this chip; sixteen cool ones cost about one.
+//
+// `magic` says whether the block is valid.  A workspace may arrive with any contents (fresh allocation): the first
+// kernel that needs the block and does not find kCtrlReady there prepares it itself (one wave wins a compare-and-swap
+// to kCtrlBusy, zeroes the block, the shared-K flags and both accumulator areas, and publishes kCtrlReady; everyone
+// else waits for that), so no host-side initialisation is required and a graph replay never depends on one.
 constexpr int kBarriers = 3;
 constexpr int kSlots = 16;
 constexpr int kSlotStride = 32;   // uint32 words between slots (128 bytes)
 constexpr int kTileCounters = 256;
+constexpr uint64_t kCtrlReady = 0x6c72776b73703031ull;
+constexpr uint64_t kCtrlBusy = 0x6c72776b73703030ull;
 struct Ctrl {
+    uint64_t magic;                     // kCtrlReady: everything below and the accumulator areas are in their between-calls state
     uint32_t epoch;                     // number of fused calls completed on this workspace
-    uint32_t error;                     // nonzero: a bounded device-side wait gave up
+    uint32_t error;                     // nonzero: a bounded device-side wait gave up; stays set until the workspace is prepared again
     uint32_t dirty[2];                  // floats of accumulator area p that are not zero
-    uint32_t pad[28];
+    uint32_t pad[26];
     uint32_t cnt[2][kBarriers][kSlots * kSlotStride];   // [epoch parity][barrier][slot]
     uint32_t tcnt[2][kTileCounters];                    // arrivals per accumulator column tile (bf16 finalisation)
 };
 static_assert(sizeof(Ctrl) <= kHeaderBytes, "control block must fit the workspace header");
 
-// Tail of a workspace that may serve a prefill call (more than 32 token rows): flags and fp32 partial
-// tiles of products whose K range is shared between workgroups (256 slots of one 256 x 256 tile, or
-// 512 of 128 x 128).  Zero when prepared; every call leaves the flags zero.
+// Workspace layout.  Everything that carries state from one call to the next sits at a FIXED offset, whatever the
+// call's shape or row count, so calls of any kind may follow each other on one workspace:
+//   [0, 16 KiB)            control block
+//   [16 KiB, 20 KiB)       flags of prefill products whose K range is shared between workgroups (zero between calls)
+//   then 8 MiB             fp32 partial tiles of decode split-K stages with bf16 finalisation (scratch)
+//   then 2 x 4 MiB         accumulator areas 0 and 1 of the fused decode kernels (zero between calls up to `dirty`)
+//   then                   staging: scratch of the call (rank-space rows, hidden rows), sized by the call
+//   last 64 MiB            only when the call has more than 32 rows: fp32 partial tiles of shared-K prefill products
 constexpr size_t kSkFlagBytes = 4096;
 constexpr size_t kSkSlotBytes = (size_t)256 * 256 * 256 * 4;
-constexpr size_t kSkBytes = kSkFlagBytes + kSkSlotBytes;
-// Tail of a decode workspace for 9..32 token rows: fp32 partial tiles of the split-K stages (one slot per
-// workgroup tile; the last K-slice of a column tile to arrive adds them up in slice order and writes bf16).
 constexpr size_t kDecPartBytes = (size_t)8 << 20;
+constexpr size_t kAccBytes = (size_t)4 << 20;
+constexpr size_t kFrontBytes = kHeaderBytes + kSkFlagBytes + kDecPartBytes + 2 * kAccBytes;
 // More token rows than this may use split-K partial tiles in slots + bf16 finalisation instead of atomics (the packed MLP
-// does from 9 rows on, the two-stage calls from 25: measured cross-over points), so the workspace has the tail for them.
+// does from 9 rows on, the two-stage calls from 25: measured cross-over points).
 constexpr int kT16Rows = 8;
-inline size_t sk_tail_bytes(int64_t M) { return M > 32 ? kSkBytes : (M > kT16Rows ? kDecPartBytes : 0); }
+inline size_t sk_tail_bytes(int64_t M) { return M > 32 ? kSkSlotBytes : 0; }
 
-// Where the parts of a workspace of `ws_bytes` bytes for M token rows sit:
-// header | acc area 0 | acc area 1 | staging | tail (decode partial tiles for 8 < M <= 32, shared-K area for M > 32).
 struct WsLayout {
-    Ctrl* ctrl; char* acc0; size_t acc_bytes; char* staging; size_t staging_bytes;
-    uint32_t* sk_flags; float* sk_slots;       // prefill tail (M > 32), else NULL
-    float* dec_part;                           // decode partial tiles (8 < M <= 32), else NULL
+    Ctrl* ctrl; uint32_t* sk_flags; float* dec_part;
+    char* acc0; size_t acc_bytes;              // area 1 = acc0 + acc_bytes
+    char* staging; size_t staging_bytes;
+    float* sk_slots;                           // calls with more than 32 rows, else NULL
 };
 inline WsLayout ws_layout(void* ws, size_t ws_bytes, int64_t M) {
     WsLayout L;
+    char* b = (char*)ws;
+    L.ctrl = (Ctrl*)b;
+    L.sk_flags = (uint32_t*)(b + kHeaderBytes);
+    L.dec_part = (float*)(b + kHeaderBytes + kSkFlagBytes);
+    L.acc0 = b + kHeaderBytes + kSkFlagBytes + kDecPartBytes;
+    L.acc_bytes = kAccBytes;
+    L.staging = b + kFrontBytes;
     const size_t tail = sk_tail_bytes(M);
-    const size_t body = ws_bytes - tail;
-    L.ctrl = (Ctrl*)ws;
-    L.acc_bytes = ((body - kHeaderBytes) / 4) & ~(size_t)255;
-    L.acc0 = (char*)ws + kHeaderBytes;
-    L.staging = L.acc0 + 2 * L.acc_bytes;
-    L.staging_bytes = body - kHeaderBytes - 2 * L.acc_bytes;
-    char* t = (char*)ws + (body & ~(size_t)255);
-    L.sk_flags = M > 32 ? (uint32_t*)t : nullptr;
-    L.sk_slots = M > 32 ? (float*)(t + kSkFlagBytes) : nullptr;
-    L.dec_part = (M > kT16Rows && M <= 32) ? (float*)t : nullptr;
+    const size_t end = (ws_bytes - tail) & ~(size_t)255;
+    L.staging_bytes = end - kFrontBytes;
+    L.sk_slots = tail ? (float*)(b + end) : nullptr;
     return L;
 }
 
@@ -87,7 +97,7 @@ struct FusedCommon {
     char* acc0;              // accumulator area 0; area 1 = acc0 + acc_bytes
     size_t acc_bytes;
     uint32_t dirty_floats;   // floats of the accumulator area this call adds into
-    uint32_t reserved;
+    uint32_t spin_limit;     // polls after which a device-wide wait gives up
     unsigned long long* trace;   // timeline buffer of trace builds, else NULL
 };
 template <int NP> struct Fused2Args { FusedCommon fc; DStageT<NP> s1, s2; };
@@ -99,7 +109,11 @@ int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& 
                          int grid, int nw, bool t16, hipStream_t s);
 int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, int nw, bool t16, hipStream_t s);
 extern unsigned long long* g_trace_buffer;   // host copy of the trace pointer (NULL unless a trace build set it)
-int decode_resident_grid();   // workgroups that are certainly co-resident (number of CUs), cached
+int decode_resident_grid();   // workgroups that are certainly co-resident (number of CUs), cached; 0 when the device is shared
+// Process-wide settings behind lowrank_configure.
+extern bool g_device_shared;        // other work may occupy CUs: no launch may rely on all of its workgroups being resident
+extern uint32_t g_wait_limit;       // polls after which a device-side wait gives up
+int ws_prepare(void* ws, hipStream_t s);   // enqueue the check-and-prepare launches (calls that run no fused decode kernel)
 
 // Launch one stage: cpl = bf16 columns per lane (4 or 8), a_f32 = activations are fp32 (rank-space
 // accumulators) rather than bf16, epi = EPI_*.

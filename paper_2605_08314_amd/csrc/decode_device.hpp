@@ -125,16 +125,20 @@ __device__ __forceinline__ void mma_block(f32x4_t (&acc)[MB][CPL], const WFrag<C
     }
 }
 
-// Hook run between the first weight loads of a tile and its first activation loads.
+// Hook run between the first weight loads of a tile and its first activation loads.  Its argument receives the
+// workspace's error word when the hook is the wait in front of a call's last stage (read right after the wait, used in
+// the epilogue: any workgroup that gave up anywhere in the launch raised that word before it arrived at the barrier
+// just passed, so the whole result turns NaN, not only the failing workgroup's part).
 // kCoherent: the activation rows were produced earlier in this launch by other workgroups and are read with
 // agent-coherent loads; kFused: hidden rows written by this tile are read by other workgroups of this launch.
-struct NoSync { static constexpr bool kCoherent = false, kFused = false; __device__ __forceinline__ void operator()() const {} };
+struct NoSync { static constexpr bool kCoherent = false, kFused = false; __device__ __forceinline__ void operator()(uint32_t&) const {} };
 // Same, for later tiles of a stage whose input other workgroups of this launch produced.
-struct NoSyncCoherent { static constexpr bool kCoherent = true, kFused = true; __device__ __forceinline__ void operator()() const {} };
+struct NoSyncCoherent { static constexpr bool kCoherent = true, kFused = true; __device__ __forceinline__ void operator()(uint32_t&) const {} };
 // Later tiles of a stage whose input (accumulators added with device-scope atomics, hidden rows or a finalised bf16
 // copy written with device-coherent stores) no workgroup on this XCD has read before the stage's barrier in this
 // launch: plain cached loads are safe (first touch misses L2) and let the other workgroups hit in L2.
-struct NoSyncPlain { static constexpr bool kCoherent = false, kFused = true; __device__ __forceinline__ void operator()() const {} };
+struct NoSyncPlain { static constexpr bool kCoherent = false, kFused = true; __device__ __forceinline__ void operator()() const {}
+                     __device__ __forceinline__ void operator()(uint32_t&) const {} };
 
 // This wave's share of rows [32*kb0, 32*kb1) of W: blocks kb0 + wave, kb0 + wave + NW, ...
 // The first PF weight blocks are requested before `sync()` runs and the activations after it, so
@@ -142,7 +146,7 @@ struct NoSyncPlain { static constexpr bool kCoherent = false, kFused = true; __d
 template <int MB, int CPL, bool AF32, int PF, int NW, class Sync>
 __device__ __forceinline__ void mma_range(f32x4_t (&acc)[MB][CPL], const bf16_t* __restrict__ W, int N,
                                           const void* A, int lda, int M, int col, int kb0, int kb1,
-                                          int wave, int j, int g, const Sync& sync) {
+                                          int wave, int j, int g, const Sync& sync, uint32_t& late_err) {
     WFrag<CPL> wf[PF];
     AFrag<AF32> af[PF][MB];
     int blk = kb0 + wave;
@@ -151,7 +155,7 @@ __device__ __forceinline__ void mma_range(f32x4_t (&acc)[MB][CPL], const bf16_t*
         const int bb = blk + NW * p;
         if (bb < kb1) load_w<CPL>(wf[p], W, N, 32 * bb + 8 * g, col);
     }
-    sync();
+    sync(late_err);
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
         const int bb = blk + NW * p;
@@ -184,7 +188,7 @@ template <int MB, int CPL, bool AF32, int PF, int NW, class Sync>
 __device__ __forceinline__ void mma_range2(f32x4_t (&acc1)[MB][CPL], f32x4_t (&acc2)[MB][CPL],
                                            const bf16_t* __restrict__ W, const bf16_t* __restrict__ W2, int N,
                                            const void* A, const void* A2, int lda, int lda2, int M, int col, int nb1, int nb2,
-                                           int wave, int j, int g, const Sync& sync) {
+                                           int wave, int j, int g, const Sync& sync, uint32_t& late_err) {
     WFrag<CPL> wf[PF];
     AFrag<AF32> af[PF][MB];
     const int nv = nb1 + nb2;
@@ -197,7 +201,7 @@ __device__ __forceinline__ void mma_range2(f32x4_t (&acc1)[MB][CPL], f32x4_t (&a
             else         load_w<CPL>(wf[p], W2, N, 32 * (v - nb1) + 8 * g, col);
         }
     }
-    sync();
+    sync(late_err);
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
         const int v = blk + NW * p;
@@ -251,7 +255,8 @@ __device__ __forceinline__ void load_bf16_row(float (&v)[CPL], const bf16_t* src
 // One workgroup tile, from loads to epilogue.  `red` is LDS scratch of red_floats<...>() floats.
 template <int MB, int CPL, bool AF32, int EPI, int PF, int NW, class Sync>
 __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float4* __restrict__ red,
-                                            const Sync& sync, size_t acc_shift, uint32_t* tcnt = nullptr) {
+                                            const Sync& sync, const size_t& acc_shift, uint32_t* const& tcnt = nullptr,
+                                            const uint32_t* poison = nullptr) {
     constexpr int NMAT = (EPI == EPI_GATEUP) ? 2 : 1;
     constexpr int NC = 16 * CPL;
     constexpr int Q = CPL / 4;
@@ -260,6 +265,7 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
     const int n0 = tn * NC;
     const int col = n0 + CPL * j;
 
+    uint32_t late_err = 0u;
     f32x4_t acc[NMAT][MB][CPL];
 #pragma unroll
     for (int mt = 0; mt < NMAT; ++mt)
@@ -273,20 +279,20 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
         int kb1 = kb0 + (P.KS >> 5);
         if (kb1 > (P.K >> 5)) kb1 = P.K >> 5;
         const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
-        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, kb0, kb1, wave, j, g, sync);
+        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, kb0, kb1, wave, j, g, sync, late_err);
     } else if constexpr (MB == 1) {
         const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
         const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
         mma_range2<MB, CPL, AF32, PF, NW>(acc[0], acc[NMAT - 1], P.W, P.W2, P.N, A, A2, P.lda, P.lda2, M, col, P.K >> 5, P.K2 >> 5,
-                                          wave, j, g, sync);
+                                          wave, j, g, sync, late_err);
     } else {
         // two 16-row blocks per wave: one product after the other (measured: the joint sequence is 1.2 us slower at 32 rows)
         const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
         const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
-        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, 0, P.K >> 5, wave, j, g, sync);
-        if constexpr (Sync::kCoherent) mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncCoherent());
-        else if constexpr (Sync::kFused) mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncPlain());
-        else mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSync());
+        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, 0, P.K >> 5, wave, j, g, sync, late_err);
+        if constexpr (Sync::kCoherent) mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncCoherent(), late_err);
+        else if constexpr (Sync::kFused) mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncPlain(), late_err);
+        else mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSync(), late_err);
     }
 
     // cross-wave reduction through LDS: red[wave][slot = (mat*MB + mb)*4 + v][q][lane]
@@ -303,6 +309,8 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
                         make_float4(acc[mt][mb][4 * q + 0][v], acc[mt][mb][4 * q + 1][v],
                                     acc[mt][mb][4 * q + 2][v], acc[mt][mb][4 * q + 3][v]);
     __syncthreads();
+    // a call whose device-wide wait gave up (or whose workspace carries an earlier failure) delivers NaN, never plausible numbers
+    const bool nan_out = (EPI == EPI_STORE) && poison != nullptr && (*poison != 0u || late_err != 0u);
     float atomic_returns = 0.f;
 #pragma unroll
     for (int pidx = tid; pidx < 256 * MB; pidx += 64 * NW) {   // (mb, v, lane') triples
@@ -340,6 +348,10 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
                 for (int b = 0; b < CPL; ++b) atomic_returns += unsafeAtomicAdd(c + b, val[0][b]);
                 }
             } else if constexpr (EPI == EPI_STORE) {
+                if (nan_out) {
+#pragma unroll
+                    for (int b = 0; b < CPL; ++b) val[0][b] = __uint_as_float(0x7fc00000u);
+                }
                 if (P.bias) {
                     float bv[CPL];
                     load_bf16_row<CPL>(bv, P.bias + n);
@@ -371,6 +383,9 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
         }
     }
     if constexpr (EPI == EPI_ATOMIC) asm volatile("" ::"v"(atomic_returns));   // every atomic above has returned
+    if constexpr (EPI == EPI_STORE) {
+        if (poison != nullptr && late_err != 0u && tid == 0) *const_cast<uint32_t*>(poison) = 1u;   // later tiles of this workgroup see it too
+    }
 
     // bf16 finalisation of a split-K stage (larger row counts, chosen by the host planner): the workgroup whose K-slice of this column
     // tile arrives last adds up all slices' partial tiles and writes the tile as bf16 once, so that the next
@@ -449,22 +464,24 @@ __global__ void __launch_bounds__(256) k_decode_stage(DStage st) {
     for (int i = 1; i < kMaxProb; ++i)
         if (i < st.nprob && tile >= st.p[i].tile_begin) pi = i;
     const DProb& P = st.p[pi];
-    decode_tile<MB, CPL, AF32, EPI, PF, 4>(P, st.M, tile - P.tile_begin, red, NoSync(), 0);
+    const size_t no_shift = 0;
+    decode_tile<MB, CPL, AF32, EPI, PF, 4>(P, st.M, tile - P.tile_begin, red, NoSync(), no_shift);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Fused decode calls: all stages of one entry point in ONE launch.  The grid is small enough for
-// every workgroup to be resident at once (host checks this against the occupancy of the kernel),
-// stages are separated by a device-wide arrive/wait counter in the workspace control block, and
-// a workgroup asks for the first weight blocks of its next tile BEFORE it waits, so HBM keeps
-// streaming across the dependency.  Waiting is bounded: after kSpinLimit polls the workgroup sets
-// the control block's error word and carries on (wrong results, reported by
-// lowrank_workspace_status), so every wave always reaches the end of the kernel.
+// every workgroup to be resident at once when the device runs nothing else, stages are separated by a
+// device-wide arrive/wait counter in the workspace control block, and a workgroup asks for the first
+// weight blocks of its next tile BEFORE it waits, so HBM keeps streaming across the dependency.
+// Waiting is bounded: after `spin_limit` polls the workgroup sets the control block's error word, marks
+// itself poisoned and carries on without further waits; a poisoned workgroup writes NaN as its results,
+// and the error word (watched by every waiting wave, checked at the start of every later call) poisons
+// all other workgroups and all later calls on that workspace, so that a failure cannot pass for a
+// result.  Every wave always reaches the end of the kernel.
 //
 // Split-K accumulators live in one of two areas picked by the parity of the control block's epoch;
 // while a call accumulates into area p it clears what the previous call dirtied in area 1-p, and
-// the last workgroup to arrive at the first barrier publishes epoch+1 and the new dirty extents.
-constexpr uint32_t kSpinLimit = 1u << 20;
+// workgroup 0, once it has seen the first barrier complete, publishes epoch+1 and the new dirty extents.
 
 // Optional timeline of the fused kernels (builds with -DLR_TRACE only; never in the shipped library):
 // thread 0 of every workgroup stores the 100 MHz wall clock at numbered points.
@@ -478,6 +495,92 @@ constexpr uint32_t kSpinLimit = 1u << 20;
 __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ uint64_t ld_agent64(const uint64_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---- control block: start of a call -------------------------------------------------------------------
+// Three 8-byte device-coherent reads {magic} {epoch, error} {dirty[0], dirty[1]}, issued at the top of the
+// kernel; nothing waits on them until ctrl_resolve, which a wave calls once its first weight blocks are on
+// their way.
+struct CtrlLoads { uint2 m, e, d; };
+struct CtrlSnap { uint32_t epoch, p, dirty_other, error; };
+
+__device__ __forceinline__ CtrlLoads ctrl_issue(const Ctrl* c) {
+    CtrlLoads L;
+    L.m = ld_coherent_b64(&c->magic);
+    L.e = ld_coherent_b64(&c->epoch);
+    L.d = ld_coherent_b64(&c->dirty[0]);
+    return L;
+}
+
+constexpr uint32_t kPrepareSpinLimit = 1u << 24;
+
+// Rare path (first call on a workspace that nobody prepared): one wave of the whole launch wins the right to
+// prepare, everyone else waits for kCtrlReady.  Wave-uniform; returns false if the wait gave up.
+__device__ __noinline__ bool ctrl_prepare(const FusedCommon& fc, uint64_t observed) {
+    Ctrl* c = fc.ctrl;
+    const int lane = threadIdx.x & 63;
+    uint32_t won = 0;
+    if (lane == 0 && observed != kCtrlBusy) {
+        uint64_t expect = observed;
+        won = __hip_atomic_compare_exchange_strong(&c->magic, &expect, kCtrlBusy, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT) ? 1u : 0u;
+    }
+    won = __builtin_amdgcn_readfirstlane(won);
+    if (won) {
+        // header behind the magic word + shared-K flags (contiguous), then both accumulator areas
+        uint2* h = reinterpret_cast<uint2*>(c) + 1;
+        const uint32_t n8 = (uint32_t)((kHeaderBytes + kSkFlagBytes) / 8 - 1);
+        for (uint32_t i = lane; i < n8; i += 64) h[i] = make_uint2(0u, 0u);
+        uint4* a = reinterpret_cast<uint4*>(fc.acc0);
+        const uint32_t n16 = (uint32_t)(2 * fc.acc_bytes / 16);
+        for (uint32_t i = lane; i < n16; i += 64) a[i] = make_uint4(0u, 0u, 0u, 0u);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");             // the zeroes are in memory before the word says so
+        if (lane == 0) __hip_atomic_store(&c->magic, kCtrlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return true;
+    }
+    uint32_t spins = 0;
+    bool ok = true;
+    while (__builtin_amdgcn_readfirstlane((uint32_t)(ld_agent64(&c->magic) == kCtrlReady)) == 0u) {
+        if (++spins > kPrepareSpinLimit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(8);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return ok;
+}
+
+// Wave-uniform.  `bad` (LDS word of the workgroup) is raised when the workspace carries an earlier failure.
+__device__ __forceinline__ CtrlSnap ctrl_resolve(const FusedCommon& fc, CtrlLoads L, uint32_t* bad) {
+    const uint64_t magic = (uint64_t)L.m.x | ((uint64_t)L.m.y << 32);
+    if (__builtin_amdgcn_readfirstlane((uint32_t)(magic != kCtrlReady)) != 0u) {
+        const bool ok = ctrl_prepare(fc, magic);
+        L = ctrl_issue(fc.ctrl);
+        if (!ok) {
+            if ((threadIdx.x & 63) == 0) { __hip_atomic_store(&fc.ctrl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); *bad = 1u; }
+        }
+    }
+    CtrlSnap c;
+    c.epoch = L.e.x; c.error = L.e.y; c.p = L.e.x & 1u;
+    c.dirty_other = c.p ? L.d.x : L.d.y;
+    if (c.error != 0u && (threadIdx.x & 63) == 0) *bad = 1u;
+    return c;
+}
+
+// Hook of the first tile of a call's first stage: resolves the control block (and with it the parity of the
+// accumulator areas) between the tile's first weight requests and its epilogue.
+struct CtrlGate {
+    static constexpr bool kCoherent = false, kFused = false;
+    const FusedCommon* fc; const CtrlLoads* loads; CtrlSnap* snap; size_t* shift;
+    uint32_t** tcnt; bool t16;      // tile counters of the call's parity (bf16 finalisation), else NULL
+    uint32_t* bad;
+    __device__ __forceinline__ void operator()(uint32_t&) const { (*this)(); }
+    __device__ __forceinline__ void operator()() const {
+        *snap = ctrl_resolve(*fc, *loads, bad);
+        *shift = (size_t)snap->p * fc->acc_bytes;
+        *tcnt = t16 ? fc->ctrl->tcnt[snap->p] : nullptr;
+    }
+};
 
 // Stage barrier.  Data shared inside a launch is only touched by atomics and by agent-coherent
 // loads / stores, so no cache maintenance is needed: it is enough that every wave has drained its
@@ -497,23 +600,37 @@ struct GridWait {
     const uint32_t* slots;
     uint32_t grid;
     uint32_t* err;
+    uint32_t spin_limit;
+    uint32_t* bad;          // LDS word of the workgroup: a wait gave up, or the error word was seen set
     int stamp;
     unsigned long long* trace;
+    bool last;              // the wait in front of the call's last stage: hand the error word to the epilogue
+    __device__ __forceinline__ void operator()(uint32_t& late_err) const {
+        (*this)();
+        if (last) late_err = ld_agent(err);
+    }
     __device__ __forceinline__ void operator()() const {
-        if (threadIdx.x < 64) {     // wave 0: lane s < kSlots watches slot s
+        if (threadIdx.x < 64) {     // wave 0: lane s < kSlots watches slot s, lane kSlots watches the error word
             const uint32_t lane = threadIdx.x;
             const uint32_t want = lane < kSlots ? (grid + kSlots - 1 - lane) / kSlots : 0u;   // workgroups with w % kSlots == lane
-            const uint32_t* p = slots + (lane < kSlots ? lane : 0u) * kSlotStride;
+            const uint32_t* p = lane < kSlots ? slots + lane * kSlotStride : (lane == kSlots ? err : slots);
             uint32_t spins = 0;
-            while (true) {
-                const bool ok = ld_agent(p) >= want;
-                if (__builtin_amdgcn_ballot_w64(!ok) == 0ull) break;
-                if (++spins > kSpinLimit) {
-                    if (lane == 0) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            bool poisoned = __builtin_amdgcn_readfirstlane(*bad) != 0u;
+            while (!poisoned) {
+                const uint32_t v = ld_agent(p);
+                if (__builtin_amdgcn_ballot_w64(lane == kSlots && v != 0u) != 0ull) { poisoned = true; break; }
+                if (__builtin_amdgcn_ballot_w64(lane < kSlots && v < want) == 0ull) break;
+                if (++spins > spin_limit) {
+                    // returning atomic, consumed: the word is set where every workgroup sees it before this one moves on
+                    uint32_t old = 0u;
+                    if (lane == 0) old = __hip_atomic_exchange(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    asm volatile("" ::"v"(old));
+                    poisoned = true;
                     break;
                 }
                 __builtin_amdgcn_s_sleep(1);
             }
+            if (poisoned && lane == 0) *bad = 1u;
         }
         __syncthreads();
         LR_STAMP_TO(trace, stamp);
@@ -525,18 +642,6 @@ struct GridWaitPlain : GridWait {
     static constexpr bool kCoherent = false, kFused = true;
     __device__ __forceinline__ GridWaitPlain(const GridWait& g) : GridWait(g) {}
 };
-
-// Start of every fused kernel: ONE 16-byte read of {epoch, error, dirty[0], dirty[1]}; nothing waits
-// on it until the first epilogue needs the parity.
-struct CtrlSnap { uint32_t epoch, p, dirty_other; };
-__device__ __forceinline__ CtrlSnap fused_begin(const FusedCommon& fc) {
-    const uint2 a = ld_coherent_b64(&fc.ctrl->epoch);      // epoch, error
-    const uint2 d = ld_coherent_b64(&fc.ctrl->dirty[0]);
-    CtrlSnap c;
-    c.epoch = a.x; c.p = a.x & 1u;
-    c.dirty_other = c.p ? d.x : d.y;
-    return c;
-}
 
 // Clear what the previous call left in the other accumulator area and the other parity's barrier
 // counters (nobody uses them during this call).  Called by every workgroup before its first arrive.
@@ -583,26 +688,35 @@ template <int MB, int CPL1, int CPL2, int PF, int NP, int NW, bool T16>
 __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     constexpr int R1 = red_float4s<MB, CPL1, EPI_ATOMIC, NW>(), R2 = red_float4s<MB, CPL2, EPI_STORE, NW>();
     __shared__ float4 red[R1 > R2 ? R1 : R2];
-    const CtrlSnap cs = fused_begin(fa.fc);
-    const uint32_t p = cs.p;
-    const size_t shift = (size_t)p * fa.fc.acc_bytes;
+    __shared__ uint32_t s_bad;
+    const CtrlLoads cl = ctrl_issue(fa.fc.ctrl);
+    if (threadIdx.x == 0) s_bad = 0u;
+    __syncthreads();
+    CtrlSnap cs;
+    size_t shift = 0;
+    uint32_t* tcp = nullptr;
+    const CtrlGate gate = {&fa.fc, &cl, &cs, &shift, &tcp, T16, &s_bad};
+    bool resolved = false;
     for (int tile = blockIdx.x; tile < fa.s1.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s1, tile);
-        decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift,
-                                                         T16 ? fa.fc.ctrl->tcnt[p] : nullptr);
+        if (!resolved) decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, gate, shift, tcp);
+        else           decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift, tcp);
+        resolved = true;
         __syncthreads();
     }
+    if (!resolved) gate();
+    const uint32_t p = cs.p;
     fused_first_arrive(fa.fc, cs);
-    const GridWait gw = {fa.fc.ctrl->cnt[p][0], gridDim.x, &fa.fc.ctrl->error, 3, fa.fc.trace};
+    const GridWait gw = {fa.fc.ctrl->cnt[p][0], gridDim.x, &fa.fc.ctrl->error, fa.fc.spin_limit, &s_bad, 3, fa.fc.trace, true};
     bool waited = false;
     for (int tile = blockIdx.x; tile < fa.s2.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s2, tile);
         if constexpr (T16) {
-            if (!waited) decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift);
-            else         decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift);
+            if (!waited) decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+            else         decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
         } else {
-            if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift);
-            else         decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift);
+            if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+            else         decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
         }
         if (!waited) fused_publish(fa.fc, cs);
         waited = true;
@@ -618,23 +732,33 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
     constexpr int RC = red_float4s<MB, CPLC, EPI_ATOMIC, NW>(), RD = red_float4s<MB, CPLD, EPI_STORE, NW>();
     constexpr int R01 = RA > RB ? RA : RB, R23 = RC > RD ? RC : RD;
     __shared__ float4 red[R01 > R23 ? R01 : R23];
-    const CtrlSnap cs = fused_begin(fa.fc);
-    const uint32_t p = cs.p;
-    const size_t shift = (size_t)p * fa.fc.acc_bytes;
+    __shared__ uint32_t s_bad;
+    const CtrlLoads cl = ctrl_issue(fa.fc.ctrl);
+    if (threadIdx.x == 0) s_bad = 0u;
+    __syncthreads();
+    CtrlSnap cs;
+    size_t shift = 0;
+    uint32_t* tcp = nullptr;
+    const CtrlGate gate = {&fa.fc, &cl, &cs, &shift, &tcp, T16, &s_bad};
     const uint32_t G = gridDim.x;
-    uint32_t (*cnt)[kSlots * kSlotStride] = fa.fc.ctrl->cnt[p];
     LR_STAMP(0);
     // A: t_gu += x U_gu
+    bool resolved = false;
     for (int tile = blockIdx.x; tile < fa.a.total_tiles; tile += G) {
-        decode_tile<MB, CPLA, false, EPI_ATOMIC, PF, NW>(fa.a.p[0], fa.a.M, tile, red, NoSync(), shift, T16 ? fa.fc.ctrl->tcnt[p] : nullptr);
+        if (!resolved) decode_tile<MB, CPLA, false, EPI_ATOMIC, PF, NW>(fa.a.p[0], fa.a.M, tile, red, gate, shift, tcp);
+        else           decode_tile<MB, CPLA, false, EPI_ATOMIC, PF, NW>(fa.a.p[0], fa.a.M, tile, red, NoSync(), shift, tcp);
+        resolved = true;
         __syncthreads();
     }
+    if (!resolved) gate();
+    const uint32_t p = cs.p;
+    uint32_t (*cnt)[kSlots * kSlotStride] = fa.fc.ctrl->cnt[p];
     LR_STAMP(1);
     fused_first_arrive(fa.fc, cs);
     LR_STAMP(2);
     // B: h = SiLU(t_g V_g + b_g) * (t_u V_u + b_u)
     {
-        const GridWait gw = {cnt[0], G, &fa.fc.ctrl->error, 3, fa.fc.trace};
+        const GridWait gw = {cnt[0], G, &fa.fc.ctrl->error, fa.fc.spin_limit, &s_bad, 3, fa.fc.trace, false};
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.b.total_tiles; tile += G) {
             if constexpr (T16) {
@@ -655,12 +779,11 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
     LR_STAMP(5);
     // C: t_d += h U_d
     {
-        const GridWait gw = {cnt[1], G, &fa.fc.ctrl->error, 6, fa.fc.trace};
+        const GridWait gw = {cnt[1], G, &fa.fc.ctrl->error, fa.fc.spin_limit, &s_bad, 6, fa.fc.trace, false};
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.c.total_tiles; tile += G) {
-            uint32_t* tc = T16 ? fa.fc.ctrl->tcnt[p] : nullptr;
-            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, GridWaitPlain(gw), shift, tc);
-            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncPlain(), shift, tc);
+            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, GridWaitPlain(gw), shift, tcp);
+            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncPlain(), shift, tcp);
             waited = true;
             __syncthreads();
         }
@@ -670,15 +793,15 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
     LR_STAMP(8);
     // D: out = t_d V_d + b_d
     {
-        const GridWait gw = {cnt[2], G, &fa.fc.ctrl->error, 9, fa.fc.trace};
+        const GridWait gw = {cnt[2], G, &fa.fc.ctrl->error, fa.fc.spin_limit, &s_bad, 9, fa.fc.trace, true};
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.d.total_tiles; tile += G) {
             if constexpr (T16) {
-                if (!waited) decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift);
-                else         decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift);
+                if (!waited) decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+                else         decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift, nullptr, &s_bad);
             } else {
-                if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift);
-                else         decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift);
+                if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+                else         decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift, nullptr, &s_bad);
             }
             waited = true;
             __syncthreads();

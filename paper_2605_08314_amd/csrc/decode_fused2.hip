@@ -24,7 +24,6 @@ static int launch_f2(const FusedCommon& fc, const DStage& s1, const DStage& s2, 
 template <int MB, int NP>
 static int launch_f2_cpl(const FusedCommon& fc, const DStage& s1, const DStage& s2, int c1, int c2, int grid, int nw, bool t16, hipStream_t s) {
     if (c1 == 4 && c2 == 4) return launch_f2<MB, 4, 4, NP>(fc, s1, s2, grid, nw, t16, s);
-    if (c1 == 8 && c2 == 4) return launch_f2<MB, 8, 4, NP>(fc, s1, s2, grid, nw, t16, s);
     set_error("bad decode tile configuration");
     return LR_ERR_UNSUPPORTED;
 }
@@ -40,15 +39,15 @@ int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& 
 }
 
 int decode_resident_grid() {
+    // A fused launch needs every workgroup resident at the same time.  Each fused kernel is compiled for at least one
+    // workgroup per CU, so one per CU is resident -- provided nothing else occupies CUs, which the caller vouches for
+    // (lowrank_configure(LR_CFG_DEVICE_SHARED, 1) withdraws that and selects one launch per stage).
+    if (g_device_shared) return 0;
     static int cached = 0;
     if (cached > 0) return cached;
-    const char* dry = getenv("LOWRANK_DECODE_DRYRUN");     // host-side tests of the plans: no device needed
-    if (dry && *dry && atoi(dry) != 0) return 256;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 0;
-    // every fused kernel is compiled for at least one 256-thread workgroup per CU; one per CU is
-    // therefore always resident when the device runs nothing else
     cached = cus;
     return cached;
 }

@@ -17,8 +17,7 @@ static int launch_mlp(const FusedMlpArgs& fa, int grid, int nw, bool t16, hipStr
 
 template <int MB>
 static int launch_mlp_cpl(const FusedMlpArgs& fa, int ca, int cc, int cd, int grid, int nw, bool t16, hipStream_t s) {
-    if (cd != 4 || ca != cc) { set_error("bad decode tile configuration"); return LR_ERR_UNSUPPORTED; }
-    if (ca == 8) return launch_mlp<MB, 8, 8, 4>(fa, grid, nw, t16, s);
+    if (cd != 4 || ca != 4 || cc != 4) { set_error("bad decode tile configuration"); return LR_ERR_UNSUPPORTED; }
     return launch_mlp<MB, 4, 4, 4>(fa, grid, nw, t16, s);
 }
 

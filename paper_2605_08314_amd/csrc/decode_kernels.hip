@@ -24,9 +24,7 @@ int decode_launch_stage(const DStage& st, int cpl, bool a_f32, int epi, hipStrea
     if (st.total_tiles <= 0 || st.M <= 0) return LR_OK;
     const int mb = st.M <= 16 ? 1 : 2;
     if (mb == 1 && cpl == 4) return launch_stage_cfg<1, 4>(st, a_f32, epi, s);
-    if (mb == 1 && cpl == 8) return launch_stage_cfg<1, 8>(st, a_f32, epi, s);
     if (mb == 2 && cpl == 4) return launch_stage_cfg<2, 4>(st, a_f32, epi, s);
-    if (mb == 2 && cpl == 8) return launch_stage_cfg<2, 8>(st, a_f32, epi, s);
     set_error("bad decode tile configuration");
     return LR_ERR_UNSUPPORTED;
 }

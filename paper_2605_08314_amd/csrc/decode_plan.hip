@@ -4,16 +4,13 @@
 #include <stdlib.h>
 #include <string.h>
 #include "decode.hpp"
-#include "decode_ring.hpp"
 
 namespace lr {
 
 unsigned long long* g_trace_buffer = nullptr;
 
-static int env_int(const char* name, int dflt) {
-    const char* v = getenv(name);
-    return (v && *v) ? atoi(v) : dflt;
-}
+bool g_device_shared = false;
+uint32_t g_wait_limit = 1u << 20;
 
 // Fast-path shape rule: rows ride on one or two 16-row MFMA blocks, K in 32-row blocks, N in
 // 64-column tiles.
@@ -22,27 +19,22 @@ bool decode_shape_ok(int64_t M, int64_t K, int64_t N) {
            K < (1 << 24) && N < (1 << 24);
 }
 
-// Columns per lane of a stage whose matrices all have N % 128 == 0 (else 4): 4 = 64-column tiles
-// with 8-byte loads (more, smaller tiles), 8 = 128-column tiles with 16-byte loads.
-static int pick_cpl(bool all128) {
-    return (env_int("LOWRANK_DECODE_CPL", 4) == 8 && all128) ? 8 : 4;
-}
+// Columns per lane of every stage: 4 = 64-column tiles with 8-byte loads.  (128-column tiles with 16-byte loads
+// were measured slower: fewer, fatter tiles.)
+constexpr int kCpl = 4;
+// Tiles of a split-K stage that runs as a launch of its own (device shared with other work, or accumulators too big).
+constexpr int kUnfusedTiles = 512;
 
 // Split-K stage: rows of W per tile so that the stage has about `want_tiles` tiles.  Multiples of
 // 32 rows, at least 128 (one block per wave); at least 256 for more than 8 token rows, which keeps
 // the fp32 atomics (tiles_k * M * N) small against the weight bytes.
 static int pick_ks(int64_t K, int64_t tiles_n_total, int64_t M, int64_t want_tiles) {
-    const int forced = env_int("LOWRANK_DECODE_KS", 0);
-    int64_t ks;
-    if (forced >= 32 && forced % 32 == 0) ks = forced;
-    else {
-        int64_t tk = want_tiles / (tiles_n_total > 0 ? tiles_n_total : 1);
-        if (tk < 1) tk = 1;
-        ks = (K + tk - 1) / tk;
-        ks = ((ks + 31) / 32) * 32;
-        const int64_t floor_ks = M > 8 ? 256 : 128;
-        if (ks < floor_ks) ks = floor_ks;
-    }
+    int64_t tk = want_tiles / (tiles_n_total > 0 ? tiles_n_total : 1);
+    if (tk < 1) tk = 1;
+    int64_t ks = (K + tk - 1) / tk;
+    ks = ((ks + 31) / 32) * 32;
+    const int64_t floor_ks = M > 8 ? 256 : 128;
+    if (ks < floor_ks) ks = floor_ks;
     if (ks > K) ks = K;
     return (int)ks;
 }
@@ -90,16 +82,13 @@ static int build_final(DStage& st, const Final* items, int n, int64_t ldt, int64
     return cpl;
 }
 
-// One launch per call unless LOWRANK_DECODE_FUSED=0 or the device query fails.  The grid is one
+// One launch per call unless the device is shared with other work (lowrank_configure) or the device query fails.  The grid is one
 // workgroup per ~96 KB of factor bytes, between 64 and the number of CUs: a stage barrier costs more
 // the more workgroups take part, and a 6 MB call (one O projection) gains nothing from 256 of them
 // (measured: 8.1 us at 64 workgroups, 9.8 us at 256), while 18 MB and more want the whole chip.
 static int fused_grid(size_t factor_bytes) {
-    if (env_int("LOWRANK_DECODE_FUSED", 1) == 0) return 0;
     const int cus = decode_resident_grid();
     if (cus <= 0) return 0;
-    const int forced = env_int("LOWRANK_DECODE_GRID", 0);
-    if (forced > 0 && forced <= cus) return forced;
     size_t g = factor_bytes / (96u << 10);
     if (g < 64) g = 64;
     if (g > (size_t)cus) g = (size_t)cus;
@@ -111,22 +100,7 @@ static int fused_grid(size_t factor_bytes) {
 // 32.7 / 31.7 at 12, 36.0 / 32.6 at 16, 52.8 / 44.7 at 32; QKV 11.7 / 13.2 at 12, 12.9 / 13.5 at 16, 15.1 / 15.0 at 24,
 // 16.2 / 15.9 at 32; O projection 9.4 / 10.0 at 12, 11.2 / 11.7 at 24, 12.1 / 12.6 at 32.
 static bool use_t16(int64_t M, int64_t col_tiles, int min_rows) {
-    const int rows = env_int("LOWRANK_DECODE_T16_ROWS", min_rows);
-    return M > rows && M > kT16Rows && col_tiles <= kTileCounters && env_int("LOWRANK_DECODE_T16", 1) != 0;
-}
-
-// Up to 16 token rows, at most four products per stage, 64-column tiles: the streaming kernel (factor bytes
-// through an LDS ring, requested across the stage barriers).  LOWRANK_DECODE_RING=0 keeps the older kernels.
-static bool ring_wanted(int64_t M, int cpl) {
-    return M <= 16 && cpl == 4 && env_int("LOWRANK_DECODE_RING", 0) != 0;
-}
-static int ring_rows(int64_t M) { int a = 1; while (a < M) a *= 2; return a; }
-static bool ring_stage(RStage& r, const DStage& st, int epi, int a_kind, bool finalise) {
-    if (st.nprob > kRingProbs) return false;
-    memset(&r, 0, sizeof(r));
-    for (int i = 0; i < st.nprob; ++i) r.p[i] = st.p[i];
-    r.nprob = st.nprob; r.total_tiles = st.total_tiles; r.epi = epi; r.a_kind = a_kind; r.finalise = finalise ? 1 : 0;
-    return true;
+    return M > min_rows && M > kT16Rows && col_tiles <= kTileCounters;
 }
 
 static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* sk_in, int nb, const Final* fin_in,
@@ -137,12 +111,10 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
     for (int i = 0; i < nf; ++i) factor_bytes += (size_t)fin_in[i].r * fin_in[i].N * 2;
     const int G = fused_grid(factor_bytes);
     const bool fused = G > 0 && (size_t)M * R * 4 <= L.acc_bytes;
-    bool all128 = true;
-    for (int i = 0; i < nb; ++i) all128 = all128 && (sk_in[i].N % 128 == 0);
-    const int c1 = pick_cpl(all128);
+    const int c1 = kCpl;
     // bf16 finalisation of t needs a slot of the workspace's partial-tile area for every tile of stage 1
     const size_t slot1 = (size_t)(M > 16 ? 32 : 16) * 16 * c1 * 4;
-    bool t16 = fused && use_t16(M, R / (16 * c1), 24) && L.dec_part;
+    bool t16 = fused && use_t16(M, R / (16 * c1), 24);
     float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* t16base = (bf16_t*)L.staging;                       // [M, R] bf16 (fused launches only)
     SplitK sk[kMaxProb]; Final fin[kMaxProb];
@@ -158,22 +130,14 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
             fin[i] = fin_in[i]; fin[i].T = t16 ? (const void*)(t16base + off) : (const void*)(tbase + off);
         }
         int ctile = 0;
-        build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : env_int("LOWRANK_DECODE_TILES", 512), c1, &ctile);
+        build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : kUnfusedTiles, c1, &ctile);
         if (!t16 || (size_t)s1.total_tiles * slot1 <= kDecPartBytes) break;
         t16 = false;                                            // too many tiles for the area: accumulate with atomics instead
     }
     const int c2 = build_final(s2, fin, nf, R, M);
     if (fused) {
-        FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, t16 ? 0u : (uint32_t)(M * R), 0u, g_trace_buffer};   // t16: nothing is accumulated in place
-        if (ring_wanted(M, c1) && c2 == 4) {
-            RingArgs ra;
-            ra.fc = fc; ra.nstages = 2; ra.M = (int)M; ra.a_rows = ring_rows(M);
-            const char* why = "";
-            if (ring_stage(ra.st[0], s1, EPI_ATOMIC, RA_BF16_PLAIN, t16) &&
-                ring_stage(ra.st[1], s2, EPI_STORE, t16 ? RA_BF16_PLAIN : RA_F32_COHERENT, false) && ring_args_ok(ra, G, &why))
-                return decode_launch_ring(ra, G, s);
-        }
-        return decode_launch_fused2(fc, s1, s2, c1, c2, G, env_int("LOWRANK_DECODE_WAVES", 8) == 4 ? 4 : 8, t16, s);
+        FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, t16 ? 0u : (uint32_t)(M * R), g_wait_limit, g_trace_buffer};   // t16: nothing is accumulated in place
+        return decode_launch_fused2(fc, s1, s2, c1, c2, G, 8, t16, s);
     }
     int st = fill_zero(tbase, (size_t)M * R * 4, s);
     if (st != LR_OK) return st;
@@ -219,11 +183,11 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     float* t = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* h = fused ? (bf16_t*)L.staging : (bf16_t*)(L.staging + align256((size_t)M * r_all * 4));
     bf16_t* t16 = (bf16_t*)(L.staging + align256((size_t)M * ffn * 2));
-    const int64_t want = fused ? G : env_int("LOWRANK_DECODE_TILES", 512);
+    const int64_t want = fused ? G : kUnfusedTiles;
     DStage sa, sb, sc, sd;
-    const int ca = pick_cpl(r_gu % 128 == 0 && r_d % 128 == 0), cc = ca;   // both split-K stages share one tile width
+    const int ca = kCpl, cc = ca;   // both split-K stages share one tile width
     const size_t slot = (size_t)(M > 16 ? 32 : 16) * 16 * ca * 4;      // bytes of one partial tile
-    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca), 8) && L.dec_part;
+    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca), 8);
     SplitK a, c;
     for (int attempt = 0; attempt < 2; ++attempt) {
         int ctile = 0;
@@ -248,25 +212,14 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     Final f = {use16 ? (const void*)(t16 + r_gu) : (const void*)(t + r_gu), r_d, V_d, d, b_d, out, {nullptr, nullptr, 0, 1}};
     const int cd = build_final(sd, &f, 1, r_all, M);
     if (fused) {
-        if (ring_wanted(M, ca) && cd == 4) {
-            RingArgs ra;
-            ra.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, use16 ? 0u : (uint32_t)(M * r_all), 0u, g_trace_buffer};
-            ra.nstages = 4; ra.M = (int)M; ra.a_rows = ring_rows(M);
-            const int act = use16 ? RA_BF16_PLAIN : RA_F32_COHERENT;
-            const char* why = "";
-            if (ring_stage(ra.st[0], sa, EPI_ATOMIC, RA_BF16_PLAIN, use16) && ring_stage(ra.st[1], sb, EPI_GATEUP, act, false) &&
-                ring_stage(ra.st[2], sc, EPI_ATOMIC, RA_BF16_COHERENT, use16) && ring_stage(ra.st[3], sd, EPI_STORE, act, false) &&
-                ring_args_ok(ra, G, &why))
-                return decode_launch_ring(ra, G, s);
-        }
         FusedMlpArgs fa;
-        fa.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, use16 ? 0u : (uint32_t)(M * r_all), 0u, g_trace_buffer};
+        fa.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, use16 ? 0u : (uint32_t)(M * r_all), g_wait_limit, g_trace_buffer};
         const DStage* src[4] = {&sa, &sb, &sc, &sd};
         DStageT<1>* dst[4] = {&fa.a, &fa.b, &fa.c, &fa.d};
         for (int i = 0; i < 4; ++i) { dst[i]->p[0] = src[i]->p[0]; dst[i]->nprob = 1; dst[i]->M = (int)M; dst[i]->total_tiles = src[i]->total_tiles; }
         // 17..32 rows: two 16-row MFMA blocks per wave; with 4 waves per workgroup the kernel has the registers for them
         // (at 8 waves it spills), measured 45.6 against 47.8 us at 32 rows.  Up to 16 rows 8 waves are faster.
-        return decode_launch_fused_mlp(fa, ca, cc, cd, G, env_int("LOWRANK_DECODE_WAVES", M > 16 ? 4 : 8) == 4 ? 4 : 8, use16, s);
+        return decode_launch_fused_mlp(fa, ca, cc, cd, G, M > 16 ? 4 : 8, use16, s);
     }
     int st = fill_zero(t, (size_t)M * r_all * 4, s);
     if (st != LR_OK) return st;

@@ -2,6 +2,7 @@
 // alignment in both element types and are the fallback under the tuned decode / prefill
 // kernels.  fp32 calls accumulate in fp64, bf16 calls in fp32.
 #include "lr_common.hpp"
+#include "decode.hpp"
 
 namespace lr {
 
@@ -140,6 +141,32 @@ int generic_pack_concat(const void* const* U_list, const int64_t* r_list, int n,
         col += r_list[i];
     }
     return LR_OK;
+}
+
+// Check-and-prepare for calls that run no fused decode kernel but use flags in the workspace (prefill products that
+// share K): when the control block does not carry the ready word, every workgroup zeroes its slice of the control block,
+// the flags and the accumulator areas; a second single-thread launch then writes the word (stream order makes it the
+// last write).  Two tiny launches; nothing is copied back and nothing waits.
+__global__ void __launch_bounds__(256) k_ws_prepare_zero(char* ws) {
+    const Ctrl* c = reinterpret_cast<const Ctrl*>(ws);
+    if (__hip_atomic_load(&c->magic, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == kCtrlReady) return;
+    uint2* head = reinterpret_cast<uint2*>(ws) + 1;                               // behind the magic word
+    const size_t n_head = (kHeaderBytes + kSkFlagBytes) / 8 - 1;
+    uint4* acc = reinterpret_cast<uint4*>(ws + kHeaderBytes + kSkFlagBytes + kDecPartBytes);
+    const size_t n_acc = 2 * kAccBytes / 16;
+    const size_t tid = (size_t)blockIdx.x * 256 + threadIdx.x, nth = (size_t)gridDim.x * 256;
+    for (size_t i = tid; i < n_head; i += nth) head[i] = make_uint2(0u, 0u);
+    for (size_t i = tid; i < n_acc; i += nth) acc[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+__global__ void k_ws_prepare_mark(Ctrl* c) {
+    if (__hip_atomic_load(&c->magic, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != kCtrlReady)
+        __hip_atomic_store(&c->magic, kCtrlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+int ws_prepare(void* ws, hipStream_t s) {
+    hipLaunchKernelGGL(k_ws_prepare_zero, dim3(128), dim3(256), 0, s, (char*)ws);
+    hipLaunchKernelGGL(k_ws_prepare_mark, dim3(1), dim3(1), 0, s, (Ctrl*)ws);
+    return launch_status("workspace preparation");
 }
 
 int fill_zero(void* p, size_t bytes, hipStream_t s) {

@@ -29,6 +29,7 @@ struct PArgs {
     uint32_t* sk_flags; float* sk_slots; uint32_t* err;
     int sk;             // 1: the launch walks k-step ranges, not tiles
     int sk_nk;          // k-steps (of 32) per tile in that case
+    uint32_t sk_spin_limit;   // polls after which the holder of a shared tile stops waiting for a partial sum
 };
 
 bool prefill_shape_ok(int64_t M, int64_t K, int64_t N);

@@ -483,14 +483,14 @@ __device__ __forceinline__ void store_partial(const f32x16_t (&acc)[BM / 64][BN 
 }
 
 // Bounded wait for a flag another workgroup of this launch sets; on giving up the error word of the
-// workspace is set and the caller carries on (wrong results, reported by lowrank_workspace_status).
-constexpr uint32_t kSkSpinLimit = 1u << 22;
-__device__ __forceinline__ void sk_wait_flag(const uint32_t* flag, uint32_t* err) {
+// workspace is set (lowrank_workspace_status reports it) and the caller writes NaN into the tile it could not finish.
+__device__ __forceinline__ bool sk_wait_flag(const uint32_t* flag, uint32_t* err, uint32_t limit) {
     uint32_t spins = 0;
     while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-        if (++spins > kSkSpinLimit) { __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
+        if (++spins > limit) { __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); return false; }
         __builtin_amdgcn_s_sleep(2);
     }
+    return true;
 }
 
 // Dense-cache rows.  A span of consecutive token rows that touches at most two sequences is described by
@@ -542,7 +542,7 @@ template <int BM, int BN, int EPI, bool SK = false>
 __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN / 64],
                                               const f32x16_t (&acc2)[(EPI == PEPI_GATEUP) ? BM / 64 : 1][(EPI == PEPI_GATEUP) ? BN / 64 : 1],
                                               const PProb& P, int M, int m0, int n0, char* patch, int wave, int lane,
-                                              const float* parts = nullptr, int part0 = 0, int part1 = 0) {
+                                              const float* parts = nullptr, int part0 = 0, int part1 = 0, float poison = 0.f) {
     // parts: partial tiles of slots [part0, part1) are added (shared-K owner), skipping empty ones
     constexpr int MI = BM / 64, NI = BN / 64;
     // the lane index goes through an opaque move: everything derived from it is recomputed here, per
@@ -602,7 +602,7 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
 #pragma unroll
                 for (int vg = 0; vg < 4; ++vg)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) psum[p2][vg][e] = 0.f;
+                    for (int e = 0; e < 4; ++e) psum[p2][vg][e] = poison;      // NaN when a partial sum never arrived
             if constexpr (SK) {
                 for (int c = part0; c < part1; c += 3) {
                     uint2 raw[3][2][4][2];
@@ -745,12 +745,18 @@ __global__ void __launch_bounds__(256, MINB) k_prefill_persist(PArgs pa) {
                     const int tile_end = (cw.next / pa.sk_nk + 1) * pa.sk_nk;   // cw.next == end of this range, inside the tile
                     int c1 = wl + 1;
                     while (c1 < (int)gridDim.x && sk_unit_begin(pa, c1) < tile_end) ++c1;
-                    if (tid == 0)
+                    uint32_t* gave_up = reinterpret_cast<uint32_t*>(lds) + (persist_lds_bytes<BM, BN>() / 4 - 1);   // last word of wave 3's patch: free here
+                    if (tid == 0) {
+                        bool ok = true;
                         for (int c = wl + 1; c < c1; ++c)
-                            if (sk_unit_begin(pa, c + 1) > sk_unit_begin(pa, c)) sk_wait_flag(pa.sk_flags + c, pa.err);
+                            if (sk_unit_begin(pa, c + 1) > sk_unit_begin(pa, c)) ok = sk_wait_flag(pa.sk_flags + c, pa.err, pa.sk_spin_limit) && ok;
+                        *gave_up = ok ? 0u : 1u;
+                    }
                     __builtin_amdgcn_s_barrier();
+                    const float poison = *gave_up ? __uint_as_float(0x7fc00000u) : 0.f;
+                    __builtin_amdgcn_s_barrier();                 // everyone has read the word before wave 3 reuses its patch
                     // (the launcher sizes the grid so that no range is empty: every slot in [wl + 1, c1) is fresh)
-                    wave_epilogue<BM, BN, EPI, true>(acc, acc2, P, pa.M, sg.m0, sg.n0, patch, wave, lane, pa.sk_slots, wl + 1, c1);
+                    wave_epilogue<BM, BN, EPI, true>(acc, acc2, P, pa.M, sg.m0, sg.n0, patch, wave, lane, pa.sk_slots, wl + 1, c1, poison);
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // partial sums have been read
                     __builtin_amdgcn_s_barrier();
                     if (tid == 0)
@@ -785,7 +791,7 @@ static int launch_persist(PArgs a, hipStream_t s, bool share_k = false) {
     // row tiles per group of the tile walk (a group's tiles are visited row-fastest): 8, and 2 for the gate/up kernel,
     // whose tiles carry two B operands (measured 393 -> 373 us on the benchmark's layer)
     a.group_m = EPI == PEPI_GATEUP ? 2 : 8;
-    { const char* e = getenv("LOWRANK_PREFILL_GROUPM"); if (e && atoi(e) > 0) a.group_m = atoi(e); }     // measurement override
+    a.sk_spin_limit = g_wait_limit < (1u << 20) ? g_wait_limit : (1u << 22);     // these polls sleep longer than the decode ones
     a.trace = g_trace_buffer;
     a.sk = 0; a.sk_nk = 0;
     int grid = 0;
@@ -817,11 +823,6 @@ static int launch_persist(PArgs a, hipStream_t s, bool share_k = false) {
     return launch_status("prefill gemm");
 }
 
-static int env_int(const char* name) { const char* v = getenv(name); return v ? atoi(v) : -1; }
-static int env_shape() { static int v = env_int("LOWRANK_PREFILL_SHAPE"); return v; }
-static int env_gu() { static int v = env_int("LOWRANK_PREFILL_GU"); return v; }
-static int env_sk() { static int v = env_int("LOWRANK_PREFILL_SHAREK"); return v; }
-
 // Tile shape of a plain launch, from a small cost model fitted to measurements on this chip, in units of "one
 // 256 x 256 tile on one CU": the 256-row kernels (one workgroup per CU) take one unit per round for 256
 // columns and 0.75 for 192; the 128 x 128 kernel needs 0.46 for its quarter-size tile when every tile has a CU
@@ -848,9 +849,7 @@ static int pick_tile(const PArgs& a) {
 // shared; with K = 4096 the hand-over of partial tiles and the lost L2 reuse (workgroups of one XCD
 // are no longer at the same k) cost more than the better balance brings, so those stay tiled.
 static bool want_share_k(const PArgs& a) {
-    if (env_sk() == 0) return false;
-    if (!a.sk_slots || !one_shape(a)) return false;
-    if (env_sk() == 1) return true;
+    if (!a.sk_slots || !one_shape(a) || g_device_shared) return false;     // the hand-over needs all workgroups resident
     const long t256 = (long)a.nprob * ((a.M + 255) / 256) * ((a.p[0].N + 255) / 256);
     const long nk = a.p[0].K / 32;
     return t256 <= 128 && t256 * nk / 256 >= 96;
@@ -873,22 +872,11 @@ void prefill_plan_query(int64_t M, int64_t K, int64_t N, int n, bool gateup, int
 
 int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
     if (a.M <= 0 || a.nprob <= 0) return LR_OK;
-    if (epi == PEPI_GATEUP) {
-        if (env_gu() == 0) return launch_persist<256, 128, PEPI_GATEUP, 1>(a, s);
-        return launch_persist<128, 128, PEPI_GATEUP, 2>(a, s);
-    }
-    switch (env_shape()) {      // measurement override
-        case 0: return launch_persist<256, 256, PEPI_STORE, 1>(a, s, env_sk() == 1);
-        case 1: return launch_persist<128, 128, PEPI_STORE, 2>(a, s, env_sk() == 1);
-        case 2: return launch_persist<256, 128, PEPI_STORE, 1>(a, s);
-        case 3: return launch_persist<128, 256, PEPI_STORE, 1>(a, s);
-        case 4: return launch_persist<256, 192, PEPI_STORE, 1>(a, s, env_sk() == 1);
-        default: break;
-    }
+    if (epi == PEPI_GATEUP) return launch_persist<128, 128, PEPI_GATEUP, 2>(a, s);
     if (want_share_k(a)) {
         // 192-wide tiles when they cover the columns exactly: more, aligned pieces of the K range per row block
         // (N = 768: four column tiles x two halves of K = eight workgroups per row block, all on one XCD)
-        if (a.p[0].N % 192 == 0 && env_int("LOWRANK_PREFILL_SK192") != 0) return launch_persist<256, 192, PEPI_STORE, 1>(a, s, true);
+        if (a.p[0].N % 192 == 0) return launch_persist<256, 192, PEPI_STORE, 1>(a, s, true);
         return launch_persist<256, 256, PEPI_STORE, 1>(a, s, true);
     }
     switch (pick_tile(a)) {

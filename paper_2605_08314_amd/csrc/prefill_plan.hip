@@ -20,6 +20,7 @@ int prefill_qkv(const void* x, const void* const* U, const void* const* V, const
                 void* ws, size_t ws_bytes, hipStream_t s) {
     const WsLayout L = ws_layout(ws, ws_bytes, M);
     bf16_t* T = (bf16_t*)L.staging;                 // [M, R] bf16
+    if (int pst = ws_prepare(ws, s); pst != LR_OK) return pst;      // shared-K flags and the error word must be valid
     PArgs a1; init_pargs(a1, M, L);
     for (int i = 0; i < n_proj; ++i) {
         if (base_of[i] != i) continue;
@@ -60,6 +61,7 @@ int prefill_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_
     const WsLayout L = ws_layout(ws, ws_bytes, M);
     bf16_t* T = (bf16_t*)L.staging;                                         // [M, r_g + r_u + r_d] bf16
     bf16_t* H = (bf16_t*)(L.staging + align256((size_t)M * r_all * 2));     // [M, ffn] bf16
+    if (int pst = ws_prepare(ws, s); pst != LR_OK) return pst;      // shared-K flags and the error word must be valid
     PArgs a; init_pargs(a, M, L); a.nprob = 1;
     {   // T_gu = x U_gu
         PProb& p = a.p[0]; zero_pprob(p);

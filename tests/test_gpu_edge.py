@@ -43,7 +43,7 @@ def test_degenerate_sizes(G, oracle, dtype):
     B = G.B
     td = G.tdtype(dtype)
     rng = np.random.default_rng(5)
-    ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    ws = B.new_workspace(B.LR_OP_LINEAR, 4, 64, 8, 32, G.code(dtype))
     # M == 0: no-op, output untouched
     x0 = torch.empty((0, 64), dtype=td, device="cuda")
     U, V = G.dev(rand_t(rng, (64, 8), dtype)), G.dev(rand_t(rng, (8, 32), dtype))
@@ -236,8 +236,7 @@ def test_mixed_calls_share_one_workspace(G, oracle):
     ta, tm = wa.t, wm.t
     nbytes = max(B.lowrank_workspace_bytes(B.LR_OP_QKV, 8, 1024, 384, 3072, B.LR_BF16, "decode"),
                  B.lowrank_workspace_bytes(B.LR_OP_PACKED_MLP, 8, 1024, 576, 2816, B.LR_BF16, "decode"))
-    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    B.lowrank_workspace_init(ws)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 256)     # never prepared: the first call does it
     x = G.dev(ta["x"])
     Us, Vs = [G.dev(ta["U_" + n]) for n in "qkv"], [G.dev(ta["V_" + n]) for n in "qkv"]
     mlp_w = [G.dev(tm[n]) for n in ("U_gu", "V_g", "V_u", "U_d", "V_d")]
@@ -269,8 +268,7 @@ def test_alternating_inputs_on_one_workspace(G, oracle, M):
     B = G.B
     ws_n = max(B.lowrank_workspace_bytes(B.LR_OP_QKV, M, 1024, 384, 3072, B.LR_BF16, "decode"),
                B.lowrank_workspace_bytes(B.LR_OP_PACKED_MLP, M, 1024, 576, 2816, B.LR_BF16, "decode"))
-    ws = torch.empty(ws_n, dtype=torch.uint8, device="cuda")
-    B.lowrank_workspace_init(ws)
+    ws = torch.empty(ws_n, dtype=torch.uint8, device="cuda").random_(0, 256)      # never prepared: the first call does it
     sets = []
     for k in range(2):
         wa = synth.attention_layer(M, d=1024, r=128, n_heads=8, S_max=8, seed=70 + k)
@@ -303,7 +301,7 @@ def test_error_codes(G):
     with pytest.raises(B.LowrankError) as e:
         B.lowrank_linear(x, U, V, None, y, "decode", small)
     assert e.value.status == -6 and "workspace" in str(e.value)
-    ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    ws = B.new_workspace(B.LR_OP_LINEAR, 4, 64, 8, 64, B.LR_BF16)
     with pytest.raises(B.LowrankError) as e:
         B.lowrank_linear(x, U, V, None, y, 7, ws)
     assert e.value.status == -5
@@ -407,24 +405,114 @@ def test_prefill_linear_shape_sweep(G, oracle, shape):
     assert max_rel_err(got[rows], want) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("M", [1, 3, 8, 11, 16])
-def test_streaming_decode_kernel_opt_in(G, oracle, monkeypatch, M):
-    """LOWRANK_DECODE_RING=1 routes decode calls of up to 16 rows through the streaming kernel (factor blocks through
-    LDS rings, requested across the stage barriers).  Same bar as the default kernels; run twice on one workspace
-    (epoch parity, counters), with the host-side walk check on."""
-    monkeypatch.setenv("LOWRANK_DECODE_RING", "1")
-    monkeypatch.setenv("LOWRANK_DECODE_CHECK", "1")
-    w = synth.mlp_layer(M, d=1024, ffn=2816, r_g=192, r_u=320, r_d=128, seed=4242 + M, dtype="bf16", with_bias=True)
+# ------------------------------------------------------------------ workspace contract
+def _mlp_case(M, seed):
+    w = synth.mlp_layer(M, d=1024, ffn=2816, r_g=192, r_u=192, r_d=192, seed=seed)
     t = w.t
-    want = oracle.packed_mlp(t["x"].f64, t["U_gu"].f64, t["V_g"].f64, t["V_u"].f64, t["U_d"].f64, t["V_d"].f64,
-                             t["b_g"].f64, t["b_u"].f64, t["b_d"].f64)
-    for _ in range(2):
-        out = G.run_mlp(w, "decode")
-        assert max_rel_err(G.host64(out), want) <= TOL["bf16"]
-    rng = np.random.default_rng(77 + M)
-    x = rand_t(rng, (M, 1024), "bf16")
-    U = rand_t(rng, (1024, 192), "bf16", 1024 ** -0.5)
-    V = rand_t(rng, (192, 2048), "bf16", 192 ** -0.5)
-    b = rand_t(rng, (2048,), "bf16")
-    y = G.run_linear(x, U, V, b, "decode", "bf16")
-    assert max_rel_err(G.host64(y), oracle.linear(x.f64, U.f64, V.f64, b.f64)) <= TOL["bf16"]
+    return ([t[n] for n in ("x", "U_gu", "V_g", "V_u", "U_d", "V_d")],
+            lambda o: o.packed_mlp(*[t[n].f64 for n in ("x", "U_gu", "V_g", "V_u", "U_d", "V_d")]))
+
+
+def test_row_counts_change_on_one_workspace(G, oracle):
+    """One workspace sized for the largest batch serves calls whose row count crosses every internal threshold
+    (atomics / bf16 finalisation at 8|9 rows, one / two row blocks at 16|17, decode / prefill at 32|33), in an order in
+    which a layout that moved with the row count would add onto stale sums: 12, 12, 4, 12, then a prefill call and a
+    decode call after it.  Every result is checked against the oracle."""
+    B = G.B
+    nbytes = B.lowrank_workspace_bytes(B.LR_OP_PACKED_MLP, 300, 1024, 576, 2816, B.LR_BF16, "auto")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 256)
+    cases = {M: _mlp_case(M, 900 + M) for M in (12, 4, 32, 300, 17, 1)}
+    dev = {M: [G.dev(a) for a in cases[M][0]] for M in cases}
+    want = {M: cases[M][1](oracle) for M in cases}
+    for M in (12, 12, 4, 12, 300, 12, 32, 17, 300, 1, 12):
+        x, U_gu, V_g, V_u, U_d, V_d = dev[M]
+        out = torch.full((M, 1024), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.lowrank_packed_mlp(x, U_gu, V_g, V_u, U_d, V_d, None, None, None, out, "auto", ws)
+        B.lowrank_workspace_status(ws)
+        assert max_rel_err(G.host64(out), want[M]) <= TOL["bf16"], M
+    # the two-stage entry point on the same buffer, rows 25 (bf16 finalisation) then 3 (atomics) then 25
+    wa = synth.attention_layer(25, d=1024, r=128, n_heads=8, S_max=8, seed=931).t
+    x, U, V = G.dev(wa["x"]), G.dev(wa["U_q"]), G.dev(wa["V_q"])
+    wantl = oracle.linear(wa["x"].f64, wa["U_q"].f64, wa["V_q"].f64)
+    for M in (25, 3, 25):
+        y = torch.full((M, 1024), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.lowrank_linear(x[:M].contiguous(), U, V, None, y, "decode", ws)
+        B.lowrank_workspace_status(ws)
+        assert max_rel_err(G.host64(y), wantl[:M]) <= TOL["bf16"], M
+
+
+@pytest.mark.parametrize("M", [1, 12, 300])
+def test_unprepared_workspace_with_arbitrary_contents(G, oracle, M):
+    """A workspace straight from the allocator, filled with 0xFF bytes, random bytes, or the 'being prepared' word
+    left behind by nobody: the first call prepares it on the stream and returns correct results, a second call reuses it."""
+    B = G.B
+    args, want_fn = _mlp_case(M, 950 + M)
+    dev = [G.dev(a) for a in args]
+    want = want_fn(oracle)
+    nbytes = B.lowrank_workspace_bytes(B.LR_OP_PACKED_MLP, M, 1024, 576, 2816, B.LR_BF16, "auto")
+    for fill in ("ff", "random", "zero"):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        if fill == "ff":
+            ws.fill_(255)
+        elif fill == "random":
+            ws.random_(0, 256)
+        else:
+            ws.zero_()
+        for _ in range(2):
+            out = torch.full((M, 1024), float("nan"), dtype=torch.bfloat16, device="cuda")
+            B.lowrank_packed_mlp(*dev, None, None, None, out, "auto", ws)
+            B.lowrank_workspace_status(ws)
+            assert max_rel_err(G.host64(out), want) <= TOL["bf16"], fill
+
+
+def test_device_shared_setting_uses_one_launch_per_stage(G, oracle):
+    """lowrank_configure(LR_CFG_DEVICE_SHARED, 1): no launch depends on co-resident workgroups; same results."""
+    B = G.B
+    args, want_fn = _mlp_case(8, 970)
+    dev = [G.dev(a) for a in args]
+    ws = B.new_workspace(B.LR_OP_PACKED_MLP, 8, 1024, 576, 2816, B.LR_BF16)
+    B.lowrank_configure(B.LR_CFG_DEVICE_SHARED, 1)
+    try:
+        out = torch.full((8, 1024), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.lowrank_packed_mlp(*dev, None, None, None, out, "decode", ws)
+        B.lowrank_workspace_status(ws)
+        wa = synth.attention_layer(8, d=1024, r=128, n_heads=8, S_max=8, seed=971).t
+        y = G.run_linear(wa["x"], wa["U_q"], wa["V_q"], None, "decode", "bf16")
+    finally:
+        B.lowrank_configure(B.LR_CFG_DEVICE_SHARED, 0)
+    assert max_rel_err(G.host64(out), want_fn(oracle)) <= TOL["bf16"]
+    assert max_rel_err(G.host64(y), oracle.linear(wa["x"].f64, wa["U_q"].f64, wa["V_q"].f64)) <= TOL["bf16"]
+
+
+def test_wait_that_gives_up_poisons_results_and_is_reported(G, oracle):
+    """The bounded device-side wait is made to give up from the host (a limit of zero polls: a workgroup that does not
+    find the barrier complete at its first look stops waiting), so every kernel still runs to its end.  The call must
+    not deliver plausible numbers: the workgroups that gave up write NaN, the status call reports the failure, every
+    later call on that workspace returns NaN only, and preparing the workspace again restores normal service."""
+    B = G.B
+    args, want_fn = _mlp_case(4, 980)
+    dev = [G.dev(a) for a in args]
+    want = want_fn(oracle)
+    ws = B.new_workspace(B.LR_OP_PACKED_MLP, 4, 1024, 576, 2816, B.LR_BF16)
+    def call():
+        out = torch.zeros((4, 1024), dtype=torch.bfloat16, device="cuda")
+        B.lowrank_packed_mlp(*dev, None, None, None, out, "decode", ws)
+        torch.cuda.synchronize()
+        return G.host64(out)
+    assert max_rel_err(call(), want) <= TOL["bf16"]
+    B.lowrank_configure(B.LR_CFG_WAIT_LIMIT, 0)
+    try:
+        got = call()
+    finally:
+        B.lowrank_configure(B.LR_CFG_WAIT_LIMIT, 1 << 20)
+    assert np.isnan(got).any()                                   # at least the workgroups that gave up
+    ok = ~np.isnan(got)
+    if ok.any():                                                 # whoever did pass every barrier had complete inputs
+        assert np.max(np.abs(got[ok] - want[ok])) <= TOL["bf16"] * np.max(np.abs(want))
+    with pytest.raises(B.LowrankError) as e:
+        B.lowrank_workspace_status(ws)
+    assert e.value.status == -7
+    assert np.isnan(call()).all()                                # the failure sticks to the workspace
+    B.lowrank_workspace_init(ws)
+    assert max_rel_err(call(), want) <= TOL["bf16"]
+    B.lowrank_workspace_status(ws)
