@@ -93,6 +93,20 @@ int lowrank_linear(const void *x, const void *U, const void *V, const void *bias
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * lowrank_linear for callers that cannot provide or allocate a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same operation and same results to rounding; the rank-space rows
+ * live in a 512 KiB scratch area built into the library image (one copy per GPU, held until the process ends), so
+ * M * r may be at most 131072 (e.g. 32 rows at rank 4096); larger calls return LR_ERR_WORKSPACE and launch nothing.
+ * Nothing is allocated or freed, here or in any routine it calls.  Up to 32 rows of bf16 with aligned operands run the
+ * decode kernels as one launch per stage (no cross-workgroup waits, so no residency requirement); every other call
+ * runs the generic kernels.  All calls on one GPU share that GPU's scratch area: calls that overlap in time on one
+ * GPU race, even on different streams; order them.  The area is cleared on the stream at the start of each call.
+ */
+int lowrank_linear_noalloc(const void *x, const void *U, const void *V, const void *bias /* nullable */,
+                           void *y, int64_t M, int64_t d_in, int64_t r, int64_t d_out,
+                           int dtype /* lr_dtype */, void *stream);
+
+/*
  * Where the K and V projections of lowrank_qkv are written besides `out` (Section 3.1,
  * second paragraph: a standard dense KV cache; layout [batch, position, head, head_dim]).
  * The M rows of x are B sequences of tokens_per_seq consecutive tokens (M = B * tokens_per_seq).

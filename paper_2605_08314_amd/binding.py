@@ -38,6 +38,8 @@ class lr_kv_target(ctypes.Structure):
 
 _lib.lowrank_linear.argtypes = [_vp] * 5 + [_i64] * 4 + [_int, _int, _vp, _sz, _vp]
 _lib.lowrank_linear.restype = _int
+_lib.lowrank_linear_noalloc.argtypes = [_vp] * 5 + [_i64] * 4 + [_int, _vp]
+_lib.lowrank_linear_noalloc.restype = _int
 _lib.lowrank_qkv.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp),
                              ctypes.POINTER(_vp), ctypes.POINTER(_i64), ctypes.POINTER(_i64), _int,
                              _i64, _i64, ctypes.POINTER(lr_kv_target), _int, _int, _vp, _sz, _vp]
@@ -162,6 +164,14 @@ def lowrank_linear(x, U, V, bias, y, phase, workspace, stream=None) -> None:
     _check(_lib.lowrank_linear(_ptr(x), _ptr(U), _ptr(V), _ptr(bias), _ptr(y), M, d_in, r, d_out,
                                _dtype_code(x), _phase(phase), _ptr(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def lowrank_linear_noalloc(x, U, V, bias, y, stream=None) -> None:
+    M, d_in = x.shape
+    r, d_out = V.shape
+    assert U.shape == (d_in, r) and y.shape == (M, d_out)
+    _check(_lib.lowrank_linear_noalloc(_ptr(x), _ptr(U), _ptr(V), _ptr(bias), _ptr(y), M, d_in, r, d_out,
+                                       _dtype_code(x), _stream(stream)))
 
 
 def lowrank_qkv(x, U: Sequence, V: Sequence, bias: Optional[Sequence], out: Sequence, kv: Optional[dict],

@@ -72,6 +72,26 @@ static size_t ws_bytes_for(int op, int64_t M, int64_t r_total, int64_t d_out) {
 
 using namespace lr;
 
+// ---- scratch of lowrank_linear_noalloc: lives in the library image, one copy per device, never freed ----------
+constexpr size_t kStaticScratchBytes = (size_t)512 << 10;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {nullptr};        // device address of `scratch` on each device, once looked up
+
+// Device address of the current device's copy of `scratch` (looked up on the first call per device).
+static int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { set_error("cannot identify the current device"); return LR_ERR_LAUNCH; }
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { set_error("static scratch: hipGetSymbolAddress failed: %s", hipGetErrorString(e)); return LR_ERR_LAUNCH; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LR_OK;
+}
+
 #ifdef LR_TRACE
 extern "C" int lowrank_debug_trace(void* buf) { lr::g_trace_buffer = (unsigned long long*)buf; return 0; }
 #endif
@@ -168,6 +188,31 @@ int lowrank_linear(const void* x, const void* U, const void* V, const void* bias
     if (plan == PLAN_DECODE) return decode_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
     if (plan == PLAN_PREFILL) return prefill_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
     float* t = (float*)ws_layout(workspace, workspace_bytes, M).staging;
+    CacheDst none = {nullptr, nullptr, 0, 1};
+    st = generic_stage1(x, false, U, t, r, M, d_in, r, dtype, s);
+    if (st != LR_OK) return st;
+    return generic_stage2(t, r, V, bias, y, M, r, d_out, none, dtype, s);
+}
+
+int lowrank_linear_noalloc(const void* x, const void* U, const void* V, const void* bias, void* y,
+                           int64_t M, int64_t d_in, int64_t r, int64_t d_out, int dtype, void* stream) {
+    if (M < 0 || d_in < 0 || r < 0 || d_out < 0) { set_error("negative size"); return LR_ERR_SHAPE; }
+    if (dtype != LR_F32 && dtype != LR_BF16) { set_error("unknown dtype %d", dtype); return LR_ERR_DTYPE; }
+    if (M == 0 || d_out == 0) return LR_OK;
+    if (!y || (d_in > 0 && !x) || (r > 0 && d_in > 0 && !U) || (r > 0 && !V)) { set_error("NULL operand"); return LR_ERR_NULL; }
+    if (M >= ((int64_t)1 << 31) / 4 || r >= ((int64_t)1 << 31) / 4 || (size_t)M * (size_t)r * 4 > kStaticScratchBytes) {
+        set_error("lowrank_linear_noalloc: M * r = %lld exceeds the %zu floats of the built-in scratch (use lowrank_linear with a workspace)",
+                  (long long)(M * r), kStaticScratchBytes / 4);
+        return LR_ERR_WORKSPACE;
+    }
+    void* sp = nullptr;
+    int st = static_scratch(&sp);
+    if (st != LR_OK) return st;
+    float* t = (float*)sp;
+    hipStream_t s = (hipStream_t)stream;
+    const bool al = aligned16(x) && aligned16(U) && aligned16(V) && aligned16(y) && aligned16(bias);
+    if (dtype == LR_BF16 && al && M <= 32 && decode_shape_ok(M, d_in, r) && decode_shape_ok(M, r, d_out))
+        return decode_linear_scratch(x, U, V, bias, y, M, d_in, r, d_out, t, s);
     CacheDst none = {nullptr, nullptr, 0, 1};
     st = generic_stage1(x, false, U, t, r, M, d_in, r, dtype, s);
     if (st != LR_OK) return st;

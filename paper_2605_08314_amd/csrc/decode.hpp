@@ -123,6 +123,9 @@ int decode_launch_stage(const DStage& st, int cpl, bool a_f32, int epi, hipStrea
 bool decode_shape_ok(int64_t M, int64_t K, int64_t N);
 int decode_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
                   int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s);
+// the same with nothing but an fp32 area t[M * r] as scratch: one launch per stage
+int decode_linear_scratch(const void* x, const void* U, const void* V, const void* bias, void* y,
+                          int64_t M, int64_t d_in, int64_t r, int64_t d_out, float* t, hipStream_t s);
 int decode_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
                void* const* out, const int64_t* r, const int64_t* d_out, int n_proj, const int* base_of,
                const int64_t* t_off, int64_t R, int64_t M, int64_t d_in, const lr_kv_target* kv,

@@ -103,13 +103,17 @@ static bool use_t16(int64_t M, int64_t col_tiles, int min_rows) {
     return M > min_rows && M > kT16Rows && col_tiles <= kTileCounters;
 }
 
+// t_only != NULL: the call has no workspace, only this fp32 area of M * R floats for the rank-space rows; it then runs as
+// one launch per stage (no control block, no cross-workgroup waits).
 static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* sk_in, int nb, const Final* fin_in,
-                         int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s) {
-    const WsLayout L = ws_layout(ws, ws_bytes, M);
+                         int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s, float* t_only = nullptr) {
+    WsLayout L;
+    if (t_only) { memset(&L, 0, sizeof(L)); L.staging = (char*)t_only; }
+    else L = ws_layout(ws, ws_bytes, M);
     size_t factor_bytes = 0;
     for (int i = 0; i < nb; ++i) factor_bytes += (size_t)d_in * sk_in[i].N * 2;
     for (int i = 0; i < nf; ++i) factor_bytes += (size_t)fin_in[i].r * fin_in[i].N * 2;
-    const int G = fused_grid(factor_bytes);
+    const int G = t_only ? 0 : fused_grid(factor_bytes);
     const bool fused = G > 0 && (size_t)M * R * 4 <= L.acc_bytes;
     const int c1 = kCpl;
     // bf16 finalisation of t needs a slot of the workspace's partial-tile area for every tile of stage 1
@@ -151,6 +155,13 @@ int decode_linear(const void* x, const void* U, const void* V, const void* bias,
     SplitK sk = {U, r, (float*)0, nullptr, nullptr};
     Final f = {(const void*)0, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
     return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, ws, ws_bytes, s);
+}
+
+int decode_linear_scratch(const void* x, const void* U, const void* V, const void* bias, void* y,
+                          int64_t M, int64_t d_in, int64_t r, int64_t d_out, float* t, hipStream_t s) {
+    SplitK sk = {U, r, (float*)0, nullptr, nullptr};
+    Final f = {(const void*)0, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
+    return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, nullptr, 0, s, t);
 }
 
 int decode_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
