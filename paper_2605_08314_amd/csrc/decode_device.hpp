@@ -131,14 +131,17 @@ __device__ __forceinline__ void mma_block(f32x4_t (&acc)[MB][CPL], const WFrag<C
 // just passed, so the whole result turns NaN, not only the failing workgroup's part).
 // kCoherent: the activation rows were produced earlier in this launch by other workgroups and are read with
 // agent-coherent loads; kFused: hidden rows written by this tile are read by other workgroups of this launch.
-struct NoSync { static constexpr bool kCoherent = false, kFused = false; __device__ __forceinline__ void operator()(uint32_t&) const {} };
+struct NoSync { static constexpr bool kCoherent = false, kFused = false; __device__ __forceinline__ void operator()(uint32_t&) const {}
+                __device__ __forceinline__ void before_epilogue() const {} };
 // Same, for later tiles of a stage whose input other workgroups of this launch produced.
-struct NoSyncCoherent { static constexpr bool kCoherent = true, kFused = true; __device__ __forceinline__ void operator()(uint32_t&) const {} };
+struct NoSyncCoherent { static constexpr bool kCoherent = true, kFused = true; __device__ __forceinline__ void operator()(uint32_t&) const {}
+                        __device__ __forceinline__ void before_epilogue() const {} };
 // Later tiles of a stage whose input (accumulators added with device-scope atomics, hidden rows or a finalised bf16
 // copy written with device-coherent stores) no workgroup on this XCD has read before the stage's barrier in this
 // launch: plain cached loads are safe (first touch misses L2) and let the other workgroups hit in L2.
 struct NoSyncPlain { static constexpr bool kCoherent = false, kFused = true; __device__ __forceinline__ void operator()() const {}
-                     __device__ __forceinline__ void operator()(uint32_t&) const {} };
+                     __device__ __forceinline__ void operator()(uint32_t&) const {}
+                     __device__ __forceinline__ void before_epilogue() const {} };
 
 // This wave's share of rows [32*kb0, 32*kb1) of W: blocks kb0 + wave, kb0 + wave + NW, ...
 // The first PF weight blocks are requested before `sync()` runs and the activations after it, so
@@ -295,6 +298,7 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
         else mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSync(), late_err);
     }
 
+    sync.before_epilogue();       // (the first tile of a call resolves the workspace's control block here: after its loads, before its first use)
     // cross-wave reduction through LDS: red[wave][slot = (mat*MB + mb)*4 + v][q][lane]
     constexpr int NSL = NMAT * MB * 4;
 #pragma unroll
@@ -518,8 +522,7 @@ constexpr uint32_t kPrepareSpinLimit = 1u << 24;
 
 // Rare path (first call on a workspace that nobody prepared): one wave of the whole launch wins the right to
 // prepare, everyone else waits for kCtrlReady.  Wave-uniform; returns false if the wait gave up.
-__device__ __noinline__ bool ctrl_prepare(const FusedCommon& fc, uint64_t observed) {
-    Ctrl* c = fc.ctrl;
+__device__ __noinline__ bool ctrl_prepare(Ctrl* c, char* acc0, size_t acc_bytes, uint64_t observed) {
     const int lane = threadIdx.x & 63;
     uint32_t won = 0;
     if (lane == 0 && observed != kCtrlBusy) {
@@ -533,8 +536,8 @@ __device__ __noinline__ bool ctrl_prepare(const FusedCommon& fc, uint64_t observ
         uint2* h = reinterpret_cast<uint2*>(c) + 1;
         const uint32_t n8 = (uint32_t)((kHeaderBytes + kSkFlagBytes) / 8 - 1);
         for (uint32_t i = lane; i < n8; i += 64) h[i] = make_uint2(0u, 0u);
-        uint4* a = reinterpret_cast<uint4*>(fc.acc0);
-        const uint32_t n16 = (uint32_t)(2 * fc.acc_bytes / 16);
+        uint4* a = reinterpret_cast<uint4*>(acc0);
+        const uint32_t n16 = (uint32_t)(2 * acc_bytes / 16);
         for (uint32_t i = lane; i < n16; i += 64) a[i] = make_uint4(0u, 0u, 0u, 0u);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");             // the zeroes are in memory before the word says so
         if (lane == 0) __hip_atomic_store(&c->magic, kCtrlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -551,13 +554,13 @@ __device__ __noinline__ bool ctrl_prepare(const FusedCommon& fc, uint64_t observ
 }
 
 // Wave-uniform.  `bad` (LDS word of the workgroup) is raised when the workspace carries an earlier failure.
-__device__ __forceinline__ CtrlSnap ctrl_resolve(const FusedCommon& fc, CtrlLoads L, uint32_t* bad) {
+__device__ __forceinline__ CtrlSnap ctrl_resolve(Ctrl* ctrl, char* acc0, size_t acc_bytes, CtrlLoads L, uint32_t* bad) {
     const uint64_t magic = (uint64_t)L.m.x | ((uint64_t)L.m.y << 32);
     if (__builtin_amdgcn_readfirstlane((uint32_t)(magic != kCtrlReady)) != 0u) {
-        const bool ok = ctrl_prepare(fc, magic);
-        L = ctrl_issue(fc.ctrl);
+        const bool ok = ctrl_prepare(ctrl, acc0, acc_bytes, magic);
+        L = ctrl_issue(ctrl);
         if (!ok) {
-            if ((threadIdx.x & 63) == 0) { __hip_atomic_store(&fc.ctrl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); *bad = 1u; }
+            if ((threadIdx.x & 63) == 0) { __hip_atomic_store(&ctrl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); *bad = 1u; }
         }
     }
     CtrlSnap c;
@@ -568,17 +571,19 @@ __device__ __forceinline__ CtrlSnap ctrl_resolve(const FusedCommon& fc, CtrlLoad
 }
 
 // Hook of the first tile of a call's first stage: resolves the control block (and with it the parity of the
-// accumulator areas) between the tile's first weight requests and its epilogue.
+// accumulator areas) after the tile's blocks have been multiplied, right before its epilogue needs the parity.
 struct CtrlGate {
     static constexpr bool kCoherent = false, kFused = false;
-    const FusedCommon* fc; const CtrlLoads* loads; CtrlSnap* snap; size_t* shift;
+    Ctrl* ctrl; char* acc0; size_t acc_bytes;       // by value: taking the address of a kernel argument would force a private copy of all of them
+    const CtrlLoads* loads; CtrlSnap* snap; size_t* shift;
     uint32_t** tcnt; bool t16;      // tile counters of the call's parity (bf16 finalisation), else NULL
     uint32_t* bad;
-    __device__ __forceinline__ void operator()(uint32_t&) const { (*this)(); }
+    __device__ __forceinline__ void operator()(uint32_t&) const {}
+    __device__ __forceinline__ void before_epilogue() const { (*this)(); }
     __device__ __forceinline__ void operator()() const {
-        *snap = ctrl_resolve(*fc, *loads, bad);
-        *shift = (size_t)snap->p * fc->acc_bytes;
-        *tcnt = t16 ? fc->ctrl->tcnt[snap->p] : nullptr;
+        *snap = ctrl_resolve(ctrl, acc0, acc_bytes, *loads, bad);
+        *shift = (size_t)snap->p * acc_bytes;
+        *tcnt = t16 ? ctrl->tcnt[snap->p] : nullptr;
     }
 };
 
@@ -605,6 +610,7 @@ struct GridWait {
     int stamp;
     unsigned long long* trace;
     bool last;              // the wait in front of the call's last stage: hand the error word to the epilogue
+    __device__ __forceinline__ void before_epilogue() const {}
     __device__ __forceinline__ void operator()(uint32_t& late_err) const {
         (*this)();
         if (last) late_err = ld_agent(err);
@@ -695,7 +701,7 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     CtrlSnap cs;
     size_t shift = 0;
     uint32_t* tcp = nullptr;
-    const CtrlGate gate = {&fa.fc, &cl, &cs, &shift, &tcp, T16, &s_bad};
+    const CtrlGate gate = {fa.fc.ctrl, fa.fc.acc0, fa.fc.acc_bytes, &cl, &cs, &shift, &tcp, T16, &s_bad};
     bool resolved = false;
     for (int tile = blockIdx.x; tile < fa.s1.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s1, tile);
@@ -739,7 +745,7 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
     CtrlSnap cs;
     size_t shift = 0;
     uint32_t* tcp = nullptr;
-    const CtrlGate gate = {&fa.fc, &cl, &cs, &shift, &tcp, T16, &s_bad};
+    const CtrlGate gate = {fa.fc.ctrl, fa.fc.acc0, fa.fc.acc_bytes, &cl, &cs, &shift, &tcp, T16, &s_bad};
     const uint32_t G = gridDim.x;
     LR_STAMP(0);
     // A: t_gu += x U_gu
