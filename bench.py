@@ -239,6 +239,44 @@ def run_prefill_attention(torch, B, gen, S):
             "TFLOPs": round(tf, 1), "frac_mfma_bf16_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
+def run_prefill_factorized_attention(torch, B, gen, S, r=R_ATTN):
+    """The same attention with factorized queries (rank-space rows t_q and V_q; the kernel rebuilds its query tiles), and the
+    two ways from x to the attention output: dense (lowrank_linear writes q, lowrank_prefill_attention reads it) against
+    factorized (lowrank_rank_project writes t_q, the attention kernel does the rest)."""
+    bf = torch.bfloat16
+    x = torch.randn((S, D), device="cuda", dtype=bf, generator=gen)
+    U = (torch.randn((D, r), device="cuda", generator=gen) * D ** -0.5).to(bf)
+    V = (torch.randn((r, D), device="cuda", generator=gen) * r ** -0.5).to(bf)
+    kc = torch.randn((1, S, HEADS, HEAD_DIM), device="cuda", dtype=bf, generator=gen)
+    vc = torch.randn((1, S, HEADS, HEAD_DIM), device="cuda", dtype=bf, generator=gen)
+    pos0 = torch.zeros((1,), device="cuda", dtype=torch.int32)
+    q, out = torch.empty((S, D), device="cuda", dtype=bf), torch.empty((S, D), device="cuda", dtype=bf)
+    tq = torch.empty((S, r), device="cuda", dtype=bf)
+    ws = B.new_workspace(B.LR_OP_LINEAR, S, D, r, D, B.LR_BF16, "prefill")
+    B.lowrank_rank_project(x, U, tq, ws)
+    scale = HEAD_DIM ** -0.5
+
+    def fact_only():
+        B.lowrank_prefill_factorized_attention(tq, V, None, kc, vc, pos0, S, out, scale, 10000.0)
+
+    def chain_dense():
+        B.lowrank_linear(x, U, V, None, q, "prefill", ws)
+        B.lowrank_prefill_attention(q, kc, vc, pos0, S, out, scale, 10000.0)
+
+    def chain_fact():
+        B.lowrank_rank_project(x, U, tq, ws)
+        B.lowrank_prefill_factorized_attention(tq, V, None, kc, vc, pos0, S, out, scale, 10000.0)
+
+    ms_f = time_region(torch, fact_only, 5, 2)
+    ms_cd = time_region(torch, chain_dense, 5, 2)
+    ms_cf = time_region(torch, chain_fact, 5, 2)
+    B.lowrank_workspace_status(ws)
+    fl = 4.0 * HEAD_DIM * HEADS * (S * (S + 1) / 2) + 2.0 * S * r * D          # attention + the in-kernel q = t_q V_q
+    return {"workload": f"S={S}, rank {r}: queries as rank-space rows", "ms": round(ms_f, 3),
+            "TFLOPs": round(fl / (ms_f * 1e-3) / 1e12, 1), "frac_mfma_bf16_peak": round(fl / (ms_f * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "chain_dense_q_ms": round(ms_cd, 3), "chain_factorized_q_ms": round(ms_cf, 3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -274,7 +312,8 @@ def main():
         return
     if args.prefill_only:
         print(json.dumps({"prefill_only": True, "prefill": run_prefill(torch, B, gen, Layer(torch, gen=gen), args.prefill_rows),
-                          "prefill_attention": run_prefill_attention(torch, B, gen, args.prefill_rows)}))
+                          "prefill_attention": run_prefill_attention(torch, B, gen, args.prefill_rows),
+                          "prefill_factorized_attention": run_prefill_factorized_attention(torch, B, gen, args.prefill_rows)}))
         return
     layers = [Layer(torch, gen=gen) for _ in range(L)]
     S_max = 64
@@ -403,6 +442,7 @@ def main():
         out["prefill_ranks"] = run_prefill_ranks(torch, B, gen)
         out["shared_basis"] = run_shared_basis(torch, B, gen)
         out["prefill_attention"] = run_prefill_attention(torch, B, gen, args.prefill_rows)
+        out["prefill_factorized_attention"] = run_prefill_factorized_attention(torch, B, gen, args.prefill_rows)
         out["decode_attention"] = run_decode_attention(torch, B, gen)
 
         # ---- CPU baseline: the oracle as it stands, on this machine's host cores, bounded sample

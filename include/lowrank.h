@@ -197,6 +197,30 @@ int lowrank_prefill_attention(const void *q, const lr_kv_target *kv, void *out, 
                               int dtype, void *stream);
 
 /*
+ * Prefill attention with FACTORIZED queries (Section 3.1, second paragraph: the prefill path consumes the low-rank factors
+ * directly and avoids materialising dense Q/K/V in memory; K and V still go to the dense cache through lowrank_qkv, which
+ * is what decode reads later).  Same operation as lowrank_prefill_attention with
+ *     q[M, n_heads * head_dim] = t_q[M, r_q] * V_q[r_q, n_heads * head_dim] (+ b_q),
+ * where every workgroup rebuilds its own 128 x 128 tile of q on the matrix cores, rounds it to the element type (as a
+ * stored q would be) and rotates / scales it in registers: the dense q never exists in memory.  t_q are the rank-space rows
+ * x * U_q of the new tokens (lowrank_rank_project), row-major; b_q (n_heads * head_dim entries) may be NULL.
+ * Supported: dtype LR_BF16, head_dim 128, r_q a multiple of 64, 16-byte aligned operands; otherwise LR_ERR_UNSUPPORTED.
+ * No workspace.  out must not alias t_q.
+ */
+int lowrank_prefill_factorized_attention(const void *t_q, const void *V_q, const void *b_q /* nullable */, int64_t r_q,
+                                         const lr_kv_target *kv, void *out, float scale, float rope_base,
+                                         int dtype, void *stream);
+
+/*
+ * First half of a factorized linear layer on its own (Section 3.1, first paragraph: the layer is a factor pair):
+ *     t[M, r] = x[M, d_in] * U[d_in, r], rounded once to the element type.
+ * These are the rank-space rows that lowrank_prefill_factorized_attention consumes.  Workspace as for
+ * lowrank_workspace_bytes(LR_OP_LINEAR, M, d_in, r, 0, ...).
+ */
+int lowrank_rank_project(const void *x, const void *U, void *t, int64_t M, int64_t d_in, int64_t r,
+                         int dtype, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Offline prepack (Section 3.1, third paragraph; Figure 3): concatenate n (1..8) factors
  * U_list[i][d_in, r_list[i]] along the rank axis into U_packed[d_in, sum r_list].  U_list and
  * r_list are HOST arrays; the matrices are device memory.  Pure data movement: bit-exact.

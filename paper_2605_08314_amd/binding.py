@@ -50,6 +50,10 @@ _lib.lowrank_decode_attention.argtypes = [_vp, ctypes.POINTER(lr_kv_target), _vp
 _lib.lowrank_decode_attention.restype = _int
 _lib.lowrank_prefill_attention.argtypes = [_vp, ctypes.POINTER(lr_kv_target), _vp, ctypes.c_float, ctypes.c_float, _int, _vp]
 _lib.lowrank_prefill_attention.restype = _int
+_lib.lowrank_prefill_factorized_attention.argtypes = [_vp, _vp, _vp, _i64, ctypes.POINTER(lr_kv_target), _vp, ctypes.c_float, ctypes.c_float, _int, _vp]
+_lib.lowrank_prefill_factorized_attention.restype = _int
+_lib.lowrank_rank_project.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp, _sz, _vp]
+_lib.lowrank_rank_project.restype = _int
 _lib.lowrank_pack_concat.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_i64), _int, _i64, _int, _vp, _vp]
 _lib.lowrank_pack_concat.restype = _int
 _lib.lowrank_workspace_bytes.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int]
@@ -228,6 +232,26 @@ def lowrank_prefill_attention(q, k_cache, v_cache, pos, tokens_per_seq: int, out
     assert q.shape == (B * tokens_per_seq, H * E) and out.shape == q.shape
     kvs = lr_kv_target(_ptr(k_cache), _ptr(v_cache), _ptr(pos), B, S_max, H, E, tokens_per_seq, 0, 0)
     _check(_lib.lowrank_prefill_attention(_ptr(q), ctypes.byref(kvs), _ptr(out), scale, rope_base, _dtype_code(q), _stream(stream)))
+
+
+def lowrank_prefill_factorized_attention(t_q, V_q, b_q, k_cache, v_cache, pos, tokens_per_seq: int, out, scale: float,
+                                         rope_base: float, stream=None) -> None:
+    """Prefill attention whose queries arrive as rank-space rows t_q [M, r] and the factor V_q [r, H * E] (+ optional b_q)."""
+    B, S_max, H, E = k_cache.shape
+    r = V_q.shape[0]
+    assert v_cache.shape == k_cache.shape and pos.dtype == torch.int32
+    assert t_q.shape == (B * tokens_per_seq, r) and V_q.shape == (r, H * E) and out.shape == (B * tokens_per_seq, H * E)
+    kvs = lr_kv_target(_ptr(k_cache), _ptr(v_cache), _ptr(pos), B, S_max, H, E, tokens_per_seq, 0, 0)
+    _check(_lib.lowrank_prefill_factorized_attention(_ptr(t_q), _ptr(V_q), _ptr(b_q), r, ctypes.byref(kvs), _ptr(out), scale,
+                                                     rope_base, _dtype_code(t_q), _stream(stream)))
+
+
+def lowrank_rank_project(x, U, t, workspace, stream=None) -> None:
+    M, d_in = x.shape
+    r = U.shape[1]
+    assert U.shape == (d_in, r) and t.shape == (M, r)
+    _check(_lib.lowrank_rank_project(_ptr(x), _ptr(U), _ptr(t), M, d_in, r, _dtype_code(x), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def lowrank_pack_concat(U_list: Sequence[torch.Tensor], U_packed: torch.Tensor, stream=None) -> None:

@@ -371,6 +371,41 @@ int lowrank_prefill_attention(const void* q, const lr_kv_target* kv, void* out, 
     return attn_prefill(q, kv, out, scale, rope_base, (hipStream_t)stream);
 }
 
+int lowrank_prefill_factorized_attention(const void* t_q, const void* V_q, const void* b_q, int64_t r_q, const lr_kv_target* kv,
+                                         void* out, float scale, float rope_base, int dtype, void* stream) {
+    if (dtype != LR_F32 && dtype != LR_BF16) { set_error("unknown dtype %d", dtype); return LR_ERR_DTYPE; }
+    if (!kv) { set_error("kv is NULL"); return LR_ERR_NULL; }
+    if (kv->B < 0 || kv->tokens_per_seq < 1 || kv->S_max < kv->tokens_per_seq || kv->n_heads < 1 || kv->head_dim < 1 || r_q < 0) {
+        set_error("kv: bad cache shape"); return LR_ERR_SHAPE; }
+    const int64_t M = kv->B * kv->tokens_per_seq, H = kv->n_heads, E = kv->head_dim;
+    if (M >= (1ll << 24) || H * E >= (1ll << 24) || kv->S_max >= (1ll << 30) || r_q >= (1ll << 20)) { set_error("size out of range"); return LR_ERR_SHAPE; }
+    if (M == 0) return LR_OK;
+    if (!t_q || !V_q || !out || !kv->k_cache || !kv->v_cache || !kv->pos) { set_error("NULL operand"); return LR_ERR_NULL; }
+    const bool al = aligned16(t_q) && aligned16(V_q) && aligned16(b_q) && aligned16(out) && aligned16(kv->k_cache) && aligned16(kv->v_cache);
+    if (!attn_prefill_ok(dtype, E, al) || r_q < 64 || r_q % 64 != 0) {
+        set_error("factorized prefill attention: needs bf16, head_dim 128, a rank that is a multiple of 64 and 16-byte aligned operands "
+                  "(otherwise reconstruct q with lowrank_linear and use lowrank_prefill_attention / lowrank_decode_attention)");
+        return LR_ERR_UNSUPPORTED;
+    }
+    return attn_prefill(nullptr, kv, out, scale, rope_base, (hipStream_t)stream, t_q, V_q, b_q, r_q);
+}
+
+int lowrank_rank_project(const void* x, const void* U, void* t, int64_t M, int64_t d_in, int64_t r, int dtype,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || d_in < 0 || r < 0) { set_error("negative size"); return LR_ERR_SHAPE; }
+    int st = check_common(dtype, LR_PHASE_AUTO, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_LINEAR, M, r, 0));
+    if (st != LR_OK) return st;
+    if (M == 0 || r == 0) return LR_OK;
+    if (!t || (d_in > 0 && (!x || !U))) { set_error("NULL operand"); return LR_ERR_NULL; }
+    hipStream_t s = (hipStream_t)stream;
+    const bool al = aligned16(x) && aligned16(U) && aligned16(t);
+    if (dtype == LR_BF16 && al && prefill_shape_ok(M, d_in, r)) return prefill_rank_project(x, U, t, M, d_in, r, workspace, workspace_bytes, s);
+    float* t32 = (float*)ws_layout(workspace, workspace_bytes, M).staging;
+    st = generic_stage1(x, false, U, t32, r, M, d_in, r, dtype, s);
+    if (st != LR_OK) return st;
+    return generic_round(t32, t, M * r, dtype, s);
+}
+
 int lowrank_pack_concat(const void* const* U_list, const int64_t* r_list, int n, int64_t d_in,
                         int dtype, void* U_packed, void* stream) {
     if (n < 1 || n > 8) { set_error("n must be 1..8"); return LR_ERR_SHAPE; }

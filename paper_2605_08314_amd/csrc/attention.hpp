@@ -22,6 +22,8 @@ int attn_decode(const void* q, const lr_kv_target* kv, void* out, float scale, f
 
 // Prefill attention (attention_prefill.hip): bf16, head_dim 128, 16-byte aligned operands.
 bool attn_prefill_ok(int dtype, int64_t E, bool aligned);
-int attn_prefill(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base, hipStream_t s);
+// q != NULL: dense queries; q == NULL: factorized queries q = tq vq (+ bq), tq [M, r_q], vq [r_q, H * 128], r_q a multiple of 64
+int attn_prefill(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base, hipStream_t s,
+                 const void* tq = nullptr, const void* vq = nullptr, const void* bq = nullptr, int64_t r_q = 0);
 
 }  // namespace lr

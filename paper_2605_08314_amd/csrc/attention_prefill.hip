@@ -34,6 +34,8 @@ struct PAttnArgs {
     int ldq;                 // elements between query rows (H * 128)
     float scale_log2e;       // softmax scale * log2(e)
     double rope_base;        // <= 0: no rotation
+    // factorized queries (k_attn_prefill<true>): q = t_q V_q (+ b_q), rebuilt tile by tile inside the kernel; q above is unused
+    const bf16_t* tq; const bf16_t* vq; const bf16_t* bq; int r_q;     // t_q [B * T, r_q], V_q [r_q, H * 128], b_q [H * 128] or NULL
 };
 
 constexpr float kLazyExp = 8.f;      // a row's reference maximum is moved when a score exceeds it by more than this (log2 units)
@@ -128,6 +130,13 @@ __global__ void __launch_bounds__(256) k_rope_new_keys(PAttnArgs a) {
     }
 }
 
+// FACT: the queries arrive in rank space (Section 3.1, attention paragraph: prefill consumes the low-rank factors without
+// materialising dense Q in memory).  The workgroup first forms its 128 x 128 tile of Q = t_q V_q (+ b_q) on the matrix cores
+// -- transposed, Q^T = V_q^T t_q^T, with the very machinery of O^T += V^T P^T: 64-row tiles of V_q (row-major, [k][e], the
+// geometry of a V cache tile) arrive by direct-to-LDS loads and are read through the transposing LDS read, the rank-space
+// row of a lane is the other operand straight from memory -- rounds it to bf16 as a stored q would be, and hands it to the
+// rotation below through LDS.
+template <bool FACT>
 __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[2 * PA_TILE];     // K0 | V0 | K1 | V1
     __shared__ double s_theta[64];
@@ -160,10 +169,103 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
     const int p_row = (int)(pos_b + s_clamped);                // position of the row
     pbf16x8_t qf[8];
     {
-        const bf16_t* qrow = a.q + ((size_t)b * a.T + (size_t)s_clamped) * a.ldq + (size_t)head * PA_E + 8 * hh;
         uint4 raw[8];
+        if constexpr (FACT) {
+            const uint32_t lds0q = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds);
+            const size_t vrow_bytes = (size_t)a.H * PA_E * 2;                  // bytes between rows of V_q
+            const char* vqbase = reinterpret_cast<const char*>(a.vq + (size_t)head * PA_E);
+            const bf16_t* tqrow = a.tq + ((size_t)b * a.T + (size_t)s_clamped) * a.r_q + 4 * hh;
+            const int nkt = a.r_q / PA_BK;
+            uint32_t voffq[4];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) raw[ks] = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
+            for (int q = 0; q < 4; ++q) {
+                const int r = 16 * wave + 4 * q + (lane >> 4);
+                voffq[q] = (uint32_t)r * (uint32_t)vrow_bytes + (uint32_t)(((lane & 15) ^ pa_f(r & 15)) * 16);
+            }
+            const int wave_q = __builtin_amdgcn_readfirstlane(wave);
+            // transposing-read offsets (as for the V operand of the main loop, see below)
+            uint32_t q_lo[4], q_hi[4];
+            {
+                const int sl = lane & 15, g1 = (lane >> 4) & 1;
+                const int rlo = 4 * hh + (sl >> 2), rhi = rlo + 8;
+                const int lowp = 2 * g1 + ((sl & 3) >> 1);
+#pragma unroll
+                for (int eb = 0; eb < 4; ++eb) {
+                    q_lo[eb] = (uint32_t)rlo * PA_TROW + (uint32_t)((((4 * eb + lowp) ^ pa_f(rlo & 15)) * 16) + (sl & 1) * 8);
+                    q_hi[eb] = (uint32_t)rhi * PA_TROW + (uint32_t)((((4 * eb + lowp) ^ pa_f(rhi & 15)) * 16) + (sl & 1) * 8);
+                }
+            }
+            pf32x16_t acc_q[4];
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc_q[eb][i] = 0.f;
+#define PA_REQUEST_VQ(KT, BUF)                                                                                 \
+            do {                                                                                               \
+                const char* vs_ = pa_uniform_ptr(vqbase + (size_t)(KT) * PA_BK * vrow_bytes);                  \
+                const uint32_t d_ = lds0q + (uint32_t)(BUF) * PA_TILE + PA_KTILE + (uint32_t)wave_q * 4096u;   \
+                _Pragma("unroll") for (int q = 0; q < 4; ++q) pa_dma16(d_ + 1024u * q, voffq[q], vs_);         \
+            } while (0)
+            if (nkt > 0) PA_REQUEST_VQ(0, 0);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            for (int kt = 0; kt < nkt; ++kt) {
+                const int buf = kt & 1;
+                if (kt + 1 < nkt) PA_REQUEST_VQ(kt + 1, buf ^ 1);
+                const char* vt = lds + buf * PA_TILE + PA_KTILE;
+                // this lane's rank-space values of the tile, in the k order of the transposed operand: step a2 takes
+                // k = 64 kt + 16 a2 + {4 hh .. + 3} and {8 + 4 hh .. + 3}
+                uint2 tlo[4], thi[4];
+#pragma unroll
+                for (int a2 = 0; a2 < 4; ++a2) {
+                    const bf16_t* tp = tqrow + PA_BK * kt + 16 * a2;
+                    tlo[a2] = *reinterpret_cast<const uint2*>(tp);
+                    thi[a2] = *reinterpret_cast<const uint2*>(tp + 8);
+                }
+#pragma unroll
+                for (int a2 = 0; a2 < 4; ++a2) {
+                    const pbf16x8_t tf = pa_frag(tlo[a2].x, tlo[a2].y, thi[a2].x, thi[a2].y);
+#pragma unroll
+                    for (int eb = 0; eb < 4; ++eb) {
+                        union { struct { ps16x4_t lo, hi; } h; pbf16x8_t v; } x;
+                        const char* vp = vt + (uint32_t)(16 * a2) * PA_TROW;
+                        x.h.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp + q_lo[eb]));
+                        x.h.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ps16x4_t*)(vp + q_hi[eb]));
+                        acc_q[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, tf, acc_q[eb], 0, 0, 0);
+                    }
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next tile has landed
+                __syncthreads();
+            }
+#undef PA_REQUEST_VQ
+            // Q^T of this lane: e = 32 eb + 8 g4 + 4 hh .. + 3 of query row li; + bias, rounded to bf16 (as a stored q is),
+            // through the wave's own rows of the staging area, and back as whole 16-byte pieces of the row
+            char* stage = lds + wave * (32 * PA_ROW);
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int e = eb * 32 + 8 * g4 + 4 * hh;
+                    float bq4[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (a.bq) {
+                        const uint2 braw = *reinterpret_cast<const uint2*>(a.bq + (size_t)head * PA_E + e);
+                        bq4[0] = __uint_as_float(braw.x << 16); bq4[1] = __uint_as_float(braw.x & 0xffff0000u);
+                        bq4[2] = __uint_as_float(braw.y << 16); bq4[3] = __uint_as_float(braw.y & 0xffff0000u);
+                    }
+                    const uint2 o = make_uint2(pa_pack2(acc_q[eb][4 * g4 + 0] + bq4[0], acc_q[eb][4 * g4 + 1] + bq4[1]),
+                                               pa_pack2(acc_q[eb][4 * g4 + 2] + bq4[2], acc_q[eb][4 * g4 + 3] + bq4[3]));
+                    *reinterpret_cast<uint2*>(stage + li * PA_ROW + e * 2) = o;
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // LDS traffic of a wave completes in order; these rows are this wave's
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) raw[ks] = *reinterpret_cast<const uint4*>(stage + li * PA_ROW + (16 * ks + 8 * hh) * 2);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __syncthreads();                                            // everyone holds its row: the area may be overwritten
+        } else {
+            const bf16_t* qrow = a.q + ((size_t)b * a.T + (size_t)s_clamped) * a.ldq + (size_t)head * PA_E + 8 * hh;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) raw[ks] = *reinterpret_cast<const uint4*>(qrow + 16 * ks);
+        }
         if (a.rope_base > 0.0) {
             // cos / sin of the block's 128 positions x 64 frequencies, computed once by all threads into LDS (the tiles
             // are not loaded yet): [row][i] as float2
@@ -410,8 +512,11 @@ __global__ void __launch_bounds__(256, 2) k_attn_prefill(PAttnArgs a) {
 
 bool attn_prefill_ok(int dtype, int64_t E, bool aligned) { return dtype == LR_BF16 && aligned && E == 128; }
 
-int attn_prefill(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base, hipStream_t s) {
+// q == NULL: factorized queries (tq, vq, bq, r_q)
+int attn_prefill(const void* q, const lr_kv_target* kv, void* out, float scale, float rope_base, hipStream_t s,
+                 const void* tq, const void* vq, const void* bq, int64_t r_q) {
     PAttnArgs a;
+    a.tq = (const bf16_t*)tq; a.vq = (const bf16_t*)vq; a.bq = (const bf16_t*)bq; a.r_q = (int)r_q;
     a.q = (const bf16_t*)q; a.k_cache = (bf16_t*)kv->k_cache; a.v_cache = (const bf16_t*)kv->v_cache; a.pos = kv->pos;
     a.out = (bf16_t*)out;
     a.B = (int)kv->B; a.T = (int)kv->tokens_per_seq; a.H = (int)kv->n_heads; a.S_max = (int)kv->S_max;
@@ -427,7 +532,8 @@ int attn_prefill(const void* q, const lr_kv_target* kv, void* out, float scale, 
     const long long groups = (long long)a.H * a.B;
     const long long grid = 8 * nqb * ((groups + 7) / 8);       // see the index mapping in the kernel
     if (grid >= (1ll << 31)) { set_error("prefill attention: too many blocks"); return LR_ERR_SHAPE; }
-    hipLaunchKernelGGL(k_attn_prefill, dim3((unsigned)grid), dim3(256), 0, s, a);
+    if (q) hipLaunchKernelGGL(k_attn_prefill<false>, dim3((unsigned)grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(k_attn_prefill<true>, dim3((unsigned)grid), dim3(256), 0, s, a);
     return launch_status("prefill attention");
 }
 

@@ -169,6 +169,21 @@ int ws_prepare(void* ws, hipStream_t s) {
     return launch_status("workspace preparation");
 }
 
+template <class IO>
+__global__ void __launch_bounds__(256) k_gen_round(const float* __restrict__ src, typename IO::T* __restrict__ dst, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] = IO::cvt(src[i]);
+}
+
+// dst[i] = src[i] rounded to dtype (nearest-even)
+int generic_round(const float* src, void* dst, int64_t n, int dtype, hipStream_t s) {
+    if (n <= 0) return LR_OK;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (dtype == LR_F32) hipLaunchKernelGGL((k_gen_round<IoF32>), dim3((unsigned)blocks), dim3(256), 0, s, src, (float*)dst, n);
+    else hipLaunchKernelGGL((k_gen_round<IoBF16>), dim3((unsigned)blocks), dim3(256), 0, s, src, (bf16_t*)dst, n);
+    return launch_status("generic round");
+}
+
 int fill_zero(void* p, size_t bytes, hipStream_t s) {
     if (bytes == 0) return LR_OK;
     size_t words = bytes / 4;   // callers pass multiples of 4

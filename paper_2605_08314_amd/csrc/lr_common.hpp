@@ -83,5 +83,6 @@ int generic_gateup(const float* t, int64_t ldt, const void* V_g, const void* V_u
 int generic_pack_concat(const void* const* U_list, const int64_t* r_list, int n, int64_t d_in,
                         int elem_bytes, void* packed, hipStream_t s);
 int fill_zero(void* p, size_t bytes, hipStream_t s);
+int generic_round(const float* src, void* dst, int64_t n, int dtype, hipStream_t s);
 
 }  // namespace lr

@@ -38,6 +38,8 @@ void prefill_plan_query(int64_t M, int64_t K, int64_t N, int n, bool gateup, int
 
 int prefill_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
                    int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s);
+int prefill_rank_project(const void* x, const void* U, void* t, int64_t M, int64_t d_in, int64_t r,
+                         void* ws, size_t ws_bytes, hipStream_t s);
 int prefill_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
                 void* const* out, const int64_t* r, const int64_t* d_out, int n_proj, const int* base_of,
                 const int64_t* t_off, int64_t R, int64_t M, int64_t d_in, const lr_kv_target* kv,

@@ -45,6 +45,19 @@ int prefill_qkv(const void* x, const void* const* U, const void* const* V, const
     return prefill_launch(a2, PEPI_STORE, s);
 }
 
+// t[M, r] = x U as one dense product, rounded to bf16 (the rank-space rows handed to the factorized attention kernel)
+int prefill_rank_project(const void* x, const void* U, void* t, int64_t M, int64_t d_in, int64_t r,
+                         void* ws, size_t ws_bytes, hipStream_t s) {
+    const WsLayout L = ws_layout(ws, ws_bytes, M);
+    if (int pst = ws_prepare(ws, s); pst != LR_OK) return pst;
+    PArgs a; init_pargs(a, M, L); a.nprob = 1;
+    PProb& p = a.p[0]; zero_pprob(p);
+    p.A = (const bf16_t*)x; p.lda = (int)d_in; p.B = (const bf16_t*)U; p.K = (int)d_in; p.N = (int)r;
+    p.C = (bf16_t*)t; p.ldc = (int)r;
+    a.tiles_n_max = p.N / 128;
+    return prefill_launch(a, PEPI_STORE, s);
+}
+
 int prefill_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
                    int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s) {
     const void* Us[1] = {U}; const void* Vs[1] = {V}; const void* bs[1] = {bias}; void* outs[1] = {y};

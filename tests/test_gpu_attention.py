@@ -301,3 +301,85 @@ def test_prefill_attention_full_size_sampled_rows(G, oracle):
     # the rotated cache rows of those heads, bf16-rounded
     kh = G.host64(kc)[0][:, hs, :]
     assert max_rel_err(kh.reshape(T, -1), k_rot.reshape(T, -1)) <= 2.0 ** -8
+
+
+# ------------------------------------------------------------------ factorized queries (rank-space rows into the attention kernel)
+@pytest.mark.parametrize("base", [0.0, 10000.0])
+@pytest.mark.parametrize("with_bias", [False, True])
+@pytest.mark.parametrize("case,r_q", [(c, r) for c, r in zip(PREFILL_CASES, (64, 128, 384, 64, 256, 192))])
+def test_prefill_factorized_attention_matches_oracle(G, oracle, case, r_q, with_bias, base):
+    """lowrank_prefill_factorized_attention takes t_q [M, r] and V_q [r, H * 128] and rebuilds its query tiles inside the
+    kernel.  Expected values: the oracle's second stage q = t_q V_q (+ b_q) followed by the oracle's attention over the
+    dense cache; the cache must end up exactly as after the dense-query entry point."""
+    B = G.B
+    Bn, T, H, S_max, pos = case
+    E = 128
+    rng = np.random.default_rng(900 + T + H + r_q)
+    _, kc, vc, pos = make_case(rng, Bn, T, H, E, S_max, pos, "bf16")
+    tq = synth.to_dtype(rng.standard_normal((Bn * T, r_q)), "bf16")
+    Vq = synth.to_dtype(rng.standard_normal((r_q, H * E)) * r_q ** -0.5, "bf16")
+    bq = synth.to_dtype(0.3 * rng.standard_normal(H * E), "bf16") if with_bias else None
+    scale = E ** -0.5
+    kd, vd = G.dev(kc), G.dev(vc)
+    out = torch.full((Bn * T, H * E), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.lowrank_prefill_factorized_attention(G.dev(tq), G.dev(Vq), None if bq is None else G.dev(bq), kd, vd, G.dev(pos), T, out, scale, base)
+    torch.cuda.synchronize()
+    q64 = oracle.stage2(tq.f64, Vq.f64, None if bq is None else bq.f64)
+    ok = kc.f64.copy()
+    want = oracle.decode_attention(q64, ok, vc.f64, pos, T, scale, rope_base=base)
+    got = G.host64(out)
+    assert np.isfinite(got).all()
+    assert max_rel_err(got, want) <= TOL["bf16"]
+    # same cache as after the dense-query entry point (the key rotation does not depend on the queries)
+    kd2 = G.dev(kc)
+    qd = G.dev(synth.to_dtype(q64, "bf16"))
+    out2 = torch.empty_like(out)
+    B.lowrank_prefill_attention(qd, kd2, G.dev(vc), G.dev(pos), T, out2, scale, base)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.bits(kd), G.bits(kd2))
+    assert max_rel_err(got, G.host64(out2)) <= TOL["bf16"]
+
+
+def test_factorized_attention_chain_without_dense_q(G, oracle):
+    """The prefill chain as the paper draws it: rank-space rows t_q = x U_q (lowrank_rank_project), K and V through
+    lowrank_qkv into the dense cache only, then attention straight from t_q and V_q -- no dense q anywhere.  Checked against
+    the oracle's linear layers + attention."""
+    B = G.B
+    Bn, T, H, E, d, r = 1, 384, 4, 128, 512, 128
+    S_max = T + 16
+    rng = np.random.default_rng(4242)
+    x = synth.to_dtype(rng.standard_normal((T, d)), "bf16")
+    Us = [synth.to_dtype(rng.standard_normal((d, r)) * d ** -0.5, "bf16") for _ in range(3)]
+    Vs = [synth.to_dtype(rng.standard_normal((r, H * E)) * r ** -0.5, "bf16") for _ in range(3)]
+    pos = np.asarray([9], dtype=np.int32)
+    hist_k = synth.to_dtype(rng.standard_normal((Bn, S_max, H, E)), "bf16")
+    hist_v = synth.to_dtype(rng.standard_normal((Bn, S_max, H, E)), "bf16")
+    kd, vd, xd = G.dev(hist_k), G.dev(hist_v), G.dev(x)
+    ws = B.new_workspace(B.LR_OP_QKV, T, d, 3 * r, 3 * H * E, B.LR_BF16, "prefill")
+    tq = torch.full((T, r), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.lowrank_rank_project(xd, G.dev(Us[0]), tq, ws)
+    B.lowrank_qkv(xd, [G.dev(Us[1]), G.dev(Us[2])], [G.dev(Vs[1]), G.dev(Vs[2])], None, [None, None],
+                  dict(k_cache=kd, v_cache=vd, pos=G.dev(pos), tokens_per_seq=T, k_index=0, v_index=1), "prefill", ws)
+    out = torch.full((T, H * E), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.lowrank_prefill_factorized_attention(tq, G.dev(Vs[0]), None, kd, vd, G.dev(pos), T, out, E ** -0.5, 10000.0)
+    B.lowrank_workspace_status(ws)
+    # rank-space rows against the oracle's first stage
+    assert max_rel_err(G.host64(tq), oracle.stage1(x.f64, Us[0].f64)) <= TOL["bf16"]
+    # the whole chain in fp64
+    okc, ovc = hist_k.f64.copy(), hist_v.f64.copy()
+    q, k, v = oracle.qkv(x.f64, [u.f64 for u in Us], [w.f64 for w in Vs],
+                         kv=dict(k_cache=okc, v_cache=ovc, pos=pos, T=T, k_index=1, v_index=2))
+    want = oracle.decode_attention(q, okc, ovc, pos, T, E ** -0.5, rope_base=10000.0)
+    assert max_rel_err(G.host64(out), want) <= TOL["bf16"]
+
+
+def test_factorized_attention_rejects_what_it_cannot_run(G):
+    B = G.B
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    pos = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.LowrankError) as e:          # rank not a multiple of 64
+        B.lowrank_prefill_factorized_attention(z(4, 96), z(96, 128), None, z(1, 8, 1, 128), z(1, 8, 1, 128), pos, 4, z(4, 128), 1.0, 0.0)
+    assert e.value.status == -8
+    with pytest.raises(B.LowrankError) as e:          # head_dim 64
+        B.lowrank_prefill_factorized_attention(z(4, 64), z(64, 64), None, z(1, 8, 1, 64), z(1, 8, 1, 64), pos, 4, z(4, 64), 1.0, 0.0)
+    assert e.value.status == -8
