@@ -131,6 +131,11 @@ __device__ __forceinline__ void mma_block(f32x4_t (&acc)[MB][CPL], const WFrag<C
 // just passed, so the whole result turns NaN, not only the failing workgroup's part).
 // kCoherent: the activation rows were produced earlier in this launch by other workgroups and are read with
 // agent-coherent loads; kFused: hidden rows written by this tile are read by other workgroups of this launch.
+#ifdef LR_DECODE_COHERENT_ACTS
+constexpr bool kPlainActsFwd = false;      // see GridWaitPlain
+#else
+constexpr bool kPlainActsFwd = true;
+#endif
 struct NoSync { static constexpr bool kCoherent = false, kFused = false; __device__ __forceinline__ void operator()(uint32_t&) const {}
                 __device__ __forceinline__ void before_epilogue() const {} };
 // Same, for later tiles of a stage whose input other workgroups of this launch produced.
@@ -139,7 +144,7 @@ struct NoSyncCoherent { static constexpr bool kCoherent = true, kFused = true; _
 // Later tiles of a stage whose input (accumulators added with device-scope atomics, hidden rows or a finalised bf16
 // copy written with device-coherent stores) no workgroup on this XCD has read before the stage's barrier in this
 // launch: plain cached loads are safe (first touch misses L2) and let the other workgroups hit in L2.
-struct NoSyncPlain { static constexpr bool kCoherent = false, kFused = true; __device__ __forceinline__ void operator()() const {}
+struct NoSyncPlain { static constexpr bool kCoherent = !kPlainActsFwd, kFused = true; __device__ __forceinline__ void operator()() const {}
                      __device__ __forceinline__ void operator()(uint32_t&) const {}
                      __device__ __forceinline__ void before_epilogue() const {} };
 
@@ -644,8 +649,15 @@ struct GridWait {
 };
 
 // The same wait in front of a stage that reads its input with plain cached loads (see NoSyncPlain).
+// Building with -DLR_DECODE_COHERENT_ACTS makes every such stage read its input with device-coherent loads instead
+// (the fallback should the first-touch argument ever stop holding: about 1 us slower per packed-MLP call).
+#ifdef LR_DECODE_COHERENT_ACTS
+constexpr bool kPlainActs = false;
+#else
+constexpr bool kPlainActs = true;
+#endif
 struct GridWaitPlain : GridWait {
-    static constexpr bool kCoherent = false, kFused = true;
+    static constexpr bool kCoherent = !kPlainActs, kFused = true;
     __device__ __forceinline__ GridWaitPlain(const GridWait& g) : GridWait(g) {}
 };
 
