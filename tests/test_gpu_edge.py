@@ -516,3 +516,61 @@ def test_wait_that_gives_up_poisons_results_and_is_reported(G, oracle):
     B.lowrank_workspace_init(ws)
     assert max_rel_err(call(), want) <= TOL["bf16"]
     B.lowrank_workspace_status(ws)
+
+
+# ------------------------------------------------------------------ exact arithmetic: indexing errors cannot hide under a tolerance
+def _sparse_int(rng, shape, nnz_axis, nnz):
+    """Matrix of -1 / 0 / +1 with exactly `nnz` nonzeros along `nnz_axis` of every slice."""
+    a = np.zeros(shape)
+    n = shape[nnz_axis]
+    other = shape[1 - nnz_axis]
+    for i in range(other):
+        idx = rng.choice(n, size=nnz, replace=False)
+        sgn = rng.choice([-1.0, 1.0], size=nnz)
+        if nnz_axis == 0:
+            a[idx, i] = sgn
+        else:
+            a[i, idx] = sgn
+    return a
+
+
+@pytest.mark.parametrize("M,d_in,r,d_out,phase", [
+    (1, 4096, 384, 4096, "decode"), (7, 4096, 384, 4096, "decode"), (16, 1024, 256, 2048, "decode"),
+    (25, 4096, 384, 4096, "decode"), (32, 2048, 128, 1024, "decode"),
+    (300, 1024, 256, 2048, "prefill"), (2048, 4096, 384, 4096, "prefill"), (1000, 512, 128, 640, "prefill"),
+])
+def test_small_integer_inputs_give_exact_results(G, oracle, M, d_in, r, d_out, phase):
+    """x, U, V hold only -1, 0, +1, sparse enough that every partial sum, every rank-space value and every output is a small
+    integer: exactly representable in bf16 and in every accumulation order.  The tuned kernels must then reproduce the oracle
+    bit for bit (through the tolerance of the ordinary parity tests a misplaced tile of small values could slip)."""
+    B = G.B
+    rng = np.random.default_rng(31 * M + r)
+    x = _sparse_int(rng, (M, d_in), 1, 8)            # 8 nonzeros per row of x           -> |t| <= 8
+    U = rng.choice([-1.0, 0.0, 1.0], size=(d_in, r))
+    V = _sparse_int(rng, (r, d_out), 0, 16)          # 16 nonzeros per column of V       -> |y| <= 128
+    bias = rng.integers(-3, 4, size=d_out).astype(np.float64)
+    xt, Ut, Vt, bt = (synth.to_dtype(a, "bf16") for a in (x, U, V, bias))
+    assert B.lowrank_plan_name(B.LR_OP_LINEAR, M, d_in, r, d_out, B.LR_BF16, phase) != "generic"
+    y = G.run_linear(xt, Ut, Vt, bt, phase, "bf16")
+    want = oracle.linear(x, U, V, bias)
+    assert np.array_equal(G.host64(y), want)
+    # and the same through lowrank_qkv with a cache (three projections of different rank, V twice)
+    if M <= 32:
+        V2 = _sparse_int(rng, (r // 2, d_out), 0, 16)
+        U2 = rng.choice([-1.0, 0.0, 1.0], size=(d_in, r // 2))
+        H, E, S_max = d_out // 128, 128, 8
+        pos = rng.integers(0, S_max, size=M).astype(np.int32)
+        kc = torch.zeros((M, S_max, H, E), dtype=torch.bfloat16, device="cuda")
+        vc = torch.zeros_like(kc)
+        outs = [torch.full((M, d_out), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+        ws = B.new_workspace(B.LR_OP_QKV, M, d_in, 2 * r + r // 2, 3 * d_out, B.LR_BF16, phase)
+        Ud, Vd, U2d, V2d = G.dev(Ut), G.dev(Vt), G.dev(synth.to_dtype(U2, "bf16")), G.dev(synth.to_dtype(V2, "bf16"))
+        B.lowrank_qkv(G.dev(xt), [Ud, U2d, Ud], [Vd, V2d, Vd], None, outs,
+                      dict(k_cache=kc, v_cache=vc, pos=G.dev(pos), tokens_per_seq=1, k_index=1, v_index=2), phase, ws)
+        B.lowrank_workspace_status(ws)
+        assert np.array_equal(G.host64(outs[0]), oracle.linear(x, U, V))
+        assert np.array_equal(G.host64(outs[1]), oracle.linear(x, U2, V2))
+        assert np.array_equal(G.host64(outs[2]), oracle.linear(x, U, V))
+        kh = G.host64(kc)
+        for b in range(M):
+            assert np.array_equal(kh[b, pos[b]].reshape(-1), oracle.linear(x[b:b + 1], U2, V2)[0])

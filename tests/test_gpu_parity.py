@@ -196,7 +196,7 @@ def test_config4_four_layer_stack(G, oracle):
         assert max_rel_err(G.host64(hn)[rows], oracle.packed_mlp(G.host64(o)[rows], *margs)) <= TOL["bf16"], li
         chain = oracle.packed_mlp(oracle.linear(oracle.qkv(chain, Uf, Vf)[0], ta["U_o"].f64, ta["V_o"].f64), *margs)
         drift = max_rel_err(G.host64(hn)[rows], chain)
-        diag_report(f"config 4 stack S={S}: after layer {li} (ranks {ra}/{rm}), whole chain", G.host64(hn)[rows], chain)
+        diag_report(f"config 4 stack S={S}: after layer {li} (ranks {ra}/{rm}), whole chain", G.host64(hn)[rows], chain, gate_blocks=False)
         assert drift <= 3 * (li + 1) * TOL["bf16"]          # three calls per layer, each within the tolerance
 
 

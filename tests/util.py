@@ -47,13 +47,17 @@ def column_block_err(got, want, block: int = 64) -> float:
     return worst
 
 
-def diag_report(label, got, exact, faithful=None, dtype="bf16") -> None:
+def diag_report(label, got, exact, faithful=None, dtype="bf16", gate_blocks=True) -> None:
     """Record the diagnostics of one output tensor: normwise-max error against the exact fp64 definition (the
-    gated number), against the rounding-faithful diagnostic oracle, the worst 64-column block, and the fraction of
-    elements outside the elementwise check."""
+    gated number), against the rounding-faithful diagnostic oracle, the worst 64-column block (gated too unless
+    gate_blocks is False), and the fraction of elements outside the elementwise check."""
     tol = TOL[dtype]
     line = f"{label:58s} exact {max_rel_err(got, exact):.2e}  per-64-col {column_block_err(got, exact):.2e}  " \
            f"elementwise-miss {elementwise_violations(got, exact, tol):.1e}"
     if faithful is not None:
         line += f"  vs rounding-faithful {max_rel_err(got, faithful):.2e}"
     DIAG_LINES.append(line)
+    # gated as well (the tolerance applied to every block of 64 columns against that block's own largest value): a wrong tile of
+    # small values cannot hide behind the tensor's maximum
+    if gate_blocks:
+        assert column_block_err(got, exact) <= tol, label
