@@ -245,7 +245,7 @@ size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total,
 
 /*
  * Optional: prepare a workspace ahead of its first use, or again after lowrank_workspace_status reported a
- * failure (enqueues three small launches on `stream`; no synchronisation).  The decode-attention workspace keeps
+ * failure (enqueues two small launches on `stream`; no synchronisation).  The decode-attention workspace keeps
  * no state between calls and needs no preparation.
  */
 int lowrank_workspace_init(void *workspace, size_t workspace_bytes, void *stream);

@@ -143,29 +143,26 @@ int generic_pack_concat(const void* const* U_list, const int64_t* r_list, int n,
     return LR_OK;
 }
 
-// Check-and-prepare for calls that run no fused decode kernel but use flags in the workspace (prefill products that
-// share K): when the control block does not carry the ready word, every workgroup zeroes its slice of the control block,
-// the flags and the accumulator areas; a second single-thread launch then writes the word (stream order makes it the
-// last write).  Two tiny launches; nothing is copied back and nothing waits.
-__global__ void __launch_bounds__(256) k_ws_prepare_zero(char* ws) {
-    const Ctrl* c = reinterpret_cast<const Ctrl*>(ws);
+// Check-and-prepare for launches that keep state in the workspace without being a fused decode kernel (the prefill product
+// that shares K, lowrank_workspace_init): ONE small launch.  When the control block carries the ready word (every call but
+// the first) the single workgroup leaves at once; otherwise it zeroes the control block, the flags and the accumulator areas
+// (8 MiB by 1024 threads: some tens of microseconds, once) and then writes the word.  Nothing is copied back, nothing waits.
+__global__ void __launch_bounds__(1024) k_ws_prepare(char* ws) {
+    Ctrl* c = reinterpret_cast<Ctrl*>(ws);
     if (__hip_atomic_load(&c->magic, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == kCtrlReady) return;
     uint2* head = reinterpret_cast<uint2*>(ws) + 1;                               // behind the magic word
     const size_t n_head = (kHeaderBytes + kSkFlagBytes) / 8 - 1;
     uint4* acc = reinterpret_cast<uint4*>(ws + kHeaderBytes + kSkFlagBytes + kDecPartBytes);
     const size_t n_acc = 2 * kAccBytes / 16;
-    const size_t tid = (size_t)blockIdx.x * 256 + threadIdx.x, nth = (size_t)gridDim.x * 256;
-    for (size_t i = tid; i < n_head; i += nth) head[i] = make_uint2(0u, 0u);
-    for (size_t i = tid; i < n_acc; i += nth) acc[i] = make_uint4(0u, 0u, 0u, 0u);
-}
-__global__ void k_ws_prepare_mark(Ctrl* c) {
-    if (__hip_atomic_load(&c->magic, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != kCtrlReady)
-        __hip_atomic_store(&c->magic, kCtrlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (size_t i = threadIdx.x; i < n_head; i += 1024) head[i] = make_uint2(0u, 0u);
+    for (size_t i = threadIdx.x; i < n_acc; i += 1024) acc[i] = make_uint4(0u, 0u, 0u, 0u);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");                             // the zeroes are in memory before the word says so
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(&c->magic, kCtrlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 int ws_prepare(void* ws, hipStream_t s) {
-    hipLaunchKernelGGL(k_ws_prepare_zero, dim3(128), dim3(256), 0, s, (char*)ws);
-    hipLaunchKernelGGL(k_ws_prepare_mark, dim3(1), dim3(1), 0, s, (Ctrl*)ws);
+    hipLaunchKernelGGL(k_ws_prepare, dim3(1), dim3(1024), 0, s, (char*)ws);
     return launch_status("workspace preparation");
 }
 

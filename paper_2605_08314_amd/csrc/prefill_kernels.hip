@@ -815,6 +815,8 @@ static int launch_persist(PArgs a, hipStream_t s, bool share_k = false) {
     }
     if constexpr (EPI == PEPI_STORE && BM == 256 && (BN == 256 || BN == 192)) {
         if (a.sk) {
+            // the only prefill launch that keeps state in the workspace (flags, error word): make sure the control block is valid
+            if (int pst = ws_prepare(reinterpret_cast<char*>(a.sk_flags) - kHeaderBytes, s); pst != LR_OK) return pst;
             hipLaunchKernelGGL((k_prefill_persist<BM, BN, EPI, MINB, true>), dim3((unsigned)grid), dim3(256), 0, s, a);
             return launch_status("prefill gemm");
         }

@@ -20,7 +20,6 @@ int prefill_qkv(const void* x, const void* const* U, const void* const* V, const
                 void* ws, size_t ws_bytes, hipStream_t s) {
     const WsLayout L = ws_layout(ws, ws_bytes, M);
     bf16_t* T = (bf16_t*)L.staging;                 // [M, R] bf16
-    if (int pst = ws_prepare(ws, s); pst != LR_OK) return pst;      // shared-K flags and the error word must be valid
     PArgs a1; init_pargs(a1, M, L);
     for (int i = 0; i < n_proj; ++i) {
         if (base_of[i] != i) continue;
@@ -49,7 +48,6 @@ int prefill_qkv(const void* x, const void* const* U, const void* const* V, const
 int prefill_rank_project(const void* x, const void* U, void* t, int64_t M, int64_t d_in, int64_t r,
                          void* ws, size_t ws_bytes, hipStream_t s) {
     const WsLayout L = ws_layout(ws, ws_bytes, M);
-    if (int pst = ws_prepare(ws, s); pst != LR_OK) return pst;
     PArgs a; init_pargs(a, M, L); a.nprob = 1;
     PProb& p = a.p[0]; zero_pprob(p);
     p.A = (const bf16_t*)x; p.lda = (int)d_in; p.B = (const bf16_t*)U; p.K = (int)d_in; p.N = (int)r;
@@ -74,7 +72,6 @@ int prefill_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_
     const WsLayout L = ws_layout(ws, ws_bytes, M);
     bf16_t* T = (bf16_t*)L.staging;                                         // [M, r_g + r_u + r_d] bf16
     bf16_t* H = (bf16_t*)(L.staging + align256((size_t)M * r_all * 2));     // [M, ffn] bf16
-    if (int pst = ws_prepare(ws, s); pst != LR_OK) return pst;      // shared-K flags and the error word must be valid
     PArgs a; init_pargs(a, M, L); a.nprob = 1;
     {   // T_gu = x U_gu
         PProb& p = a.p[0]; zero_pprob(p);
