@@ -142,7 +142,7 @@ def run_prefill_ranks(torch, B, gen, S_list=(512, 2048, 8192), ranks=((384, 768)
             tiles = {"x*U_qkv": B.lowrank_prefill_tile(S, D, ra, 3), "t*V_qkv": B.lowrank_prefill_tile(S, ra, D, 3),
                      "x*U_gu": B.lowrank_prefill_tile(S, D, 2 * rm, 1), "h*U_d": B.lowrank_prefill_tile(S, FFN, rm, 1),
                      "t*V_d": B.lowrank_prefill_tile(S, rm, D, 1)}
-            r["tiles"] = {k: f"{v[0]}x{v[1]}" + ("+shareK" if v[2] else "") for k, v in tiles.items()}
+            r["tiles"] = {k: f"{v[0]}x{v[1]}" + ("+shareK" if v[2] == 1 else (f"+splitK{v[2]}" if v[2] > 1 else "")) for k, v in tiles.items()}
             rows[f"r{ra}-{rm}_S{S}"] = r
         del ly
     return rows

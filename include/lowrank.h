@@ -279,9 +279,11 @@ const char *lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, 
  * Tile selection of the prefill phase (Section 3: phase-specific kernels; heterogeneous ranks multiply the GEMM
  * shapes a layer runs): for n_products (1..8) dense products C[M, N] = A[M, K] * B[K, N] of one launch -- the
  * rank-space products x U_i of one call, or its reconstruction products t_i V_i -- the workgroup tile
- * tile_m x tile_n (256x256, 256x192 or 128x128) and whether the K range of a tile is shared between workgroups
- * (long K, few tiles: the h U_d product of the MLP).  gate_up != 0 asks for the fused gate/up kernel (always
- * 128x128, two accumulator sets).  Pure host function, deterministic, no GPU needed.  LR_ERR_UNSUPPORTED when
+ * tile_m x tile_n (256x256, 256x192 or 128x128) and how the K range is divided: *share_k = 0 (every tile runs its whole K),
+ * 1 (long K, few tiles, thousands of rows -- the h U_d product of the MLP: workgroups share a tile's K range and hand
+ * partial tiles to the one that holds its first k-step) or n >= 2 (few rows and a long K -- the rank-space products of a
+ * prompt of some hundred tokens: K is cut into n chunks that run as products of one launch, a second small launch adds
+ * their fp32 partial sums).  gate_up != 0 asks for the fused gate/up kernel (always 128x128, two accumulator sets).  Pure host function, deterministic, no GPU needed.  LR_ERR_UNSUPPORTED when
  * the shape is outside the matrix-core rule (K % 64 == 0, N % 128 == 0).
  */
 int lowrank_prefill_tile(int64_t M, int64_t K, int64_t N, int n_products, int gate_up,

@@ -117,10 +117,11 @@ def lowrank_version() -> str:
 
 
 def lowrank_prefill_tile(M: int, K: int, N: int, n_products: int = 1, gate_up: bool = False):
-    """(tile_m, tile_n, share_k) the prefill dispatcher picks for n_products products [M, K] x [K, N]."""
+    """(tile_m, tile_n, share_k) the prefill dispatcher picks for n_products products [M, K] x [K, N];
+    share_k: 0 = none, 1 = shared-K walk, n >= 2 = K cut into n chunks (split-K with a reduction launch)."""
     bm, bn, sk = _int(0), _int(0), _int(0)
     _check(_lib.lowrank_prefill_tile(M, K, N, n_products, int(gate_up), ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(sk)))
-    return bm.value, bn.value, bool(sk.value)
+    return bm.value, bn.value, sk.value
 
 
 def lowrank_workspace_bytes(op: int, M: int, d_in: int, r_total: int, d_out: int, dtype: int, phase) -> int:

@@ -4,8 +4,8 @@
 
 namespace lr {
 
-enum { PEPI_STORE = 0, PEPI_GATEUP = 1 };
-constexpr int kMaxPProb = 8;
+enum { PEPI_STORE = 0, PEPI_GATEUP = 1, PEPI_PARTIAL = 2 };     // PARTIAL: fp32 partial sums of a K chunk to P.Cf (no bias, no cache)
+constexpr int kMaxPProb = 16;
 
 // One dense product C[M, N] = A[M, K] * B[K, N] (+ epilogue); A, B, C row-major bf16.
 struct PProb {
@@ -13,6 +13,7 @@ struct PProb {
     const bf16_t* A2; int lda2; const bf16_t* B2; int K2;   // PEPI_GATEUP: the up-branch product
     int N;
     bf16_t* C; int ldc;                                     // nullable for STORE when only the cache is wanted
+    float* Cf;                                              // PEPI_PARTIAL: fp32 output [M, ldc]
     const bf16_t* bias; const bf16_t* bias2;
     void* cache; const int32_t* pos; int S_max; int T;      // optional dense-cache scatter of the rows of C
 };

@@ -545,6 +545,29 @@ __device__ __forceinline__ void wave_epilogue(const f32x16_t (&acc)[BM / 64][BN 
                                               const float* parts = nullptr, int part0 = 0, int part1 = 0, float poison = 0.f) {
     // parts: partial tiles of slots [part0, part1) are added (shared-K owner), skipping empty ones
     constexpr int MI = BM / 64, NI = BN / 64;
+    if constexpr (EPI == PEPI_PARTIAL) {
+        // fp32 partial sums of one K chunk, straight from the accumulators: lane (li, lg) holds, for tile row 32 mi + li of
+        // its wave's quarter, columns 32 ni + 8 vg + 4 lg .. + 3
+        asm volatile("s_nop 15\n\ts_nop 15" : "+v"(lane));
+        const int wm = wave >> 1, wn = wave & 1, li = lane & 31, lg = lane >> 5;
+        float* const Cf = P.Cf;
+        const int ldc = P.ldc, N = P.N;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int row = m0 + wm * (BM / 2) + mi * 32 + li;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    const int col = n0 + wn * (BN / 2) + ni * 32 + 8 * vg + 4 * lg;
+                    const float4 o = make_float4(acc_elem(acc[mi][ni][4 * vg + 0]), acc_elem(acc[mi][ni][4 * vg + 1]),
+                                                 acc_elem(acc[mi][ni][4 * vg + 2]), acc_elem(acc[mi][ni][4 * vg + 3]));
+                    if (row < M && col < N) *reinterpret_cast<float4*>(Cf + (size_t)row * ldc + col) = o;
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
+    }
     // the lane index goes through an opaque move: everything derived from it is recomputed here, per
     // tile, instead of being hoisted out of the tile loop and held (or spilled) across the main loop
     // ... and the matrix pipeline gets the distance it needs before its results are read (32 wait states)
@@ -859,21 +882,100 @@ static bool want_share_k(const PArgs& a) {
 
 // The tile the dispatcher would pick for `n` products C[M, N] = A[M, K] * B[K, N] launched together (plain
 // epilogue), and whether they would share K between workgroups.  Pure host logic (no device needed).
+static int split_k_chunks(const PArgs& a);
 void prefill_plan_query(int64_t M, int64_t K, int64_t N, int n, bool gateup, int* bm, int* bn, int* share_k) {
     PArgs a;
     memset(&a, 0, sizeof(a));
     a.M = (int)M; a.nprob = n < 1 ? 1 : (n > kMaxPProb ? kMaxPProb : n);
-    for (int i = 0; i < a.nprob; ++i) { a.p[i].K = (int)K; a.p[i].N = (int)N; }
+    for (int i = 0; i < a.nprob; ++i) { a.p[i].K = (int)K; a.p[i].N = (int)N; a.p[i].C = reinterpret_cast<bf16_t*>(sizeof(float)); }
     a.sk_slots = reinterpret_cast<float*>(sizeof(float));      // "a shared-K area exists"; never dereferenced here
     *share_k = 0;
     if (gateup) { *bm = 128; *bn = 128; return; }
+    if (const int split = split_k_chunks(a); split >= 2) { *share_k = split; *bm = 128; *bn = 128; return; }
     if (want_share_k(a)) { *share_k = 1; *bm = 256; *bn = (N % 192 == 0) ? 192 : 256; return; }
     const int t = pick_tile(a);
     *bm = t == 128 ? 128 : 256; *bn = t;
 }
 
+// C[m, n] = sum over `split` partial matrices (fp32, `stride` floats apart), rounded to bf16
+__global__ void __launch_bounds__(256) k_prefill_reduce(const float* __restrict__ part, int split, size_t stride,
+                                                        bf16_t* __restrict__ C, int ldc, int M, int N) {
+    const size_t total = (size_t)M * (size_t)(N / 4);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t m = i / (size_t)(N / 4);
+        const int n = 4 * (int)(i - m * (size_t)(N / 4));
+        const float* src = part + m * (size_t)N + n;
+        float4 acc = *reinterpret_cast<const float4*>(src);
+        for (int sp = 1; sp < split; ++sp) {
+            const float4 v = *reinterpret_cast<const float4*>(src + (size_t)sp * stride);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *reinterpret_cast<uint2*>(C + m * (size_t)ldc + n) = make_uint2(ppack2(acc.x, acc.y), ppack2(acc.z, acc.w));
+    }
+}
+
+// Few rows and a long K (a rank-space product x U or h U_d of a prompt of some hundred tokens: 24..192 tiles of 128 x 128
+// for 512 workgroup slots, each with hundreds of k-steps): the K range is cut into `split` chunks that run as separate
+// products of ONE launch and leave fp32 partial sums in the workspace tail (the area of the shared-K partial tiles, unused by
+// such a launch); a small second launch adds them in chunk order (deterministic) and rounds once.  Returns how many chunks
+// would be used (0 or 1: not worth it or not possible).
+static int split_k_chunks(const PArgs& a) {
+    if (!a.sk_slots || a.nprob < 1) return 0;
+    long t128 = 0, n_sum = 0;
+    for (int i = 0; i < a.nprob; ++i) {
+        const PProb& p = a.p[i];
+        if (p.bias || p.cache || !p.C || p.K != a.p[0].K || (p.N & 3)) return 0;
+        t128 += (long)((a.M + 127) / 128) * ((p.N + 127) / 128);
+        n_sum += p.N;
+    }
+    if (t128 > 192) return 0;                                   // enough tiles to fill the chip as they are
+    long split = 512 / t128;
+    const long by_k = a.p[0].K / 512, by_prob = kMaxPProb / a.nprob;
+    const long by_mem = (long)(kSkSlotBytes / ((size_t)a.M * (size_t)n_sum * 4));
+    if (by_k < split) split = by_k;
+    if (by_prob < split) split = by_prob;
+    if (by_mem < split) split = by_mem;
+    if (split > 8) split = 8;
+    return split >= 2 ? (int)split : 0;
+}
+
+static int launch_split_k(const PArgs& a, int split, hipStream_t s) {
+    const int K = a.p[0].K;
+    const int chunk = ((K / 64 + split - 1) / split) * 64;
+    PArgs b = a;
+    b.nprob = 0;
+    size_t off[kMaxPProb];
+    int used[kMaxPProb];
+    size_t o = 0;
+    for (int i = 0; i < a.nprob; ++i) { off[i] = o; o += (size_t)split * (size_t)a.M * (size_t)a.p[i].N; used[i] = 0; }
+    for (int sp = 0; sp < split; ++sp)
+        for (int i = 0; i < a.nprob; ++i) {
+            const int k0 = sp * chunk, kc = K - k0 < chunk ? K - k0 : chunk;
+            if (kc <= 0) continue;
+            PProb& p = b.p[b.nprob++];
+            p = a.p[i];
+            p.A = a.p[i].A + k0; p.B = a.p[i].B + (size_t)k0 * (size_t)a.p[i].N; p.K = kc;
+            p.C = nullptr; p.Cf = a.sk_slots + off[i] + (size_t)sp * (size_t)a.M * (size_t)a.p[i].N; p.ldc = a.p[i].N;
+            used[i] = sp + 1;
+        }
+    int st = launch_persist<128, 128, PEPI_PARTIAL, 2>(b, s, false);
+    if (st != LR_OK) return st;
+    for (int i = 0; i < a.nprob; ++i) {
+        const size_t total = (size_t)a.M * (size_t)(a.p[i].N / 4);
+        size_t blocks = (total + 255) / 256;
+        if (blocks > 2048) blocks = 2048;
+        hipLaunchKernelGGL(k_prefill_reduce, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)(a.sk_slots + off[i]), used[i],
+                           (size_t)a.M * (size_t)a.p[i].N, a.p[i].C, a.p[i].ldc, a.M, a.p[i].N);
+    }
+    return launch_status("prefill split-K reduction");
+}
+
 int prefill_launch(const PArgs& a, int epi, hipStream_t s) {
     if (a.M <= 0 || a.nprob <= 0) return LR_OK;
+    if (epi == PEPI_STORE) {
+        const int split = split_k_chunks(a);
+        if (split >= 2) return launch_split_k(a, split, s);
+    }
     if (epi == PEPI_GATEUP) return launch_persist<128, 128, PEPI_GATEUP, 2>(a, s);
     if (want_share_k(a)) {
         // 192-wide tiles when they cover the columns exactly: more, aligned pieces of the K range per row block

@@ -122,22 +122,31 @@ def test_prefill_tile_selection_over_the_benchmark_shapes(B):
     for M, K, N, n in shapes:
         bm, bn, sk = B.lowrank_prefill_tile(M, K, N, n)
         assert (bm, bn) in {(256, 256), (256, 192), (128, 128)}, (M, K, N, n)
-        assert not sk or (bm == 256 and K >= 4096 and n * ((M + 255) // 256) * ((N + 255) // 256) <= 128), (M, K, N, n)
+        t128 = n * ((M + 127) // 128) * ((N + 127) // 128)
+        if sk == 1:      # shared-K walk: tall tiles, long K, few tiles
+            assert bm == 256 and K >= 4096 and n * ((M + 255) // 256) * ((N + 255) // 256) <= 128, (M, K, N, n)
+        elif sk >= 2:    # K cut into sk chunks: only when the 128 x 128 tiles leave most of the 512 workgroup slots empty
+            assert (bm, bn) == (128, 128) and t128 <= 192 and t128 * sk <= 512 and K // sk >= 512 and n * sk <= 16, (M, K, N, n, sk)
+        else:
+            assert sk == 0
         if bn == 192:
             assert N % 192 == 0 or ((N + 191) // 192) * 192 - N < ((N + 255) // 256) * 256 - N      # 192-wide only where it wastes fewer columns
         assert B.lowrank_prefill_tile(M, K, N, n) == (bm, bn, sk)                                       # deterministic
     # S = 8192, ranks 384/768 (the benchmark's layer): reconstruction products on 256x256, the rank-space products
     # of width 1152 / 1536 on 256x192, h U_d (K = 11008, 96 tiles for 256 CUs) shares K on 256x192
-    assert B.lowrank_prefill_tile(8192, 384, 4096, 3) == (256, 256, False)
-    assert B.lowrank_prefill_tile(8192, 4096, 384, 3) == (256, 192, False)
-    assert B.lowrank_prefill_tile(8192, 4096, 1536, 1) == (256, 192, False)
-    assert B.lowrank_prefill_tile(8192, 11008, 768, 1) == (256, 192, True)
-    assert B.lowrank_prefill_tile(8192, 768, 4096, 1) == (256, 256, False)
-    # few rows: every product fits the chip as 128x128 tiles in one round
-    assert B.lowrank_prefill_tile(512, 4096, 384, 3) == (128, 128, False)
-    assert B.lowrank_prefill_tile(512, 11008, 768, 1) == (128, 128, False)
+    assert B.lowrank_prefill_tile(8192, 384, 4096, 3) == (256, 256, 0)
+    assert B.lowrank_prefill_tile(8192, 4096, 384, 3) == (256, 192, 0)
+    assert B.lowrank_prefill_tile(8192, 4096, 1536, 1) == (256, 192, 0)
+    assert B.lowrank_prefill_tile(8192, 11008, 768, 1) == (256, 192, 1)
+    assert B.lowrank_prefill_tile(8192, 768, 4096, 1) == (256, 256, 0)
+    # few rows: the rank-space products (long K, 24..36 tiles of 128x128 for 512 slots) cut K into chunks,
+    # the reconstruction products (K = rank) run as they are
+    assert B.lowrank_prefill_tile(512, 4096, 384, 3) == (128, 128, 5)      # 36 tiles: 16 products at most -> 5 chunks
+    assert B.lowrank_prefill_tile(512, 11008, 768, 1) == (128, 128, 8)
+    assert B.lowrank_prefill_tile(512, 384, 4096, 3) == (128, 128, 0)
+    assert B.lowrank_prefill_tile(2048, 11008, 768, 1) == (128, 128, 5)     # 96 tiles x 5 <= 512
     # the fused gate/up kernel has one shape; shapes outside the matrix-core rule are refused
-    assert B.lowrank_prefill_tile(8192, 768, 11008, 1, gate_up=True) == (128, 128, False)
+    assert B.lowrank_prefill_tile(8192, 768, 11008, 1, gate_up=True) == (128, 128, 0)
     with pytest.raises(B.LowrankError):
         B.lowrank_prefill_tile(8192, 100, 4096, 1)
 

@@ -538,6 +538,7 @@ def _sparse_int(rng, shape, nnz_axis, nnz):
     (1, 4096, 384, 4096, "decode"), (7, 4096, 384, 4096, "decode"), (16, 1024, 256, 2048, "decode"),
     (25, 4096, 384, 4096, "decode"), (32, 2048, 128, 1024, "decode"),
     (300, 1024, 256, 2048, "prefill"), (2048, 4096, 384, 4096, "prefill"), (1000, 512, 128, 640, "prefill"),
+    (333, 2112, 256, 640, "prefill"),        # ragged rows; K cut into chunks of 576, 576, 576 and 384 (split-K with a shorter last chunk)
 ])
 def test_small_integer_inputs_give_exact_results(G, oracle, M, d_in, r, d_out, phase):
     """x, U, V hold only -1, 0, +1, sparse enough that every partial sum, every rank-space value and every output is a small
