@@ -109,6 +109,7 @@ int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& 
                          int grid, int nw, bool t16, hipStream_t s);
 int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, int nw, bool t16, hipStream_t s);
 extern unsigned long long* g_trace_buffer;   // host copy of the trace pointer (NULL unless a trace build set it)
+bool decode_grid_is_resident(const void* kernel, int threads, int grid);   // occupancy of this very kernel x compute units >= grid
 int decode_resident_grid();   // workgroups that are certainly co-resident (number of CUs), cached; 0 when the device is shared
 // Process-wide settings behind lowrank_configure.
 extern bool g_device_shared;        // other work may occupy CUs: no launch may rely on all of its workgroups being resident

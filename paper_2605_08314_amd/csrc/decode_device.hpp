@@ -715,6 +715,7 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     uint32_t* tcp = nullptr;
     const CtrlGate gate = {fa.fc.ctrl, fa.fc.acc0, fa.fc.acc_bytes, &cl, &cs, &shift, &tcp, T16, &s_bad};
     bool resolved = false;
+    LR_STAMP(0);
     for (int tile = blockIdx.x; tile < fa.s1.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s1, tile);
         if (!resolved) decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, gate, shift, tcp);
@@ -724,7 +725,9 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     }
     if (!resolved) gate();
     const uint32_t p = cs.p;
+    LR_STAMP(1);
     fused_first_arrive(fa.fc, cs);
+    LR_STAMP(2);
     const GridWait gw = {fa.fc.ctrl->cnt[p][0], gridDim.x, &fa.fc.ctrl->error, fa.fc.spin_limit, &s_bad, 3, fa.fc.trace, true};
     bool waited = false;
     for (int tile = blockIdx.x; tile < fa.s2.total_tiles; tile += gridDim.x) {
@@ -741,6 +744,7 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
         __syncthreads();
     }
     if (blockIdx.x == 0 && !waited) { gw(); fused_publish(fa.fc, cs); }
+    LR_STAMP(10);
 }
 
 // lowrank_packed_mlp: four stages, three barriers.

@@ -11,13 +11,10 @@ static int launch_f2(const FusedCommon& fc, const DStage& s1, const DStage& s2, 
     for (int i = 0; i < NP; ++i) { fa.s1.p[i] = s1.p[i]; fa.s2.p[i] = s2.p[i]; }
     fa.s1.nprob = s1.nprob; fa.s1.M = s1.M; fa.s1.total_tiles = s1.total_tiles;
     fa.s2.nprob = s2.nprob; fa.s2.M = s2.M; fa.s2.total_tiles = s2.total_tiles;
-    if (t16) {
-        if (nw == 8) hipLaunchKernelGGL((k_decode_fused2<MB, C1, C2, 3, NP, 8, true>), dim3((unsigned)grid), dim3(512), 0, s, fa);
-        else hipLaunchKernelGGL((k_decode_fused2<MB, C1, C2, 3, NP, 4, true>), dim3((unsigned)grid), dim3(256), 0, s, fa);
-    } else {
-        if (nw == 8) hipLaunchKernelGGL((k_decode_fused2<MB, C1, C2, 3, NP, 8, false>), dim3((unsigned)grid), dim3(512), 0, s, fa);
-        else hipLaunchKernelGGL((k_decode_fused2<MB, C1, C2, 3, NP, 4, false>), dim3((unsigned)grid), dim3(256), 0, s, fa);
-    }
+    void (*kern)(Fused2Args<NP>) = t16 ? (nw == 8 ? k_decode_fused2<MB, C1, C2, 3, NP, 8, true> : k_decode_fused2<MB, C1, C2, 3, NP, 4, true>)
+                                       : (nw == 8 ? k_decode_fused2<MB, C1, C2, 3, NP, 8, false> : k_decode_fused2<MB, C1, C2, 3, NP, 4, false>);
+    if (!decode_grid_is_resident((const void*)kern, 64 * nw, grid)) return LR_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * nw), 0, s, fa);
     return launch_status("fused decode (two stages)");
 }
 
@@ -36,6 +33,29 @@ int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& 
                                  : launch_f2_cpl<1, 8>(fc, s1, s2, cpl1, cpl2, grid, nw, t16, s);
     return small ? launch_f2_cpl<2, 4>(fc, s1, s2, cpl1, cpl2, grid, nw, t16, s)
                  : launch_f2_cpl<2, 8>(fc, s1, s2, cpl1, cpl2, grid, nw, t16, s);
+}
+
+// Whether `grid` workgroups of this very kernel (threads per workgroup as launched, static LDS only) can be resident at the
+// same time on an otherwise idle device: the runtime's occupancy figure for the kernel times the number of compute units.
+// Queried once per kernel; sets the error message when it does not fit.
+bool decode_grid_is_resident(const void* kernel, int threads, int grid) {
+    struct Seen { const void* k; int per_cu; };
+    static Seen seen[64];
+    static int n_seen = 0;
+    int per_cu = -1;
+    for (int i = 0; i < n_seen; ++i)
+        if (seen[i].k == kernel) per_cu = seen[i].per_cu;
+    if (per_cu < 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, 0) != hipSuccess) { (void)hipGetLastError(); n = 1; }   // (no figure: trust the launch bounds)
+        per_cu = n;
+        if (n_seen < 64) seen[n_seen++] = Seen{kernel, per_cu};
+    }
+    const int cus = decode_resident_grid();
+    if ((long)per_cu * (cus > 0 ? cus : 1) >= grid) return true;
+    set_error("a fused decode launch of %d workgroups cannot be resident on this device (%d per compute unit x %d); "
+              "use lowrank_configure(LR_CFG_DEVICE_SHARED, 1) for one launch per stage", grid, per_cu, cus);
+    return false;
 }
 
 int decode_resident_grid() {

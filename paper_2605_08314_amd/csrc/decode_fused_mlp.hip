@@ -5,13 +5,10 @@ namespace lr {
 
 template <int MB, int CA, int CC, int CD>
 static int launch_mlp(const FusedMlpArgs& fa, int grid, int nw, bool t16, hipStream_t s) {
-    if (t16) {
-        if (nw == 8) hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 8, true>), dim3((unsigned)grid), dim3(512), 0, s, fa);
-        else hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 4, true>), dim3((unsigned)grid), dim3(256), 0, s, fa);
-    } else {
-        if (nw == 8) hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 8, false>), dim3((unsigned)grid), dim3(512), 0, s, fa);
-        else hipLaunchKernelGGL((k_decode_fused_mlp<MB, CA, CC, CD, 3, 4, false>), dim3((unsigned)grid), dim3(256), 0, s, fa);
-    }
+    void (*kern)(FusedMlpArgs) = t16 ? (nw == 8 ? k_decode_fused_mlp<MB, CA, CC, CD, 3, 8, true> : k_decode_fused_mlp<MB, CA, CC, CD, 3, 4, true>)
+                                     : (nw == 8 ? k_decode_fused_mlp<MB, CA, CC, CD, 3, 8, false> : k_decode_fused_mlp<MB, CA, CC, CD, 3, 4, false>);
+    if (!decode_grid_is_resident((const void*)kern, 64 * nw, grid)) return LR_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * nw), 0, s, fa);
     return launch_status("fused decode (packed MLP)");
 }
 
