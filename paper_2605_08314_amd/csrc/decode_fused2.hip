@@ -1,5 +1,6 @@
 // Launcher of the fused two-stage decode kernel (lowrank_linear, lowrank_qkv).
 #include <stdlib.h>
+#include <mutex>
 #include "decode_device.hpp"
 
 namespace lr {
@@ -42,6 +43,8 @@ bool decode_grid_is_resident(const void* kernel, int threads, int grid) {
     struct Seen { const void* k; int per_cu; };
     static Seen seen[64];
     static int n_seen = 0;
+    static std::mutex mu;                                        // entry points may be called from several host threads
+    std::lock_guard<std::mutex> lock(mu);
     int per_cu = -1;
     for (int i = 0; i < n_seen; ++i)
         if (seen[i].k == kernel) per_cu = seen[i].per_cu;
