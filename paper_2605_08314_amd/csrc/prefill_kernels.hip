@@ -897,20 +897,33 @@ void prefill_plan_query(int64_t M, int64_t K, int64_t N, int n, bool gateup, int
     *bm = t == 128 ? 128 : 256; *bn = t;
 }
 
-// C[m, n] = sum over `split` partial matrices (fp32, `stride` floats apart), rounded to bf16
-__global__ void __launch_bounds__(256) k_prefill_reduce(const float* __restrict__ part, int split, size_t stride,
-                                                        bf16_t* __restrict__ C, int ldc, int M, int N) {
-    const size_t total = (size_t)M * (size_t)(N / 4);
+// One launch adds the partial matrices of every product of a split-K launch: blockIdx.y is the product,
+// C[m, n] = sum over `split` partial matrices (fp32, `stride` floats apart) in chunk order, rounded to bf16 once.
+struct RProb {
+    const float* part;
+    bf16_t* C;
+    size_t stride;
+    int ldc, N, split;
+};
+struct RArgs {
+    int M;
+    RProb p[kMaxPProb / 2];
+};
+
+__global__ void __launch_bounds__(256) k_prefill_reduce(const RArgs a) {
+    const RProb& r = a.p[blockIdx.y];
+    const int N = r.N, split = r.split;
+    const size_t total = (size_t)a.M * (size_t)(N / 4);
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         const size_t m = i / (size_t)(N / 4);
         const int n = 4 * (int)(i - m * (size_t)(N / 4));
-        const float* src = part + m * (size_t)N + n;
+        const float* src = r.part + m * (size_t)N + n;
         float4 acc = *reinterpret_cast<const float4*>(src);
         for (int sp = 1; sp < split; ++sp) {
-            const float4 v = *reinterpret_cast<const float4*>(src + (size_t)sp * stride);
+            const float4 v = *reinterpret_cast<const float4*>(src + (size_t)sp * r.stride);
             acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
         }
-        *reinterpret_cast<uint2*>(C + m * (size_t)ldc + n) = make_uint2(ppack2(acc.x, acc.y), ppack2(acc.z, acc.w));
+        *reinterpret_cast<uint2*>(r.C + m * (size_t)r.ldc + n) = make_uint2(ppack2(acc.x, acc.y), ppack2(acc.z, acc.w));
     }
 }
 
@@ -960,13 +973,17 @@ static int launch_split_k(const PArgs& a, int split, hipStream_t s) {
         }
     int st = launch_persist<128, 128, PEPI_PARTIAL, 2>(b, s, false);
     if (st != LR_OK) return st;
+    RArgs r;
+    r.M = a.M;
+    size_t blocks = 1;
     for (int i = 0; i < a.nprob; ++i) {
-        const size_t total = (size_t)a.M * (size_t)(a.p[i].N / 4);
-        size_t blocks = (total + 255) / 256;
-        if (blocks > 2048) blocks = 2048;
-        hipLaunchKernelGGL(k_prefill_reduce, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)(a.sk_slots + off[i]), used[i],
-                           (size_t)a.M * (size_t)a.p[i].N, a.p[i].C, a.p[i].ldc, a.M, a.p[i].N);
+        r.p[i].part = a.sk_slots + off[i]; r.p[i].C = a.p[i].C; r.p[i].stride = (size_t)a.M * (size_t)a.p[i].N;
+        r.p[i].ldc = a.p[i].ldc; r.p[i].N = a.p[i].N; r.p[i].split = used[i];
+        const size_t b = ((size_t)a.M * (size_t)(a.p[i].N / 4) + 255) / 256;
+        if (b > blocks) blocks = b;
     }
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_prefill_reduce, dim3((unsigned)blocks, (unsigned)a.nprob), dim3(256), 0, s, r);
     return launch_status("prefill split-K reduction");
 }
 
