@@ -107,7 +107,7 @@ struct FusedMlpArgs { FusedCommon fc; DStageT<1> a, b, c, d; };
 // of each stage.  Return LR_ERR_UNSUPPORTED if the grid would not be fully resident.
 int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int cpl1, int cpl2,
                          int grid, int nw, bool t16, hipStream_t s);
-int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, int nw, bool t16, hipStream_t s);
+int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, bool t16, hipStream_t s);
 extern unsigned long long* g_trace_buffer;   // host copy of the trace pointer (NULL unless a trace build set it)
 bool decode_grid_is_resident(const void* kernel, int threads, int grid);   // occupancy of this very kernel x compute units >= grid
 int decode_resident_grid();   // workgroups that are certainly co-resident (number of CUs), cached; 0 when the device is shared

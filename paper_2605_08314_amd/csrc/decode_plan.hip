@@ -118,7 +118,9 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
     const int c1 = kCpl;
     // bf16 finalisation of t needs a slot of the workspace's partial-tile area for every tile of stage 1
     const size_t slot1 = (size_t)(M > 16 ? 32 : 16) * 16 * c1 * 4;
-    bool t16 = fused && use_t16(M, R / (16 * c1), 24);
+    // two-stage calls: from 25 rows on, and only when the rank-space rows are wide (measured at 25 / 28 / 32 rows: QKV, R = 1152,
+    // 16.0 / 16.3 / 16.6 us finalised against 16.0 / 16.6 / 17.5 with atomics; O projection, R = 384, 12.5 / 12.6 / 13.0 against 12.0 / 12.2 / 12.5)
+    bool t16 = fused && R >= 768 && use_t16(M, R / (16 * c1), 24);
     float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* t16base = (bf16_t*)L.staging;                       // [M, R] bf16 (fused launches only)
     SplitK sk[kMaxProb]; Final fin[kMaxProb];
@@ -228,9 +230,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
         const DStage* src[4] = {&sa, &sb, &sc, &sd};
         DStageT<1>* dst[4] = {&fa.a, &fa.b, &fa.c, &fa.d};
         for (int i = 0; i < 4; ++i) { dst[i]->p[0] = src[i]->p[0]; dst[i]->nprob = 1; dst[i]->M = (int)M; dst[i]->total_tiles = src[i]->total_tiles; }
-        // 17..32 rows: two 16-row MFMA blocks per wave; with 4 waves per workgroup the kernel has the registers for them
-        // (at 8 waves it spills), measured 45.6 against 47.8 us at 32 rows.  Up to 16 rows 8 waves are faster.
-        return decode_launch_fused_mlp(fa, ca, cc, cd, G, M > 16 ? 4 : 8, use16, s);
+        return decode_launch_fused_mlp(fa, ca, cc, cd, G, use16, s);
     }
     int st = fill_zero(t, (size_t)M * r_all * 4, s);
     if (st != LR_OK) return st;
