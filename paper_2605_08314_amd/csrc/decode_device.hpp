@@ -288,19 +288,14 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
         if (kb1 > (P.K >> 5)) kb1 = P.K >> 5;
         const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
         mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, kb0, kb1, wave, j, g, sync, late_err);
-    } else if constexpr (MB == 1) {
+    } else {
+        // gate/up: the blocks of both products as one request sequence, one set of weight and activation registers for both (two
+        // ranges one after the other, each with its own registers, leave the compiler twice the prefetch registers live at the
+        // border between the products: at two 16-row blocks per wave that spills from two blocks ahead on)
         const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
         const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
         mma_range2<MB, CPL, AF32, PF, NW>(acc[0], acc[NMAT - 1], P.W, P.W2, P.N, A, A2, P.lda, P.lda2, M, col, P.K >> 5, P.K2 >> 5,
                                           wave, j, g, sync, late_err);
-    } else {
-        // two 16-row blocks per wave: one product after the other (measured: the joint sequence is 1.2 us slower at 32 rows)
-        const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
-        const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
-        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, 0, P.K >> 5, wave, j, g, sync, late_err);
-        if constexpr (Sync::kCoherent) mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncCoherent(), late_err);
-        else if constexpr (Sync::kFused) mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSyncPlain(), late_err);
-        else mma_range<MB, CPL, AF32, PF, NW>(acc[NMAT - 1], P.W2, P.N, A2, P.lda2, M, col, 0, P.K2 >> 5, wave, j, g, NoSync(), late_err);
     }
 
     sync.before_epilogue();       // (the first tile of a call resolves the workspace's control block here: after its loads, before its first use)
@@ -749,8 +744,10 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     LR_STAMP(10);
 }
 
-// lowrank_packed_mlp: four stages, three barriers.
-template <int MB, int CPLA, int CPLC, int CPLD, int PF, int NW, bool T16>
+// lowrank_packed_mlp: four stages, three barriers.  PFA..PFD: weight blocks a wave requests ahead in each stage (the blocks
+// requested before a stage's barrier are what streams while the barrier is pending; the gate/up stage, with two accumulator
+// sets, has the fewest registers to spare).
+template <int MB, int CPLA, int CPLC, int CPLD, int PFA, int PFB, int PFC, int PFD, int NW, bool T16>
 __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
     constexpr int RA = red_float4s<MB, CPLA, EPI_ATOMIC, NW>(), RB = red_float4s<MB, 4, EPI_GATEUP, NW>();
     constexpr int RC = red_float4s<MB, CPLC, EPI_ATOMIC, NW>(), RD = red_float4s<MB, CPLD, EPI_STORE, NW>();
@@ -769,8 +766,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
     // A: t_gu += x U_gu
     bool resolved = false;
     for (int tile = blockIdx.x; tile < fa.a.total_tiles; tile += G) {
-        if (!resolved) decode_tile<MB, CPLA, false, EPI_ATOMIC, PF, NW>(fa.a.p[0], fa.a.M, tile, red, gate, shift, tcp);
-        else           decode_tile<MB, CPLA, false, EPI_ATOMIC, PF, NW>(fa.a.p[0], fa.a.M, tile, red, NoSync(), shift, tcp);
+        if (!resolved) decode_tile<MB, CPLA, false, EPI_ATOMIC, PFA, NW>(fa.a.p[0], fa.a.M, tile, red, gate, shift, tcp);
+        else           decode_tile<MB, CPLA, false, EPI_ATOMIC, PFA, NW>(fa.a.p[0], fa.a.M, tile, red, NoSync(), shift, tcp);
         resolved = true;
         __syncthreads();
     }
@@ -786,11 +783,11 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.b.total_tiles; tile += G) {
             if constexpr (T16) {
-                if (!waited) decode_tile<MB, 4, false, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, GridWaitPlain(gw), shift);
-                else         decode_tile<MB, 4, false, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncPlain(), shift);
+                if (!waited) decode_tile<MB, 4, false, EPI_GATEUP, PFB, NW>(fa.b.p[0], fa.b.M, tile, red, GridWaitPlain(gw), shift);
+                else         decode_tile<MB, 4, false, EPI_GATEUP, PFB, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncPlain(), shift);
             } else {
-                if (!waited) decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, GridWaitPlain(gw), shift);
-                else         decode_tile<MB, 4, true, EPI_GATEUP, PF, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncPlain(), shift);
+                if (!waited) decode_tile<MB, 4, true, EPI_GATEUP, PFB, NW>(fa.b.p[0], fa.b.M, tile, red, GridWaitPlain(gw), shift);
+                else         decode_tile<MB, 4, true, EPI_GATEUP, PFB, NW>(fa.b.p[0], fa.b.M, tile, red, NoSyncPlain(), shift);
             }
             if (!waited) fused_publish(fa.fc, cs);
             waited = true;
@@ -806,8 +803,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
         const GridWait gw = {cnt[1], G, &fa.fc.ctrl->error, fa.fc.spin_limit, &s_bad, 6, fa.fc.trace, false};
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.c.total_tiles; tile += G) {
-            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, GridWaitPlain(gw), shift, tcp);
-            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PF, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncPlain(), shift, tcp);
+            if (!waited) decode_tile<MB, CPLC, false, EPI_ATOMIC, PFC, NW>(fa.c.p[0], fa.c.M, tile, red, GridWaitPlain(gw), shift, tcp);
+            else         decode_tile<MB, CPLC, false, EPI_ATOMIC, PFC, NW>(fa.c.p[0], fa.c.M, tile, red, NoSyncPlain(), shift, tcp);
             waited = true;
             __syncthreads();
         }
@@ -821,11 +818,11 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused_mlp(FusedMlpArgs fa) {
         bool waited = false;
         for (int tile = blockIdx.x; tile < fa.d.total_tiles; tile += G) {
             if constexpr (T16) {
-                if (!waited) decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
-                else         decode_tile<MB, CPLD, false, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift, nullptr, &s_bad);
+                if (!waited) decode_tile<MB, CPLD, false, EPI_STORE, PFD, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+                else         decode_tile<MB, CPLD, false, EPI_STORE, PFD, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift, nullptr, &s_bad);
             } else {
-                if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
-                else         decode_tile<MB, CPLD, true, EPI_STORE, PF, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift, nullptr, &s_bad);
+                if (!waited) decode_tile<MB, CPLD, true, EPI_STORE, PFD, NW>(fa.d.p[0], fa.d.M, tile, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+                else         decode_tile<MB, CPLD, true, EPI_STORE, PFD, NW>(fa.d.p[0], fa.d.M, tile, red, NoSyncPlain(), shift, nullptr, &s_bad);
             }
             waited = true;
             __syncthreads();

@@ -3,14 +3,18 @@
 
 namespace lr {
 
-// Weight blocks a wave requests ahead (PF) and waves per workgroup (NW).  Up to 16 rows: three blocks, eight waves.  From 17
-// rows on (two 16-row blocks per wave) three blocks ahead no longer fit the registers of eight waves, and four waves leave
-// every SIMD with a single wave; one block ahead on eight waves still keeps 32 KB per compute unit in flight, twice what
-// saturates it (measured at 17 / 24 / 32 rows: 38.3 / 39.9 / 42.8 us against 42.5 / 43.9 / 45.4 with three blocks on four waves).
+// Weight blocks a wave requests ahead in each of the four stages, on eight waves per workgroup.  Up to 16 rows: three everywhere.
+// From 17 rows on (two 16-row blocks per wave) the gate/up stage, with its two accumulator sets, has registers for two blocks
+// ahead (three spill: 46 us at 32 rows); the other stages keep two or three, which covers a wave's whole share of their
+// tiles, so that those bytes stream while the barrier in front of the stage is pending.  Measured at 17 / 24 / 32 rows:
+// 34.6 / 36.5 / 39.3 us, against 37.5 / 39.3 / 41.7 with one block ahead in every stage and 42.5 / 43.9 / 45.4 with three
+// blocks on four waves (the most that configuration's registers allowed on eight).
 template <int MB, int CA, int CC, int CD>
 static int launch_mlp(const FusedMlpArgs& fa, int grid, bool t16, hipStream_t s) {
-    constexpr int PF = MB == 1 ? 3 : 1, NW = 8;
-    void (*kern)(FusedMlpArgs) = t16 ? k_decode_fused_mlp<MB, CA, CC, CD, PF, NW, true> : k_decode_fused_mlp<MB, CA, CC, CD, PF, NW, false>;
+    constexpr int NW = 8;
+    void (*kern)(FusedMlpArgs) = nullptr;
+    if constexpr (MB == 1) kern = t16 ? k_decode_fused_mlp<MB, CA, CC, CD, 3, 3, 3, 3, NW, true> : k_decode_fused_mlp<MB, CA, CC, CD, 3, 3, 3, 3, NW, false>;
+    else kern = t16 ? k_decode_fused_mlp<MB, CA, CC, CD, 2, 2, 3, 3, NW, true> : k_decode_fused_mlp<MB, CA, CC, CD, 2, 2, 3, 3, NW, false>;
     if (!decode_grid_is_resident((const void*)kern, 64 * NW, grid)) return LR_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), 0, s, fa);
     return launch_status("fused decode (packed MLP)");
