@@ -67,6 +67,24 @@ __device__ __forceinline__ void st_coherent_b64(void* p, uint2 v) {
     __hip_atomic_store(reinterpret_cast<uint64_t*>(p), (uint64_t)v.x | ((uint64_t)v.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// 16-byte device-coherent load, issued without a wait (the 64-bit atomic load above is the widest the compiler offers); the
+// caller passes all destinations of a batch to wait_loads_b128 before it reads any of them.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t ld_coherent_b128_issue(const void* p) {
+    u32x4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_b128(u32x4_t (&v)[N]) {
+    static_assert(N == 8 || N == 12, "batch size");
+    if constexpr (N == 8)
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]) :: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]),
+                                            "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]) :: "memory");
+}
+
 // COH: the rows were written earlier in this launch by other workgroups -> coherent loads.
 template <bool AF32, bool COH>
 __device__ __forceinline__ void load_a(AFrag<AF32>& f, const void* A, int lda, int m, int M, int k) {
@@ -427,21 +445,25 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
                         acc4[q][0] = acc4[q][1] = acc4[q][2] = acc4[q][3] = 0.f;
                     }
                     for (int sl0 = 0; sl0 < slices; sl0 += SB) {
-                        uint2 a[IT][SB], b[IT][SB];
+                        u32x4_t a[IT][SB];
 #pragma unroll
                         for (int q = 0; q < IT; ++q)
 #pragma unroll
                             for (int u = 0; u < SB; ++u) {
                                 const int sl = sl0 + u < slices ? sl0 + u : slices - 1;
-                                a[q][u] = ld_coherent_b64(src[q] + (size_t)sl * step); b[q][u] = ld_coherent_b64(src[q] + (size_t)sl * step + 2);
+                                a[q][u] = ld_coherent_b128_issue(src[q] + (size_t)sl * step);
                             }
+                        // (the loads above are issued by hand: the compiler does not count them, so the wait is written out and
+                        // takes every destination as an operand, which keeps their uses behind it)
+#pragma unroll
+                        for (int q = 0; q < IT; ++q) wait_loads_b128<SB>(a[q]);
 #pragma unroll
                         for (int q = 0; q < IT; ++q)
 #pragma unroll
                             for (int u = 0; u < SB; ++u)
                                 if (sl0 + u < slices) {
                                     acc4[q][0] += __uint_as_float(a[q][u].x); acc4[q][1] += __uint_as_float(a[q][u].y);
-                                    acc4[q][2] += __uint_as_float(b[q][u].x); acc4[q][3] += __uint_as_float(b[q][u].y);
+                                    acc4[q][2] += __uint_as_float(a[q][u].z); acc4[q][3] += __uint_as_float(a[q][u].w);
                                 }
                     }
 #pragma unroll
