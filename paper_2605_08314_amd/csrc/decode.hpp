@@ -66,8 +66,8 @@ constexpr size_t kDecPartBytes = (size_t)8 << 20;
 constexpr size_t kAccBytes = (size_t)4 << 20;
 constexpr size_t kFrontBytes = kHeaderBytes + kSkFlagBytes + kDecPartBytes + 2 * kAccBytes;
 // More token rows than this may use split-K partial tiles in slots + bf16 finalisation instead of atomics (the packed MLP
-// does from 9 rows on, the two-stage calls from 25: measured cross-over points).
-constexpr int kT16Rows = 8;
+// does from 8 rows on, the two-stage calls from 17 when their rank-space rows are wide: measured cross-over points).
+constexpr int kT16Rows = 7;
 inline size_t sk_tail_bytes(int64_t M) { return M > 32 ? kSkSlotBytes : 0; }
 
 struct WsLayout {

@@ -96,9 +96,9 @@ static int fused_grid(size_t factor_bytes) {
 }
 
 // More than `min_rows` token rows: split-K accumulators are finalised to bf16 once (see decode_tile) instead of
-// every consumer workgroup converting all of t.  Measured (atomics / finalisation, us): packed MLP 30.7 / 30.7 at 8 rows,
-// 32.7 / 31.7 at 12, 36.0 / 32.6 at 16, 52.8 / 44.7 at 32; QKV 11.7 / 13.2 at 12, 12.9 / 13.5 at 16, 15.1 / 15.0 at 24,
-// 16.2 / 15.9 at 32; O projection 9.4 / 10.0 at 12, 11.2 / 11.7 at 24, 12.1 / 12.6 at 32.
+// every consumer workgroup converting all of t.  Measured (atomics / finalisation, us): packed MLP 29.0 / 31.0 at 5 rows,
+// 29.2 / 31.3 at 6, 31.8 / 31.5 at 8; QKV (R = 1152) 12.0 / 13.3 at 9, 12.2 / 13.5 at 12, 13.3 / 13.9 at 16, 14.1 / 14.1 at 17,
+// 15.5 / 14.6 at 24, 17.5 / 16.6 at 32; O projection (R = 384) 12.0 / 12.5 at 25, 12.5 / 13.0 at 32.
 static bool use_t16(int64_t M, int64_t col_tiles, int min_rows) {
     return M > min_rows && M > kT16Rows && col_tiles <= kTileCounters;
 }
@@ -118,9 +118,8 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
     const int c1 = kCpl;
     // bf16 finalisation of t needs a slot of the workspace's partial-tile area for every tile of stage 1
     const size_t slot1 = (size_t)(M > 16 ? 32 : 16) * 16 * c1 * 4;
-    // two-stage calls: from 25 rows on, and only when the rank-space rows are wide (measured at 25 / 28 / 32 rows: QKV, R = 1152,
-    // 16.0 / 16.3 / 16.6 us finalised against 16.0 / 16.6 / 17.5 with atomics; O projection, R = 384, 12.5 / 12.6 / 13.0 against 12.0 / 12.2 / 12.5)
-    bool t16 = fused && R >= 768 && use_t16(M, R / (16 * c1), 24);
+    // two-stage calls: from 17 rows on, and only when the rank-space rows are wide
+    bool t16 = fused && R >= 768 && use_t16(M, R / (16 * c1), 16);
     float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* t16base = (bf16_t*)L.staging;                       // [M, R] bf16 (fused launches only)
     SplitK sk[kMaxProb]; Final fin[kMaxProb];
@@ -192,7 +191,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     const int G = fused_grid(((size_t)d * r_gu + (size_t)(r_g + r_u) * ffn + (size_t)ffn * r_d + (size_t)r_d * d) * 2);
     const bool fused = G > 0 && (size_t)M * r_all * 4 <= L.acc_bytes;
     // rank-space accumulators t[M, r_g + r_u + r_d] (fp32), the bf16 hidden rows h[M, ffn] and, for more
-    // than 8 token rows in a fused launch, the bf16 copy t16 of t
+    // than 7 token rows in a fused launch, the bf16 copy t16 of t
     float* t = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* h = fused ? (bf16_t*)L.staging : (bf16_t*)(L.staging + align256((size_t)M * r_all * 4));
     bf16_t* t16 = (bf16_t*)(L.staging + align256((size_t)M * ffn * 2));
@@ -200,7 +199,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     DStage sa, sb, sc, sd;
     const int ca = kCpl, cc = ca;   // both split-K stages share one tile width
     const size_t slot = (size_t)(M > 16 ? 32 : 16) * 16 * ca * 4;      // bytes of one partial tile
-    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca), 8);
+    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca), 7);
     SplitK a, c;
     for (int attempt = 0; attempt < 2; ++attempt) {
         int ctile = 0;
