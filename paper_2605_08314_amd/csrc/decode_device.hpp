@@ -721,7 +721,8 @@ __device__ __forceinline__ const DProb& find_prob(const DStageT<NP>& st, int til
 }
 
 // lowrank_linear / lowrank_qkv: t += x U (split-K, atomics)  ->  barrier  ->  y = t V (+bias, cache).
-template <int MB, int CPL1, int CPL2, int PF, int NP, int NW, bool T16>
+// PF1, PF2: weight blocks a wave requests ahead in either stage.
+template <int MB, int CPL1, int CPL2, int PF1, int PF2, int NP, int NW, bool T16>
 __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     constexpr int R1 = red_float4s<MB, CPL1, EPI_ATOMIC, NW>(), R2 = red_float4s<MB, CPL2, EPI_STORE, NW>();
     __shared__ float4 red[R1 > R2 ? R1 : R2];
@@ -737,8 +738,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     LR_STAMP(0);
     for (int tile = blockIdx.x; tile < fa.s1.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s1, tile);
-        if (!resolved) decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, gate, shift, tcp);
-        else           decode_tile<MB, CPL1, false, EPI_ATOMIC, PF, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift, tcp);
+        if (!resolved) decode_tile<MB, CPL1, false, EPI_ATOMIC, PF1, NW>(P, fa.s1.M, tile - P.tile_begin, red, gate, shift, tcp);
+        else           decode_tile<MB, CPL1, false, EPI_ATOMIC, PF1, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift, tcp);
         resolved = true;
         __syncthreads();
     }
@@ -752,11 +753,11 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     for (int tile = blockIdx.x; tile < fa.s2.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s2, tile);
         if constexpr (T16) {
-            if (!waited) decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
-            else         decode_tile<MB, CPL2, false, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
+            if (!waited) decode_tile<MB, CPL2, false, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+            else         decode_tile<MB, CPL2, false, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
         } else {
-            if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
-            else         decode_tile<MB, CPL2, true, EPI_STORE, PF, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
+            if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+            else         decode_tile<MB, CPL2, true, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
         }
         if (!waited) fused_publish(fa.fc, cs);
         waited = true;

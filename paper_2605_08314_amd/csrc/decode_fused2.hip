@@ -16,8 +16,8 @@ static int launch_f2(const FusedCommon& fc, const DStage& s1, const DStage& s2, 
     // 8.96 against 9.25 us at one row and 0.2-0.3 us less up to 16 rows, QKV unchanged; one block ahead loses 0.7 us on QKV),
     // from 17 rows on three
     if (nw != 8) { set_error("bad decode launch configuration"); return LR_ERR_UNSUPPORTED; }
-    constexpr int PF = MB == 1 ? 2 : 3;
-    void (*kern)(Fused2Args<NP>) = t16 ? k_decode_fused2<MB, C1, C2, PF, NP, 8, true> : k_decode_fused2<MB, C1, C2, PF, NP, 8, false>;
+    constexpr int PF = MB == 1 ? 2 : 3;      // the same in both stages (3 / 2, 2 / 3, 1 / 2, 2 / 1 measured: no better or worse)
+    void (*kern)(Fused2Args<NP>) = t16 ? k_decode_fused2<MB, C1, C2, PF, PF, NP, 8, true> : k_decode_fused2<MB, C1, C2, PF, PF, NP, 8, false>;
     if (!decode_grid_is_resident((const void*)kern, 64 * nw, grid)) return LR_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * nw), 0, s, fa);
     return launch_status("fused decode (two stages)");
