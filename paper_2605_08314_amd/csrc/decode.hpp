@@ -66,8 +66,8 @@ constexpr size_t kDecPartBytes = (size_t)8 << 20;
 constexpr size_t kAccBytes = (size_t)4 << 20;
 constexpr size_t kFrontBytes = kHeaderBytes + kSkFlagBytes + kDecPartBytes + 2 * kAccBytes;
 // More token rows than this may use split-K partial tiles in slots + bf16 finalisation instead of atomics (the packed MLP
-// does from 8 rows on, the two-stage calls from 17 when their rank-space rows are wide: measured cross-over points).
-constexpr int kT16Rows = 7;
+// does from 25 rows on: measured cross-over point; the two-stage calls keep the atomics).
+constexpr int kT16Rows = 24;
 inline size_t sk_tail_bytes(int64_t M) { return M > 32 ? kSkSlotBytes : 0; }
 
 struct WsLayout {
@@ -103,10 +103,9 @@ struct FusedCommon {
 template <int NP> struct Fused2Args { FusedCommon fc; DStageT<NP> s1, s2; };
 struct FusedMlpArgs { FusedCommon fc; DStageT<1> a, b, c, d; };
 
-// Fused launches (all stages in one kernel, `grid` resident workgroups of nw = 4 or 8 waves).  cpl* = columns per lane
+// Fused launches (all stages in one kernel, `grid` resident workgroups of 8 waves).  cpl* = columns per lane
 // of each stage.  Return LR_ERR_UNSUPPORTED if the grid would not be fully resident.
-int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int cpl1, int cpl2,
-                         int grid, int nw, bool t16, hipStream_t s);
+int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int cpl1, int cpl2, int grid, hipStream_t s);
 int decode_launch_fused_mlp(const FusedMlpArgs& fa, int cpl_a, int cpl_c, int cpl_d, int grid, bool t16, hipStream_t s);
 extern unsigned long long* g_trace_buffer;   // host copy of the trace pointer (NULL unless a trace build set it)
 bool decode_grid_is_resident(const void* kernel, int threads, int grid);   // occupancy of this very kernel x compute units >= grid

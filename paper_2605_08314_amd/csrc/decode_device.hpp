@@ -334,8 +334,29 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
     // a call whose device-wide wait gave up (or whose workspace carries an earlier failure) delivers NaN, never plausible numbers
     const bool nan_out = (EPI == EPI_STORE) && poison != nullptr && (*poison != 0u || late_err != 0u);
     float atomic_returns = 0.f;
+    // Split-K stage that accumulates with atomics: one atomic per thread on CONSECUTIVE floats of a row (a wave-level atomic then
+    // covers two whole 128-byte lines; in the operand layout a lane owns 4 columns of 4 rows, 16 bytes apart from its neighbours'),
+    // over the M valid rows only, by all waves.
+    const bool contiguous_atomics = EPI == EPI_ATOMIC && tcnt == nullptr;
+    if constexpr (EPI == EPI_ATOMIC) {
+        if (contiguous_atomics) {
+            float* const cbase = (float*)((char*)P.C + acc_shift) + n0;
+            for (int e = tid; e < M * NC; e += 64 * NW) {
+                const int m = e / NC, c = e - m * NC;
+                const int sl = (m >> 4) * 4 + (m & 3), ln = ((m & 15) >> 2) * 16 + c / CPL, b = c % CPL;
+                const float* r0 = reinterpret_cast<const float*>(&red[(sl * Q + (b >> 2)) * 64 + ln]) + (b & 3);
+                float sum = r0[0];
 #pragma unroll
-    for (int pidx = tid; pidx < 256 * MB; pidx += 64 * NW) {   // (mb, v, lane') triples
+                for (int w = 1; w < NW; ++w) sum += r0[(size_t)w * NSL * Q * 64 * 4];
+                // RETURNING atomics: a non-returning one is acknowledged as soon as the L2 has accepted it,
+                // before it is performed where other XCDs can see it; its return value only exists once it
+                // has been performed, and consuming the values below orders them before the arrival signal.
+                atomic_returns += unsafeAtomicAdd(cbase + (size_t)m * P.ldc + c, sum);
+            }
+        }
+    }
+#pragma unroll
+    for (int pidx = tid; pidx < (contiguous_atomics ? 0 : 256 * MB); pidx += 64 * NW) {   // (mb, v, lane') triples
         const int sl = pidx >> 6, ln = pidx & 63;
         const int mb = sl >> 2, v = sl & 3;
         const int m = 16 * mb + 4 * (ln >> 4) + v;
@@ -361,13 +382,6 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
                     float* ps = P.part + (size_t)(P.tile_begin + lt) * (16 * MB * NC) + (size_t)m * NC + (n - n0);
 #pragma unroll
                     for (int b = 0; b < CPL; b += 2) st_coherent_b64(ps + b, make_uint2(__float_as_uint(val[0][b]), __float_as_uint(val[0][b + 1])));
-                } else {
-                // RETURNING atomics: a non-returning one is acknowledged as soon as the L2 has accepted it,
-                // before it is performed where other XCDs can see it; its return value only exists once it
-                // has been performed, and consuming the values below orders them before the arrival signal.
-                float* c = (float*)((char*)P.C + acc_shift) + (size_t)m * P.ldc + n;
-#pragma unroll
-                for (int b = 0; b < CPL; ++b) atomic_returns += unsafeAtomicAdd(c + b, val[0][b]);
                 }
             } else if constexpr (EPI == EPI_STORE) {
                 if (nan_out) {
@@ -722,7 +736,7 @@ __device__ __forceinline__ const DProb& find_prob(const DStageT<NP>& st, int til
 
 // lowrank_linear / lowrank_qkv: t += x U (split-K, atomics)  ->  barrier  ->  y = t V (+bias, cache).
 // PF1, PF2: weight blocks a wave requests ahead in either stage.
-template <int MB, int CPL1, int CPL2, int PF1, int PF2, int NP, int NW, bool T16>
+template <int MB, int CPL1, int CPL2, int PF1, int PF2, int NP, int NW>
 __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     constexpr int R1 = red_float4s<MB, CPL1, EPI_ATOMIC, NW>(), R2 = red_float4s<MB, CPL2, EPI_STORE, NW>();
     __shared__ float4 red[R1 > R2 ? R1 : R2];
@@ -733,13 +747,13 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     CtrlSnap cs;
     size_t shift = 0;
     uint32_t* tcp = nullptr;
-    const CtrlGate gate = {fa.fc.ctrl, fa.fc.acc0, fa.fc.acc_bytes, &cl, &cs, &shift, &tcp, T16, &s_bad};
+    const CtrlGate gate = {fa.fc.ctrl, fa.fc.acc0, fa.fc.acc_bytes, &cl, &cs, &shift, &tcp, false, &s_bad};
     bool resolved = false;
     LR_STAMP(0);
     for (int tile = blockIdx.x; tile < fa.s1.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s1, tile);
-        if (!resolved) decode_tile<MB, CPL1, false, EPI_ATOMIC, PF1, NW>(P, fa.s1.M, tile - P.tile_begin, red, gate, shift, tcp);
-        else           decode_tile<MB, CPL1, false, EPI_ATOMIC, PF1, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift, tcp);
+        if (!resolved) decode_tile<MB, CPL1, false, EPI_ATOMIC, PF1, NW>(P, fa.s1.M, tile - P.tile_begin, red, gate, shift);
+        else           decode_tile<MB, CPL1, false, EPI_ATOMIC, PF1, NW>(P, fa.s1.M, tile - P.tile_begin, red, NoSync(), shift);
         resolved = true;
         __syncthreads();
     }
@@ -752,13 +766,8 @@ __global__ void __launch_bounds__(64 * NW) k_decode_fused2(Fused2Args<NP> fa) {
     bool waited = false;
     for (int tile = blockIdx.x; tile < fa.s2.total_tiles; tile += gridDim.x) {
         const DProb& P = find_prob<NP>(fa.s2, tile);
-        if constexpr (T16) {
-            if (!waited) decode_tile<MB, CPL2, false, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
-            else         decode_tile<MB, CPL2, false, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
-        } else {
-            if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
-            else         decode_tile<MB, CPL2, true, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
-        }
+        if (!waited) decode_tile<MB, CPL2, true, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, GridWaitPlain(gw), shift, nullptr, &s_bad);
+        else         decode_tile<MB, CPL2, true, EPI_STORE, PF2, NW>(P, fa.s2.M, tile - P.tile_begin, red, NoSyncPlain(), shift, nullptr, &s_bad);
         if (!waited) fused_publish(fa.fc, cs);
         waited = true;
         __syncthreads();

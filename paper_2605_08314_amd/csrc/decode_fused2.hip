@@ -6,7 +6,7 @@
 namespace lr {
 
 template <int MB, int C1, int C2, int NP>
-static int launch_f2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int grid, int nw, bool t16, hipStream_t s) {
+static int launch_f2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int grid, hipStream_t s) {
     Fused2Args<NP> fa;
     fa.fc = fc;
     for (int i = 0; i < NP; ++i) { fa.s1.p[i] = s1.p[i]; fa.s2.p[i] = s2.p[i]; }
@@ -14,30 +14,26 @@ static int launch_f2(const FusedCommon& fc, const DStage& s1, const DStage& s2, 
     fa.s2.nprob = s2.nprob; fa.s2.M = s2.M; fa.s2.total_tiles = s2.total_tiles;
     // eight waves; up to 16 rows each wave is two weight blocks ahead (measured against three in one run: the O projection
     // 8.96 against 9.25 us at one row and 0.2-0.3 us less up to 16 rows, QKV unchanged; one block ahead loses 0.7 us on QKV),
-    // from 17 rows on three
-    if (nw != 8) { set_error("bad decode launch configuration"); return LR_ERR_UNSUPPORTED; }
-    constexpr int PF = MB == 1 ? 2 : 3;      // the same in both stages (3 / 2, 2 / 3, 1 / 2, 2 / 1 measured: no better or worse)
-    void (*kern)(Fused2Args<NP>) = t16 ? k_decode_fused2<MB, C1, C2, PF, PF, NP, 8, true> : k_decode_fused2<MB, C1, C2, PF, PF, NP, 8, false>;
-    if (!decode_grid_is_resident((const void*)kern, 64 * nw, grid)) return LR_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * nw), 0, s, fa);
+    // from 17 rows on three; the same in both stages (3 / 2, 2 / 3, 1 / 2, 2 / 1 measured: no better or worse)
+    constexpr int PF = MB == 1 ? 2 : 3, NW = 8;
+    void (*kern)(Fused2Args<NP>) = k_decode_fused2<MB, C1, C2, PF, PF, NP, NW>;
+    if (!decode_grid_is_resident((const void*)kern, 64 * NW, grid)) return LR_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW), 0, s, fa);
     return launch_status("fused decode (two stages)");
 }
 
 template <int MB, int NP>
-static int launch_f2_cpl(const FusedCommon& fc, const DStage& s1, const DStage& s2, int c1, int c2, int grid, int nw, bool t16, hipStream_t s) {
-    if (c1 == 4 && c2 == 4) return launch_f2<MB, 4, 4, NP>(fc, s1, s2, grid, nw, t16, s);
+static int launch_f2_cpl(const FusedCommon& fc, const DStage& s1, const DStage& s2, int c1, int c2, int grid, hipStream_t s) {
+    if (c1 == 4 && c2 == 4) return launch_f2<MB, 4, 4, NP>(fc, s1, s2, grid, s);
     set_error("bad decode tile configuration");
     return LR_ERR_UNSUPPORTED;
 }
 
-int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int cpl1, int cpl2,
-                         int grid, int nw, bool t16, hipStream_t s) {
+int decode_launch_fused2(const FusedCommon& fc, const DStage& s1, const DStage& s2, int cpl1, int cpl2, int grid, hipStream_t s) {
     if (s1.M <= 0) return LR_OK;
     const bool small = s1.nprob <= 4 && s2.nprob <= 4;
-    if (s1.M <= 16) return small ? launch_f2_cpl<1, 4>(fc, s1, s2, cpl1, cpl2, grid, nw, t16, s)
-                                 : launch_f2_cpl<1, 8>(fc, s1, s2, cpl1, cpl2, grid, nw, t16, s);
-    return small ? launch_f2_cpl<2, 4>(fc, s1, s2, cpl1, cpl2, grid, nw, t16, s)
-                 : launch_f2_cpl<2, 8>(fc, s1, s2, cpl1, cpl2, grid, nw, t16, s);
+    if (s1.M <= 16) return small ? launch_f2_cpl<1, 4>(fc, s1, s2, cpl1, cpl2, grid, s) : launch_f2_cpl<1, 8>(fc, s1, s2, cpl1, cpl2, grid, s);
+    return small ? launch_f2_cpl<2, 4>(fc, s1, s2, cpl1, cpl2, grid, s) : launch_f2_cpl<2, 8>(fc, s1, s2, cpl1, cpl2, grid, s);
 }
 
 // Whether `grid` workgroups of this very kernel (threads per workgroup as launched, static LDS only) can be resident at the

@@ -96,9 +96,10 @@ static int fused_grid(size_t factor_bytes) {
 }
 
 // More than `min_rows` token rows: split-K accumulators are finalised to bf16 once (see decode_tile) instead of
-// every consumer workgroup converting all of t.  Measured (atomics / finalisation, us): packed MLP 29.0 / 31.0 at 5 rows,
-// 29.2 / 31.3 at 6, 31.8 / 31.5 at 8; QKV (R = 1152) 12.0 / 13.3 at 9, 12.2 / 13.5 at 12, 13.3 / 13.9 at 16, 14.1 / 14.1 at 17,
-// 15.5 / 14.6 at 24, 17.5 / 16.6 at 32; O projection (R = 384) 12.0 / 12.5 at 25, 12.5 / 13.0 at 32.
+// every consumer workgroup converting all of t.  Measured (atomics / finalisation, us): packed MLP 27.3 / 31.2 at 8 rows,
+// 30.1 / 32.6 at 16, 33.7 / 34.5 at 20, 34.9 / 34.95 at 24, 36.15 / 36.05 at 28, 37.2 / 36.9 at 32; QKV (R = 1152) 11.9 / 13.9
+// at 16, 12.8 / 14.4 at 20, 13.95 / 15.2 at 32; O projection (R = 384) 12.0 / 12.5 at 25, 12.5 / 13.0 at 32.  (Before the
+// atomics went out as one per thread on consecutive floats the cross-over points were 8 and 17 rows.)
 static bool use_t16(int64_t M, int64_t col_tiles, int min_rows) {
     return M > min_rows && M > kT16Rows && col_tiles <= kTileCounters;
 }
@@ -116,33 +117,26 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
     const int G = t_only ? 0 : fused_grid(factor_bytes);
     const bool fused = G > 0 && (size_t)M * R * 4 <= L.acc_bytes;
     const int c1 = kCpl;
-    // bf16 finalisation of t needs a slot of the workspace's partial-tile area for every tile of stage 1
-    const size_t slot1 = (size_t)(M > 16 ? 32 : 16) * 16 * c1 * 4;
-    // two-stage calls: from 17 rows on, and only when the rank-space rows are wide
-    bool t16 = fused && R >= 768 && use_t16(M, R / (16 * c1), 16);
+    // two-stage calls add their split-K partial sums with atomics at every row count (see the measurements above); the bf16
+    // finalisation is the packed MLP's, whose split-K stages are followed by the widest consumers
     float* tbase = fused ? (float*)L.acc0 : (float*)L.staging;
-    bf16_t* t16base = (bf16_t*)L.staging;                       // [M, R] bf16 (fused launches only)
     SplitK sk[kMaxProb]; Final fin[kMaxProb];
     DStage s1, s2;
-    for (int attempt = 0; attempt < 2; ++attempt) {
-        // the callers pass the column offset of each product inside t as the pointer value of C / T
-        for (int i = 0; i < nb; ++i) {
-            const size_t off = (size_t)(uintptr_t)sk_in[i].C;
-            sk[i] = sk_in[i]; sk[i].C = tbase + off; sk[i].T16 = t16 ? t16base + off : nullptr; sk[i].part = t16 ? L.dec_part : nullptr;
-        }
-        for (int i = 0; i < nf; ++i) {
-            const size_t off = (size_t)(uintptr_t)fin_in[i].T;
-            fin[i] = fin_in[i]; fin[i].T = t16 ? (const void*)(t16base + off) : (const void*)(tbase + off);
-        }
-        int ctile = 0;
-        build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : kUnfusedTiles, c1, &ctile);
-        if (!t16 || (size_t)s1.total_tiles * slot1 <= kDecPartBytes) break;
-        t16 = false;                                            // too many tiles for the area: accumulate with atomics instead
+    // the callers pass the column offset of each product inside t as the pointer value of C / T
+    for (int i = 0; i < nb; ++i) {
+        const size_t off = (size_t)(uintptr_t)sk_in[i].C;
+        sk[i] = sk_in[i]; sk[i].C = tbase + off; sk[i].T16 = nullptr; sk[i].part = nullptr;
     }
+    for (int i = 0; i < nf; ++i) {
+        const size_t off = (size_t)(uintptr_t)fin_in[i].T;
+        fin[i] = fin_in[i]; fin[i].T = (const void*)(tbase + off);
+    }
+    int ctile = 0;
+    build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : kUnfusedTiles, c1, &ctile);
     const int c2 = build_final(s2, fin, nf, R, M);
     if (fused) {
-        FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, t16 ? 0u : (uint32_t)(M * R), g_wait_limit, g_trace_buffer};   // t16: nothing is accumulated in place
-        return decode_launch_fused2(fc, s1, s2, c1, c2, G, 8, t16, s);
+        FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, (uint32_t)(M * R), g_wait_limit, g_trace_buffer};
+        return decode_launch_fused2(fc, s1, s2, c1, c2, G, s);
     }
     int st = fill_zero(tbase, (size_t)M * R * 4, s);
     if (st != LR_OK) return st;
@@ -191,7 +185,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     const int G = fused_grid(((size_t)d * r_gu + (size_t)(r_g + r_u) * ffn + (size_t)ffn * r_d + (size_t)r_d * d) * 2);
     const bool fused = G > 0 && (size_t)M * r_all * 4 <= L.acc_bytes;
     // rank-space accumulators t[M, r_g + r_u + r_d] (fp32), the bf16 hidden rows h[M, ffn] and, for more
-    // than 7 token rows in a fused launch, the bf16 copy t16 of t
+    // than 24 token rows in a fused launch, the bf16 copy t16 of t
     float* t = fused ? (float*)L.acc0 : (float*)L.staging;
     bf16_t* h = fused ? (bf16_t*)L.staging : (bf16_t*)(L.staging + align256((size_t)M * r_all * 4));
     bf16_t* t16 = (bf16_t*)(L.staging + align256((size_t)M * ffn * 2));
@@ -199,7 +193,7 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     DStage sa, sb, sc, sd;
     const int ca = kCpl, cc = ca;   // both split-K stages share one tile width
     const size_t slot = (size_t)(M > 16 ? 32 : 16) * 16 * ca * 4;      // bytes of one partial tile
-    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca), 7);
+    bool use16 = fused && use_t16(M, (r_gu + r_d) / (16 * ca), 24);
     SplitK a, c;
     for (int attempt = 0; attempt < 2; ++attempt) {
         int ctile = 0;

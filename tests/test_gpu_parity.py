@@ -65,13 +65,13 @@ def run_attention(G, oracle, w, phase):
     assert max_rel_err(G.host64(y), oracle.linear(t["a"].f64, t["U_o"].f64, t["V_o"].f64)) <= TOL[w.dtype]
 
 
-@pytest.mark.parametrize("Bsz", [1, 4, 16, 24, 25, 32])  # 24 / 25: atomics / bf16 finalisation of the split-K stage
+@pytest.mark.parametrize("Bsz", [1, 4, 16, 17, 25, 32])  # 16 / 17: one / two 16-row blocks per wave
 def test_config2_decode_attention(G, oracle, Bsz):
     run_attention(G, oracle, synth.attention_layer(Bsz, S_max=64), "decode")
 
 
 # ------------------------------------------------------------------ config 3: decode packed MLP
-@pytest.mark.parametrize("Bsz", [1, 8, 9, 32])        # 8 / 9: the last row count with atomics, the first with bf16 finalisation
+@pytest.mark.parametrize("Bsz", [1, 8, 16, 17, 24, 25, 32])   # 16 / 17: one / two 16-row blocks per wave; 24 / 25: the last row count with atomics, the first with bf16 finalisation
 def test_config3_decode_packed_mlp(G, oracle, Bsz):
     w = synth.mlp_layer(Bsz)
     out = G.run_mlp(w, "decode")
