@@ -71,6 +71,16 @@ class Layer:
         self.U_gu = w(d, 2 * r_mlp, d)
         self.V_g, self.V_u = w(r_mlp, ffn, r_mlp), w(r_mlp, ffn, r_mlp)
         self.U_d, self.V_d = w(ffn, r_mlp, ffn), w(r_mlp, d, r_mlp)
+        self.P = None
+
+    def make_panels(self, torch, B):
+        """The decode copy of every factor: 64-column panels (lowrank_pack_panels), made once at load time."""
+        def pk(W):
+            P = torch.empty_like(W)
+            B.lowrank_pack_panels(W, P)
+            return P
+        self.P = dict(U=[pk(u) for u in self.U], V=[pk(v) for v in self.V], U_gu=pk(self.U_gu), V_g=pk(self.V_g),
+                      V_u=pk(self.V_u), U_d=pk(self.U_d), V_d=pk(self.V_d))
 
 
 def capture(torch, fn):
@@ -286,6 +296,7 @@ def main():
     ap.add_argument("--batch", type=int, default=1, help="token rows B of the timed decode step")
     ap.add_argument("--prefill-rows", type=int, default=8192)
     ap.add_argument("--eager", action="store_true", help="plain launches instead of HIP-graph replay")
+    ap.add_argument("--row-major", action="store_true", help="decode on the row-major factors instead of their prepacked 64-column panels")
     ap.add_argument("--quick", action="store_true", help="skip the per-batch table, prefill and the CPU baseline")
     ap.add_argument("--prefill-only", action="store_true", help="only the prefill layer (for profiling): one JSON line with its numbers")
     ap.add_argument("--attention-only", action="store_true", help="only the decode-attention rows (for profiling)")
@@ -316,6 +327,11 @@ def main():
                           "prefill_factorized_attention": run_prefill_factorized_attention(torch, B, gen, args.prefill_rows)}))
         return
     layers = [Layer(torch, gen=gen) for _ in range(L)]
+    panels = not args.row_major
+    if panels:
+        for ly in layers:
+            ly.make_panels(torch, B)
+        torch.cuda.synchronize()
     S_max = 64
     bf = torch.bfloat16
 
@@ -331,19 +347,27 @@ def main():
         ws_mlp = B.new_workspace(B.LR_OP_PACKED_MLP, Bn, D, 3 * R_MLP, FFN, B.LR_BF16, "decode")
         return dict(x=x, a=a, q=q, k=k, v=v, o=o, m=m, kc=kc, vc=vc, pos=pos, ws_qkv=ws_qkv, ws_o=ws_o, ws_mlp=ws_mlp)
 
-    def op_qkv(buf, li):
-        ly = layers[li]
-        B.lowrank_qkv(buf["x"], ly.U[:3], ly.V[:3], None, [buf["q"], buf["k"], buf["v"]],
-                      dict(k_cache=buf["kc"][li], v_cache=buf["vc"][li], pos=buf["pos"], tokens_per_seq=1, k_index=1, v_index=2),
-                      "decode", buf["ws_qkv"])
+    def make_ops(pan):
+        def fac(ly):
+            return ly.P if pan else dict(U=ly.U, V=ly.V, U_gu=ly.U_gu, V_g=ly.V_g, V_u=ly.V_u, U_d=ly.U_d, V_d=ly.V_d)
 
-    def op_o(buf, li):
-        ly = layers[li]
-        B.lowrank_linear(buf["a"], ly.U[3], ly.V[3], None, buf["o"], "decode", buf["ws_o"])
+        def op_qkv(buf, li):
+            f = fac(layers[li])
+            B.lowrank_qkv(buf["x"], f["U"][:3], f["V"][:3], None, [buf["q"], buf["k"], buf["v"]],
+                          dict(k_cache=buf["kc"][li], v_cache=buf["vc"][li], pos=buf["pos"], tokens_per_seq=1, k_index=1, v_index=2),
+                          "decode", buf["ws_qkv"], panels=pan)
 
-    def op_mlp(buf, li):
-        ly = layers[li]
-        B.lowrank_packed_mlp(buf["x"], ly.U_gu, ly.V_g, ly.V_u, ly.U_d, ly.V_d, None, None, None, buf["m"], "decode", buf["ws_mlp"])
+        def op_o(buf, li):
+            f = fac(layers[li])
+            B.lowrank_linear(buf["a"], f["U"][3], f["V"][3], None, buf["o"], "decode", buf["ws_o"], panels=pan)
+
+        def op_mlp(buf, li):
+            f = fac(layers[li])
+            B.lowrank_packed_mlp(buf["x"], f["U_gu"], f["V_g"], f["V_u"], f["U_d"], f["V_d"], None, None, None, buf["m"], "decode",
+                                 buf["ws_mlp"], panels=pan)
+        return op_qkv, op_o, op_mlp
+
+    op_qkv, op_o, op_mlp = make_ops(panels)
 
     def sweep(buf, ops):
         for li in range(L):
@@ -414,7 +438,9 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"decode step, {L} LLaMA-7B-shaped low-rank layers (QKV+cache r=384, O r=384, packed MLP r=768), B={Bt}",
-                   "layers": L, "batch": Bt, "d": D, "ffn": FFN, "r_attn": R_ATTN, "r_mlp": R_MLP},
+                   "layers": L, "batch": Bt, "d": D, "ffn": FFN, "r_attn": R_ATTN, "r_mlp": R_MLP,
+                   "factor_layout": ("64-column panels, prepacked once with lowrank_pack_panels (decode); row-major (prefill)" if panels
+                                     else "row-major")},
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "tokens_per_s": round(Bt / (ms_per_step * 1e-3), 1),
         "host_wall_ms_per_step": round(wall_ms, 4), "launch": "eager" if args.eager else "hip_graph_replay",
@@ -422,21 +448,25 @@ def main():
     }
 
     if not args.quick:
-        # ---- per-entry-point decode table
-        table = {}
-        for Bn in sorted({1, 4, 8, 16, 32}):
-            b2 = buf if Bn == Bt else decode_buffers(Bn)
-            row = {}
-            for name, op, nbytes in (("qkv", op_qkv, attn_bytes(Bn)[0]), ("o", op_o, attn_bytes(Bn)[1]), ("mlp", op_mlp, mlp_bytes(Bn))):
-                fn = (lambda: sweep(b2, (op,))) if args.eager else capture(torch, lambda: sweep(b2, (op,)))
-                ms = time_region(torch, fn, 10, 2) / L
-                row[name] = {"us": round(ms * 1e3, 2), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
-            for k in ("ws_qkv", "ws_o", "ws_mlp"):
-                B.lowrank_workspace_status(b2[k])
-            table[f"B{Bn}"] = row
-            if b2 is not buf:
-                del b2
-        out["decode_ops"] = table
+        # ---- per-entry-point decode table (in the factor layout of the step; on the row-major factors for two batch sizes as well)
+        def ops_table(batches, ops):
+            table = {}
+            for Bn in batches:
+                b2 = buf if Bn == Bt else decode_buffers(Bn)
+                row = {}
+                for name, op, nbytes in (("qkv", ops[0], attn_bytes(Bn)[0]), ("o", ops[1], attn_bytes(Bn)[1]), ("mlp", ops[2], mlp_bytes(Bn))):
+                    fn = (lambda: sweep(b2, (op,))) if args.eager else capture(torch, lambda: sweep(b2, (op,)))
+                    ms = time_region(torch, fn, 10, 2) / L
+                    row[name] = {"us": round(ms * 1e3, 2), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+                for k in ("ws_qkv", "ws_o", "ws_mlp"):
+                    B.lowrank_workspace_status(b2[k])
+                table[f"B{Bn}"] = row
+                if b2 is not buf:
+                    del b2
+            return table
+        out["decode_ops"] = ops_table(sorted({1, 4, 8, 16, 32}), (op_qkv, op_o, op_mlp))
+        if panels:
+            out["decode_ops_row_major"] = ops_table([1, 32], make_ops(False))
 
         out["prefill"] = run_prefill(torch, B, gen, layers[0], args.prefill_rows)
         out["prefill_ranks"] = run_prefill_ranks(torch, B, gen)

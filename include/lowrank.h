@@ -64,7 +64,14 @@
 extern "C" {
 #endif
 
-typedef enum { LR_F32 = 0, LR_BF16 = 1 } lr_dtype;
+/*
+ * Element type of a call.  LR_BF16_PANELS is bf16 whose FACTOR operands (every U, V, U_gu, V_g, V_u, U_d, V_d argument) are
+ * stored as 64-column panels (lowrank_pack_panels) instead of row-major; x, biases, outputs and caches are as with LR_BF16.
+ * Only lowrank_linear, lowrank_qkv and lowrank_packed_mlp accept it, and only where they run the decode kernels (decode
+ * phase, up to 32 rows, fast-path shapes, aligned operands); any other such call returns LR_ERR_UNSUPPORTED and launches
+ * nothing.  Results are those of the same call on row-major factors, bit for bit in the same launch shape.
+ */
+typedef enum { LR_F32 = 0, LR_BF16 = 1, LR_BF16_PANELS = 2 } lr_dtype;
 
 /* Phase of serving (paper: "phase-specific kernels").  AUTO picks DECODE when M <= 32. */
 typedef enum { LR_PHASE_DECODE = 0, LR_PHASE_PREFILL = 1, LR_PHASE_AUTO = 2 } lr_phase;
@@ -229,6 +236,18 @@ int lowrank_pack_concat(const void *const *U_list, const int64_t *r_list, int n,
                         int dtype, void *U_packed, void *stream);
 
 /*
+ * Offline prepack for decode (Section 3.1, first paragraph: factors are "loaded into a common native factorized
+ * representation"; the layout is the library's choice): re-lay a row-major bf16 factor W[K, N], N a multiple of 64, as
+ * N / 64 panels of 64 columns,
+ *     W_panels[((n / 64) * K + k) * 64 + n % 64] = W[k * N + n],
+ * so that the 64-column tile a decode workgroup streams is one contiguous run instead of K row segments of 128 bytes
+ * N * 2 bytes apart.  Panels of a concatenation are the concatenation of the panels (ranks that are multiples of 64).
+ * dtype must be LR_BF16; W and W_panels are distinct 16-byte aligned device buffers of K * N elements.  Pure data
+ * movement: bit-exact.  A server keeps this copy for decode beside the row-major one that prefill reads.
+ */
+int lowrank_pack_panels(const void *W, int64_t K, int64_t N, void *W_panels, int dtype, void *stream);
+
+/*
  * Workspace size in bytes (pure host function, no GPU needed).  Meaning of the size arguments:
  *   LR_OP_LINEAR      d_in, r_total = r,                 d_out
  *   LR_OP_QKV         d_in, r_total = sum of r[i],       d_out = sum of d_out[i]
@@ -269,7 +288,8 @@ int lowrank_configure(int option, int64_t value);
 
 /*
  * Name of the kernel family the dispatcher picks for a call of this shape, e.g.
- * "decode_mfma", "prefill_mfma", "generic" (pure host function; static storage).
+ * "decode_mfma", "prefill_mfma", "generic" (pure host function; static storage); with LR_BF16_PANELS
+ * "decode_mfma" or "unsupported".
  * `aligned` is nonzero when every pointer of the call is 16-byte aligned.
  */
 const char *lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, int64_t d_out,

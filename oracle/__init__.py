@@ -167,6 +167,20 @@ def pack_concat(U_list: Sequence[np.ndarray]) -> np.ndarray:
     return packed
 
 
+def pack_panels(W: np.ndarray) -> np.ndarray:
+    """Decode prepack (a pure re-layout, Section 3.1 first paragraph leaves the native layout to the runtime): the row-major
+    factor W[K, N], N a multiple of 64, as N / 64 panels of 64 columns; returns an array [N / 64, K, 64] whose flat order is
+    the layout: panel p holds columns 64 p .. 64 p + 63 of every row, rows in order.  Bit-exact for any dtype."""
+    W = np.ascontiguousarray(W)
+    K, N = W.shape
+    assert N % 64 == 0
+    out = np.empty((N // 64, K, 64), dtype=W.dtype)
+    for p in range(N // 64):
+        for k in range(K):
+            out[p, k, :] = W[k, 64 * p:64 * p + 64]
+    return out
+
+
 def rope(x, positions, H: int, E: int, base: float = 10000.0) -> np.ndarray:
     """Rotary position embedding, rotate-half pairing (i, i + E/2), angle p * base**(-2i/E);
     x [rows, H*E], positions [rows] (Section 4: RoPE on q and k)."""

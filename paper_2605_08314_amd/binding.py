@@ -22,7 +22,7 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_08314_amd.build`")
 _lib = ctypes.CDLL(LIB_PATH)
 
-LR_F32, LR_BF16 = 0, 1
+LR_F32, LR_BF16, LR_BF16_PANELS = 0, 1, 2
 LR_PHASE_DECODE, LR_PHASE_PREFILL, LR_PHASE_AUTO = 0, 1, 2
 LR_OP_LINEAR, LR_OP_QKV, LR_OP_PACKED_MLP, LR_OP_DECODE_ATTENTION = 0, 1, 2, 3
 PHASES = {"decode": LR_PHASE_DECODE, "prefill": LR_PHASE_PREFILL, "auto": LR_PHASE_AUTO}
@@ -56,6 +56,8 @@ _lib.lowrank_rank_project.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp
 _lib.lowrank_rank_project.restype = _int
 _lib.lowrank_pack_concat.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_i64), _int, _i64, _int, _vp, _vp]
 _lib.lowrank_pack_concat.restype = _int
+_lib.lowrank_pack_panels.argtypes = [_vp, _i64, _i64, _vp, _int, _vp]
+_lib.lowrank_pack_panels.restype = _int
 _lib.lowrank_workspace_bytes.argtypes = [_int, _i64, _i64, _i64, _i64, _int, _int]
 _lib.lowrank_workspace_bytes.restype = _sz
 _lib.lowrank_workspace_init.argtypes = [_vp, _sz, _vp]
@@ -83,7 +85,14 @@ def _check(st: int) -> None:
         raise LowrankError(st)
 
 
-def _dtype_code(t: torch.Tensor) -> int:
+def _dtype_code(t: torch.Tensor, panels: bool = False) -> int:
+    if panels:
+        assert t.dtype == torch.bfloat16, "panel layout is bf16 only"
+        return LR_BF16_PANELS
+    return _plain_dtype_code(t)
+
+
+def _plain_dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return LR_F32
     if t.dtype == torch.bfloat16:
@@ -162,12 +171,13 @@ def new_workspace(op: int, M: int, d_in: int, r_total: int, d_out: int, dtype: i
     return ws
 
 
-def lowrank_linear(x, U, V, bias, y, phase, workspace, stream=None) -> None:
+def lowrank_linear(x, U, V, bias, y, phase, workspace, stream=None, panels: bool = False) -> None:
+    """panels=True: U and V hold 64-column panels (lowrank_pack_panels); their shapes are still (d_in, r), (r, d_out)."""
     M, d_in = x.shape
     r, d_out = V.shape
     assert U.shape == (d_in, r) and y.shape == (M, d_out)
     _check(_lib.lowrank_linear(_ptr(x), _ptr(U), _ptr(V), _ptr(bias), _ptr(y), M, d_in, r, d_out,
-                               _dtype_code(x), _phase(phase), _ptr(workspace),
+                               _dtype_code(x, panels), _phase(phase), _ptr(workspace),
                                workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
@@ -180,7 +190,7 @@ def lowrank_linear_noalloc(x, U, V, bias, y, stream=None) -> None:
 
 
 def lowrank_qkv(x, U: Sequence, V: Sequence, bias: Optional[Sequence], out: Sequence, kv: Optional[dict],
-                phase, workspace, stream=None) -> None:
+                phase, workspace, stream=None, panels: bool = False) -> None:
     """``kv``: dict(k_cache, v_cache, pos, tokens_per_seq, k_index, v_index) or None; the caches
     are [B, S_max, n_heads, head_dim] tensors, pos an int32 device tensor [B]."""
     n = len(U)
@@ -196,11 +206,12 @@ def lowrank_qkv(x, U: Sequence, V: Sequence, bias: Optional[Sequence], out: Sequ
         kvs = ctypes.pointer(lr_kv_target(_ptr(kc), _ptr(kv["v_cache"]), _ptr(kv["pos"]), B, S_max, H, E,
                                           kv["tokens_per_seq"], kv["k_index"], kv["v_index"]))
     _check(_lib.lowrank_qkv(_ptr(x), arr(U), arr(V), None if bias is None else arr(bias), arr(out), rs, ns, n,
-                            M, d_in, kvs, _dtype_code(x), _phase(phase), _ptr(workspace),
+                            M, d_in, kvs, _dtype_code(x, panels), _phase(phase), _ptr(workspace),
                             workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
-def lowrank_packed_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, phase, workspace, stream=None) -> None:
+def lowrank_packed_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, phase, workspace, stream=None,
+                       panels: bool = False) -> None:
     M, d = x.shape
     r_g, ffn = V_g.shape
     r_u = V_u.shape[0]
@@ -209,7 +220,7 @@ def lowrank_packed_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, phase, w
     assert U_d.shape == (ffn, r_d) and V_d.shape == (r_d, d) and out.shape == (M, d)
     _check(_lib.lowrank_packed_mlp(_ptr(x), _ptr(U_gu), _ptr(V_g), _ptr(V_u), _ptr(U_d), _ptr(V_d),
                                    _ptr(b_g), _ptr(b_u), _ptr(b_d), _ptr(out), M, d, ffn, r_g, r_u, r_d,
-                                   _dtype_code(x), _phase(phase), _ptr(workspace),
+                                   _dtype_code(x, panels), _phase(phase), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
@@ -253,6 +264,13 @@ def lowrank_rank_project(x, U, t, workspace, stream=None) -> None:
     assert U.shape == (d_in, r) and t.shape == (M, r)
     _check(_lib.lowrank_rank_project(_ptr(x), _ptr(U), _ptr(t), M, d_in, r, _dtype_code(x), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def lowrank_pack_panels(W: torch.Tensor, W_panels: torch.Tensor, stream=None) -> None:
+    """W [K, N] row-major bf16 -> W_panels (same shape and size): N / 64 panels of 64 columns, each [K, 64] contiguous."""
+    K, N = W.shape
+    assert W_panels.numel() == W.numel() and W_panels.dtype == W.dtype
+    _check(_lib.lowrank_pack_panels(_ptr(W), K, N, _ptr(W_panels), _plain_dtype_code(W), _stream(stream)))
 
 
 def lowrank_pack_concat(U_list: Sequence[torch.Tensor], U_packed: torch.Tensor, stream=None) -> None:

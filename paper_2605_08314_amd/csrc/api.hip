@@ -28,8 +28,8 @@ int launch_status(const char* what) {
 
 static inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
-static int check_common(int dtype, int phase, int64_t M, void* ws, size_t ws_bytes, size_t need) {
-    if (dtype != LR_F32 && dtype != LR_BF16) { set_error("unknown dtype %d", dtype); return LR_ERR_DTYPE; }
+static int check_common(int dtype, int phase, int64_t M, void* ws, size_t ws_bytes, size_t need, bool allow_panels = false) {
+    if (dtype != LR_F32 && dtype != LR_BF16 && !(allow_panels && dtype == LR_BF16_PANELS)) { set_error("unknown dtype %d", dtype); return LR_ERR_DTYPE; }
     if (phase != LR_PHASE_DECODE && phase != LR_PHASE_PREFILL && phase != LR_PHASE_AUTO) {
         set_error("unknown phase %d", phase); return LR_ERR_PHASE; }
     if (M > 0) {
@@ -46,6 +46,14 @@ static inline int resolve_phase(int phase, int64_t M) {
 }
 
 enum Plan { PLAN_GENERIC = 0, PLAN_DECODE = 1, PLAN_PREFILL = 2 };
+
+// LR_BF16_PANELS: bf16 data whose factor operands are stored as 64-column panels; only the decode kernels read that layout.
+static int panels_need_decode(Plan plan) {
+    if (plan == PLAN_DECODE) return LR_OK;
+    set_error("factors in panel layout (LR_BF16_PANELS) are read by the decode kernels only: up to 32 rows, decode phase, "
+              "16-byte aligned operands, every d_in and r a multiple of 32, every r and d_out a multiple of 64");
+    return LR_ERR_UNSUPPORTED;
+}
 static const char* const kPlanNames[] = {"generic", "decode_mfma", "prefill_mfma"};
 
 
@@ -105,7 +113,7 @@ size_t lowrank_workspace_bytes(int op, int64_t M, int64_t d_in, int64_t r_total,
                                int dtype, int phase) {
     if (op < LR_OP_LINEAR || op > LR_OP_DECODE_ATTENTION) return 0;
     if (M < 0 || d_in < 0 || r_total < 0 || d_out < 0) return 0;
-    if (dtype != LR_F32 && dtype != LR_BF16) return 0;
+    if (dtype != LR_F32 && dtype != LR_BF16 && dtype != LR_BF16_PANELS) return 0;
     if (phase < LR_PHASE_DECODE || phase > LR_PHASE_AUTO) return 0;
     if (op == LR_OP_DECODE_ATTENTION) return (r_total > 0 && d_in % r_total == 0) ? attn_ws_bytes(M, d_in, r_total) : 0;
     return ws_bytes_for(op, M, r_total, d_out);
@@ -161,6 +169,10 @@ const char* lowrank_plan_name(int op, int64_t M, int64_t d_in, int64_t r_total, 
         dec = decode_shape_ok(M, d_in, r_total) && decode_shape_ok(M, r_total, d_out);
         pre = prefill_shape_ok(M, d_in, r_total) && prefill_shape_ok(M, r_total, d_out);
     }
+    if (dtype == LR_BF16_PANELS) {      // panels run the decode kernels or nothing
+        const Plan p = pick_plan(LR_BF16, phase, M, dec, pre, aligned != 0);
+        return p == PLAN_DECODE ? kPlanNames[PLAN_DECODE] : "unsupported";
+    }
     return kPlanNames[pick_plan(dtype, phase, M, dec, pre, aligned != 0)];
 }
 
@@ -177,15 +189,18 @@ int lowrank_linear(const void* x, const void* U, const void* V, const void* bias
                    int64_t M, int64_t d_in, int64_t r, int64_t d_out, int dtype, int phase,
                    void* workspace, size_t workspace_bytes, void* stream) {
     if (M < 0 || d_in < 0 || r < 0 || d_out < 0) { set_error("negative size"); return LR_ERR_SHAPE; }
-    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_LINEAR, M, r, d_out));
+    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_LINEAR, M, r, d_out), true);
     if (st != LR_OK) return st;
+    const bool panels = dtype == LR_BF16_PANELS;
+    if (panels) dtype = LR_BF16;
     if (M == 0 || d_out == 0) return LR_OK;
     if (!y || (d_in > 0 && !x) || (r > 0 && d_in > 0 && !U) || (r > 0 && !V)) { set_error("NULL operand"); return LR_ERR_NULL; }
     hipStream_t s = (hipStream_t)stream;
     const bool al = aligned16(x) && aligned16(U) && aligned16(V) && aligned16(y) && aligned16(bias);
     const Plan plan = pick_plan(dtype, phase, M, decode_shape_ok(M, d_in, r) && decode_shape_ok(M, r, d_out),
                                 prefill_shape_ok(M, d_in, r) && prefill_shape_ok(M, r, d_out), al);
-    if (plan == PLAN_DECODE) return decode_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
+    if (panels && (st = panels_need_decode(plan)) != LR_OK) return st;
+    if (plan == PLAN_DECODE) return decode_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s, panels);
     if (plan == PLAN_PREFILL) return prefill_linear(x, U, V, bias, y, M, d_in, r, d_out, workspace, workspace_bytes, s);
     float* t = (float*)ws_layout(workspace, workspace_bytes, M).staging;
     CacheDst none = {nullptr, nullptr, 0, 1};
@@ -231,8 +246,10 @@ int lowrank_qkv(const void* x, const void* const* U, const void* const* V, const
         if (r[i] < 0 || d_out[i] < 0) { set_error("negative size in projection %d", i); return LR_ERR_SHAPE; }
         r_sum += r[i]; n_sum += d_out[i];
     }
-    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_QKV, M, r_sum, n_sum));
+    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_QKV, M, r_sum, n_sum), true);
     if (st != LR_OK) return st;
+    const bool panels = dtype == LR_BF16_PANELS;
+    if (panels) dtype = LR_BF16;
     // shared bases: projection i reuses the stage-1 product of the first j < i with U[j] == U[i]
     int base_of[8]; int64_t t_off[8]; int64_t R = 0;
     for (int i = 0; i < n_proj; ++i) {
@@ -275,8 +292,9 @@ int lowrank_qkv(const void* x, const void* const* U, const void* const* V, const
     }
     if (kv) al = al && aligned16(kv->k_cache) && aligned16(kv->v_cache);
     const Plan plan = pick_plan(dtype, phase, M, dec, pre, al);
+    if (panels && (st = panels_need_decode(plan)) != LR_OK) return st;
     if (plan == PLAN_DECODE)
-        return decode_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, workspace_bytes, s);
+        return decode_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, workspace_bytes, s, panels);
     if (plan == PLAN_PREFILL)
         return prefill_qkv(x, U, V, bias, out, r, d_out, n_proj, base_of, t_off, R, M, d_in, kv, workspace, workspace_bytes, s);
     float* t = (float*)ws_layout(workspace, workspace_bytes, M).staging;
@@ -302,8 +320,10 @@ int lowrank_packed_mlp(const void* x, const void* U_gu, const void* V_g, const v
                        int dtype, int phase, void* workspace, size_t workspace_bytes, void* stream) {
     if (M < 0 || d < 0 || ffn < 0 || r_g < 0 || r_u < 0 || r_d < 0) { set_error("negative size"); return LR_ERR_SHAPE; }
     const int64_t r_total = r_g + r_u + r_d;
-    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_PACKED_MLP, M, r_total, ffn));
+    int st = check_common(dtype, phase, M, workspace, workspace_bytes, ws_bytes_for(LR_OP_PACKED_MLP, M, r_total, ffn), true);
     if (st != LR_OK) return st;
+    const bool panels = dtype == LR_BF16_PANELS;
+    if (panels) dtype = LR_BF16;
     if (M == 0 || d == 0) return LR_OK;
     if (!x || !out) { set_error("NULL operand"); return LR_ERR_NULL; }
     if ((r_g + r_u > 0 && !U_gu) || (r_g > 0 && ffn > 0 && !V_g) || (r_u > 0 && ffn > 0 && !V_u) ||
@@ -316,8 +336,9 @@ int lowrank_packed_mlp(const void* x, const void* U_gu, const void* V_g, const v
     const bool pre = prefill_shape_ok(M, d, r_g + r_u) && prefill_shape_ok(M, r_g, ffn) && prefill_shape_ok(M, r_u, ffn) &&
                      prefill_shape_ok(M, ffn, r_d) && prefill_shape_ok(M, r_d, d);
     const Plan plan = pick_plan(dtype, phase, M, dec, pre, al);
+    if (panels && (st = panels_need_decode(plan)) != LR_OK) return st;
     if (plan == PLAN_DECODE)
-        return decode_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, workspace_bytes, s);
+        return decode_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, workspace_bytes, s, panels);
     if (plan == PLAN_PREFILL)
         return prefill_mlp(x, U_gu, V_g, V_u, U_d, V_d, b_g, b_u, b_d, out, M, d, ffn, r_g, r_u, r_d, workspace, workspace_bytes, s);
     char* base = ws_layout(workspace, workspace_bytes, M).staging;
@@ -420,6 +441,16 @@ int lowrank_pack_concat(const void* const* U_list, const int64_t* r_list, int n,
     }
     if (R * d_in > 0 && !U_packed) { set_error("U_packed is NULL"); return LR_ERR_NULL; }
     return generic_pack_concat(U_list, r_list, n, d_in, dtype == LR_F32 ? 4 : 2, U_packed, (hipStream_t)stream);
+}
+
+int lowrank_pack_panels(const void* W, int64_t K, int64_t N, void* W_panels, int dtype, void* stream) {
+    if (dtype != LR_BF16) { set_error("lowrank_pack_panels: bf16 only"); return LR_ERR_DTYPE; }
+    if (K < 0 || N < 0 || (N % 64) != 0) { set_error("lowrank_pack_panels: N must be a multiple of 64 (and sizes non-negative)"); return LR_ERR_SHAPE; }
+    if (K * N == 0) return LR_OK;
+    if (!W || !W_panels) { set_error("NULL operand"); return LR_ERR_NULL; }
+    if (W == W_panels) { set_error("lowrank_pack_panels: not in place"); return LR_ERR_SHAPE; }
+    if (!aligned16(W) || !aligned16(W_panels)) { set_error("lowrank_pack_panels: operands must be 16-byte aligned"); return LR_ERR_ALIGN; }
+    return generic_pack_panels(W, K, N, W_panels, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -22,6 +22,8 @@ struct DProb {
     int tiles_n;      // column tiles (N / NC)
     int KS;           // rows of W per tile (multiple of 32); tiles along K = ceil(K / KS)
     int tile_begin;   // first tile index of this product inside the stage
+    int wstride;      // elements between consecutive rows of W (and W2) as stored: N, or 64 for the panel layout
+    int64_t wtile, wtile2;   // elements between consecutive column tiles of W / W2: the tile width, or K * 64 (K2 * 64) for panels
 };
 
 template <int NP> struct DStageT { DProb p[NP]; int nprob, M, total_tiles; };
@@ -119,20 +121,21 @@ int ws_prepare(void* ws, hipStream_t s);   // enqueue the check-and-prepare laun
 // accumulators) rather than bf16, epi = EPI_*.
 int decode_launch_stage(const DStage& st, int cpl, bool a_f32, int epi, hipStream_t s);
 
-// Host planners (decode_plan.hip).  They assume decode_shape_ok(...) held for every product.
+// Host planners (decode_plan.hip).  They assume decode_shape_ok(...) held for every product.  panels: the factors are stored
+// as 64-column panels (lowrank_pack_panels) instead of row-major.
 bool decode_shape_ok(int64_t M, int64_t K, int64_t N);
 int decode_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
-                  int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s);
+                  int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s, bool panels);
 // the same with nothing but an fp32 area t[M * r] as scratch: one launch per stage
 int decode_linear_scratch(const void* x, const void* U, const void* V, const void* bias, void* y,
                           int64_t M, int64_t d_in, int64_t r, int64_t d_out, float* t, hipStream_t s);
 int decode_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
                void* const* out, const int64_t* r, const int64_t* d_out, int n_proj, const int* base_of,
                const int64_t* t_off, int64_t R, int64_t M, int64_t d_in, const lr_kv_target* kv,
-               void* ws, size_t ws_bytes, hipStream_t s);
+               void* ws, size_t ws_bytes, hipStream_t s, bool panels);
 int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u, const void* U_d,
                const void* V_d, const void* b_g, const void* b_u, const void* b_d, void* out,
                int64_t M, int64_t d, int64_t ffn, int64_t r_g, int64_t r_u, int64_t r_d,
-               void* ws, size_t ws_bytes, hipStream_t s);
+               void* ws, size_t ws_bytes, hipStream_t s, bool panels);
 
 }  // namespace lr

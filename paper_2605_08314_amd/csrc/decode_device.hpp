@@ -305,14 +305,14 @@ __device__ __forceinline__ void decode_tile(const DProb& P, int M, int lt, float
         int kb1 = kb0 + (P.KS >> 5);
         if (kb1 > (P.K >> 5)) kb1 = P.K >> 5;
         const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
-        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W, P.N, A, P.lda, M, col, kb0, kb1, wave, j, g, sync, late_err);
+        mma_range<MB, CPL, AF32, PF, NW>(acc[0], P.W + (size_t)tn * P.wtile, P.wstride, A, P.lda, M, CPL * j, kb0, kb1, wave, j, g, sync, late_err);
     } else {
         // gate/up: the blocks of both products as one request sequence, one set of weight and activation registers for both (two
         // ranges one after the other, each with its own registers, leave the compiler twice the prefetch registers live at the
         // border between the products: at two 16-row blocks per wave that spills from two blocks ahead on)
         const void* A = AF32 ? (const void*)((const char*)P.A + acc_shift) : P.A;
         const void* A2 = AF32 ? (const void*)((const char*)P.A2 + acc_shift) : P.A2;
-        mma_range2<MB, CPL, AF32, PF, NW>(acc[0], acc[NMAT - 1], P.W, P.W2, P.N, A, A2, P.lda, P.lda2, M, col, P.K >> 5, P.K2 >> 5,
+        mma_range2<MB, CPL, AF32, PF, NW>(acc[0], acc[NMAT - 1], P.W + (size_t)tn * P.wtile, P.W2 + (size_t)tn * P.wtile2, P.wstride, A, A2, P.lda, P.lda2, M, CPL * j, P.K >> 5, P.K2 >> 5,
                                           wave, j, g, sync, late_err);
     }
 

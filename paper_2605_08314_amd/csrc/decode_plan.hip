@@ -40,13 +40,22 @@ static int pick_ks(int64_t K, int64_t tiles_n_total, int64_t M, int64_t want_til
 }
 
 static void zero_prob(DProb& p) { memset(&p, 0, sizeof(p)); p.T = 1; }
+// Where the factor of every product of a stage lives: row-major [K, N] as stored in a checkpoint, or 64-column panels
+// (lowrank_pack_panels: element (k, n) at ((n / 64) * K + k) * 64 + n % 64), in which a tile is one contiguous run.
+static void set_wlayout(DStage& st, int nc, bool panels) {
+    for (int i = 0; i < st.nprob; ++i) {
+        DProb& p = st.p[i];
+        if (panels) { p.wstride = nc; p.wtile = (int64_t)p.K * nc; p.wtile2 = (int64_t)p.K2 * nc; }
+        else { p.wstride = p.N; p.wtile = nc; p.wtile2 = nc; }
+    }
+}
 
 struct SplitK { const void* W; int64_t N; float* C; bf16_t* T16; float* part; };   // T16: bf16 copy of C made by the last K-slice (or NULL)
 struct Final { const void* T; int64_t r; const void* V; int64_t N; const void* bias; void* Y; CacheDst cd; };   // T: fp32 or bf16 rank-space rows
 
 // t[M, ldc] += A[M, K] * W_i[K, N_i] for several weight matrices sharing A, split along K.
 static void build_splitk(DStage& st, const void* A, int64_t lda, int64_t M, int64_t K, const SplitK* items, int n,
-                         int64_t ldc, int64_t want_tiles, int cpl, int* ctile_next) {
+                         int64_t ldc, int64_t want_tiles, int cpl, int* ctile_next, bool panels) {
     st.nprob = n; st.M = (int)M;
     int64_t n_all = 0;
     for (int i = 0; i < n; ++i) n_all += items[i].N;
@@ -62,10 +71,11 @@ static void build_splitk(DStage& st, const void* A, int64_t lda, int64_t M, int6
         tile += p.tiles_n * tk;
     }
     st.total_tiles = tile;
+    set_wlayout(st, nc, panels);
 }
 
 // y_i[M, N_i] = t_i[M, r_i] * V_i[r_i, N_i] + bias_i: full K per tile, the epilogue writes bf16.
-static int build_final(DStage& st, const Final* items, int n, int64_t ldt, int64_t M) {
+static int build_final(DStage& st, const Final* items, int n, int64_t ldt, int64_t M, bool panels) {
     st.nprob = n; st.M = (int)M;
     const int cpl = 4;   // 64-column tiles: full K per tile, so narrow tiles are the only source of parallelism
     const int nc = 16 * cpl;
@@ -79,6 +89,7 @@ static int build_final(DStage& st, const Final* items, int n, int64_t ldt, int64
         tile += p.tiles_n;
     }
     st.total_tiles = tile;
+    set_wlayout(st, nc, panels);
     return cpl;
 }
 
@@ -107,7 +118,7 @@ static bool use_t16(int64_t M, int64_t col_tiles, int min_rows) {
 // t_only != NULL: the call has no workspace, only this fp32 area of M * R floats for the rank-space rows; it then runs as
 // one launch per stage (no control block, no cross-workgroup waits).
 static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* sk_in, int nb, const Final* fin_in,
-                         int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s, float* t_only = nullptr) {
+                         int nf, int64_t R, void* ws, size_t ws_bytes, hipStream_t s, bool panels, float* t_only = nullptr) {
     WsLayout L;
     if (t_only) { memset(&L, 0, sizeof(L)); L.staging = (char*)t_only; }
     else L = ws_layout(ws, ws_bytes, M);
@@ -132,8 +143,8 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
         fin[i] = fin_in[i]; fin[i].T = (const void*)(tbase + off);
     }
     int ctile = 0;
-    build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : kUnfusedTiles, c1, &ctile);
-    const int c2 = build_final(s2, fin, nf, R, M);
+    build_splitk(s1, x, d_in, M, d_in, sk, nb, R, fused ? G : kUnfusedTiles, c1, &ctile, panels);
+    const int c2 = build_final(s2, fin, nf, R, M, panels);
     if (fused) {
         FusedCommon fc = {L.ctrl, L.acc0, L.acc_bytes, (uint32_t)(M * R), g_wait_limit, g_trace_buffer};
         return decode_launch_fused2(fc, s1, s2, c1, c2, G, s);
@@ -146,23 +157,23 @@ static int run_two_stage(const void* x, int64_t d_in, int64_t M, const SplitK* s
 }
 
 int decode_linear(const void* x, const void* U, const void* V, const void* bias, void* y,
-                  int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s) {
+                  int64_t M, int64_t d_in, int64_t r, int64_t d_out, void* ws, size_t ws_bytes, hipStream_t s, bool panels) {
     SplitK sk = {U, r, (float*)0, nullptr, nullptr};
     Final f = {(const void*)0, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
-    return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, ws, ws_bytes, s);
+    return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, ws, ws_bytes, s, panels);
 }
 
 int decode_linear_scratch(const void* x, const void* U, const void* V, const void* bias, void* y,
                           int64_t M, int64_t d_in, int64_t r, int64_t d_out, float* t, hipStream_t s) {
     SplitK sk = {U, r, (float*)0, nullptr, nullptr};
     Final f = {(const void*)0, r, V, d_out, bias, y, {nullptr, nullptr, 0, 1}};
-    return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, nullptr, 0, s, t);
+    return run_two_stage(x, d_in, M, &sk, 1, &f, 1, r, nullptr, 0, s, false, t);
 }
 
 int decode_qkv(const void* x, const void* const* U, const void* const* V, const void* const* bias,
                void* const* out, const int64_t* r, const int64_t* d_out, int n_proj, const int* base_of,
                const int64_t* t_off, int64_t R, int64_t M, int64_t d_in, const lr_kv_target* kv,
-               void* ws, size_t ws_bytes, hipStream_t s) {
+               void* ws, size_t ws_bytes, hipStream_t s, bool panels) {
     SplitK sk[kMaxProb]; int nb = 0;
     for (int i = 0; i < n_proj; ++i)
         if (base_of[i] == i) sk[nb++] = SplitK{U[i], r[i], (float*)(uintptr_t)t_off[i], nullptr, nullptr};
@@ -173,13 +184,13 @@ int decode_qkv(const void* x, const void* const* U, const void* const* V, const 
         if (kv && i == kv->v_index) cd = CacheDst{kv->v_cache, kv->pos, kv->S_max, kv->tokens_per_seq};
         f[i] = Final{(const void*)(uintptr_t)t_off[i], r[i], V[i], d_out[i], bias ? bias[i] : nullptr, out[i], cd};
     }
-    return run_two_stage(x, d_in, M, sk, nb, f, n_proj, R, ws, ws_bytes, s);
+    return run_two_stage(x, d_in, M, sk, nb, f, n_proj, R, ws, ws_bytes, s, panels);
 }
 
 int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u, const void* U_d,
                const void* V_d, const void* b_g, const void* b_u, const void* b_d, void* out,
                int64_t M, int64_t d, int64_t ffn, int64_t r_g, int64_t r_u, int64_t r_d,
-               void* ws, size_t ws_bytes, hipStream_t s) {
+               void* ws, size_t ws_bytes, hipStream_t s, bool panels) {
     const int64_t r_gu = r_g + r_u, r_all = r_gu + r_d;
     const WsLayout L = ws_layout(ws, ws_bytes, M);
     const int G = fused_grid(((size_t)d * r_gu + (size_t)(r_g + r_u) * ffn + (size_t)ffn * r_d + (size_t)r_d * d) * 2);
@@ -198,9 +209,9 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
     for (int attempt = 0; attempt < 2; ++attempt) {
         int ctile = 0;
         a = SplitK{U_gu, r_gu, t, use16 ? t16 : nullptr, use16 ? L.dec_part : nullptr};
-        build_splitk(sa, x, d, M, d, &a, 1, r_all, want, ca, &ctile);
+        build_splitk(sa, x, d, M, d, &a, 1, r_all, want, ca, &ctile, panels);
         c = SplitK{U_d, r_d, t + r_gu, use16 ? t16 + r_gu : nullptr, use16 ? L.dec_part : nullptr};   // the two split-K stages take turns in the same slots
-        build_splitk(sc, h, ffn, M, ffn, &c, 1, r_all, want, cc, &ctile);
+        build_splitk(sc, h, ffn, M, ffn, &c, 1, r_all, want, cc, &ctile, panels);
         const int most = sa.total_tiles > sc.total_tiles ? sa.total_tiles : sc.total_tiles;
         if (!use16 || (size_t)most * slot <= kDecPartBytes) break;
         use16 = false;
@@ -214,9 +225,10 @@ int decode_mlp(const void* x, const void* U_gu, const void* V_g, const void* V_u
         p.N = (int)ffn; p.Y = h; p.bias = (const bf16_t*)b_g; p.bias2 = (const bf16_t*)b_u;
         p.tiles_n = (int)(ffn / 64); p.KS = (int)r_g; p.tile_begin = 0;
         sb.total_tiles = p.tiles_n;
+        set_wlayout(sb, 64, panels);
     }
     Final f = {use16 ? (const void*)(t16 + r_gu) : (const void*)(t + r_gu), r_d, V_d, d, b_d, out, {nullptr, nullptr, 0, 1}};
-    const int cd = build_final(sd, &f, 1, r_all, M);
+    const int cd = build_final(sd, &f, 1, r_all, M, panels);
     if (fused) {
         FusedMlpArgs fa;
         fa.fc = FusedCommon{L.ctrl, L.acc0, L.acc_bytes, use16 ? 0u : (uint32_t)(M * r_all), g_wait_limit, g_trace_buffer};

@@ -143,6 +143,26 @@ int generic_pack_concat(const void* const* U_list, const int64_t* r_list, int n,
     return LR_OK;
 }
 
+// 64-column panels of a row-major bf16 matrix [K, N]: element (k, n) goes to ((n / 64) * K + k) * 64 + n % 64.
+// One thread per 16-byte unit (8 columns); a panel row is 128 bytes, so reads and writes are whole 128-byte segments.
+__global__ void __launch_bounds__(256) k_pack_panels(const uint4* __restrict__ W, uint4* __restrict__ P, int64_t K, int64_t N) {
+    const int64_t units_per_row = N / 8, total = K * units_per_row;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t k = i / units_per_row, u = i - k * units_per_row;      // unit u of row k
+        const int64_t panel = u >> 3, pu = u & 7;
+        P[(panel * K + k) * 8 + pu] = W[i];
+    }
+}
+
+int generic_pack_panels(const void* W, int64_t K, int64_t N, void* panels, hipStream_t s) {
+    const int64_t total = K * (N / 8);
+    if (total <= 0) return LR_OK;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(k_pack_panels, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)W, (uint4*)panels, K, N);
+    return launch_status("pack panels");
+}
+
 // Check-and-prepare for launches that keep state in the workspace without being a fused decode kernel (the prefill product
 // that shares K, lowrank_workspace_init): ONE small launch.  When the control block carries the ready word (every call but
 // the first) the single workgroup leaves at once; otherwise it zeroes the control block, the flags and the accumulator areas

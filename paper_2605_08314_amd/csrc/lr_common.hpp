@@ -82,6 +82,7 @@ int generic_gateup(const float* t, int64_t ldt, const void* V_g, const void* V_u
                    int dtype, hipStream_t s);
 int generic_pack_concat(const void* const* U_list, const int64_t* r_list, int n, int64_t d_in,
                         int elem_bytes, void* packed, hipStream_t s);
+int generic_pack_panels(const void* W, int64_t K, int64_t N, void* panels, hipStream_t s);   // bf16 [K, N] -> 64-column panels
 int fill_zero(void* p, size_t bytes, hipStream_t s);
 int generic_round(const float* src, void* dst, int64_t n, int dtype, hipStream_t s);
 

@@ -63,6 +63,12 @@ def test_validation_errors_without_launch(B):
     assert call(wsb=16) == -6 and b"workspace" in lib.lowrank_last_error()
     assert call(y=None) == -1
     assert call(M=0, ws=None) == 0          # empty batch: legal no-op, needs no workspace
+    assert call(dtype=2) == -8 and b"panel" in lib.lowrank_last_error()    # panel layout outside the decode fast path (r = 8)
+    lib.lowrank_pack_panels.argtypes = B._lib.lowrank_pack_panels.argtypes
+    assert lib.lowrank_pack_panels(fake, 8, 100, 0x2000, 1, None) == -2      # N not a multiple of 64
+    assert lib.lowrank_pack_panels(fake, 8, 128, 0x2000, 0, None) == -3      # bf16 only
+    assert lib.lowrank_pack_panels(fake, 8, 128, fake, 1, None) == -2        # not in place
+    assert lib.lowrank_pack_panels(None, 0, 128, None, 1, None) == 0         # empty: no-op
 
 
 def test_plan_names(B):
@@ -74,6 +80,12 @@ def test_plan_names(B):
     assert B.lowrank_plan_name(B.LR_OP_QKV, 3, 37, 5, 19, B.LR_BF16, "decode") == "generic"
     assert B.lowrank_plan_name(B.LR_OP_LINEAR, 16, 512, 128, 512, B.LR_F32, "decode") == "generic"
     assert B.lowrank_plan_name(B.LR_OP_LINEAR, 16, 4096, 384, 4096, B.LR_BF16, "decode", aligned=False) == "generic"
+    # factors stored as 64-column panels: the decode kernels or nothing
+    assert B.lowrank_plan_name(B.LR_OP_LINEAR, 16, 4096, 384, 4096, B.LR_BF16_PANELS, "decode") == "decode_mfma"
+    assert B.lowrank_plan_name(B.LR_OP_LINEAR, 512, 4096, 384, 4096, B.LR_BF16_PANELS, "auto") == "unsupported"
+    assert B.lowrank_plan_name(B.LR_OP_LINEAR, 3, 37, 5, 19, B.LR_BF16_PANELS, "decode") == "unsupported"
+    assert B.lowrank_workspace_bytes(B.LR_OP_LINEAR, 16, 4096, 384, 4096, B.LR_BF16_PANELS, "decode") == \
+        B.lowrank_workspace_bytes(B.LR_OP_LINEAR, 16, 4096, 384, 4096, B.LR_BF16, "decode")
 
 
 def _dry_lib(B):

@@ -145,6 +145,30 @@ def test_pack_concat_bitwise_and_order(oracle):
         assert np.array_equal(packed[:, 0:3], Us[0]) and np.array_equal(packed[:, 4:10], Us[2])
 
 
+def test_pack_panels_layout(oracle):
+    # hand example: K = 2, N = 128, W[k, n] = 128 k + n.  Panel 0 is columns 0..63 of row 0, then of row 1; panel 1 columns 64..127.
+    W = np.arange(256, dtype=np.uint16).reshape(2, 128)
+    flat = oracle.pack_panels(W).reshape(-1)
+    want = list(range(0, 64)) + list(range(128, 192)) + list(range(64, 128)) + list(range(192, 256))
+    assert flat.tolist() == want
+    # the flat index of element (k, n) as the boundary states it, element by element on a ragged-looking shape
+    rng = np.random.default_rng(181)
+    K, N = 7, 192
+    W = rng.integers(0, 60000, size=(K, N)).astype(np.uint16)
+    flat = oracle.pack_panels(W).reshape(-1)
+    for k in range(K):
+        for n in range(N):
+            assert flat[((n // 64) * K + k) * 64 + n % 64] == W[k, n]
+    # undoing it is a concatenation of the panels along the columns; panels of a concatenation are the panels side by side
+    for dt in (np.uint16, np.float32):
+        A = rng.integers(0, 60000, size=(5, 128)).astype(dt)
+        Bm = rng.integers(0, 60000, size=(5, 64)).astype(dt)
+        P = oracle.pack_panels(A)
+        assert P.dtype == dt and np.array_equal(np.concatenate(list(P), axis=1), A)
+        assert np.array_equal(oracle.pack_panels(np.concatenate([A, Bm], axis=1)),
+                              np.concatenate([oracle.pack_panels(A), oracle.pack_panels(Bm)], axis=0))
+
+
 def test_packed_projection_equals_separate_bitwise(oracle):
     rng = np.random.default_rng(19)
     x = rng.standard_normal((4, 33))
