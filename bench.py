@@ -33,7 +33,7 @@ D, FFN, R_ATTN, R_MLP, HEADS, HEAD_DIM = 4096, 11008, 384, 768, 32, 128
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per decode-MLP launch at B=1 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
 # same counters read for the 256 MiB copy of --pmc-mode (profiles/decode_mlp_pmc_traffic.txt).
-MLP_TRAFFIC_BYTES = 70921940
+MLP_TRAFFIC_BYTES = 70926778
 TRAFFIC_SOURCE = "profiles/decode_mlp_pmc_traffic.txt (rocprofv3 --pmc run of `bench.py --pmc-mode`; not measured in this run)"
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
